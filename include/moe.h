@@ -1,0 +1,178 @@
+/*
+ * libmoe -- one-GPU forward pass of a Mixture-of-Experts layer for AMD gfx950.
+ *
+ * The layer is the one the paper states in Sec. 2.1: a gating network multiplies
+ * every token embedding by its trainable matrix and sends the token to its top-k
+ * experts; each expert is a two-layer fully connected network; the output is the
+ * gate-weighted sum of the selected experts' outputs.  Between gate and experts
+ * the tokens are packed into an expert-major buffer, and unpacked afterwards:
+ * these are the payloads of the two all-to-all exchanges of expert parallelism
+ * (end of Sec. 2.1, Sec. 2.2), here built for one GPU's share with no network.
+ * moe_layer_chunked splits the token stream into equal parts and overlaps the
+ * packing of part i+1 with the expert computation of part i, the one-GPU analogue
+ * of the paper's all-to-all micro-ops pipelined with the expert FFN (Sec. 4.2,
+ * "Pipelining micro-ops"; Sec. 6.1).
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers unless a comment says "host".
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Calls only enqueue work; they never synchronise the host with the device,
+ *     never allocate or free device memory, and never copy results to the host.
+ *   - The caller owns every buffer, including `workspace`
+ *     (size from moe_workspace_bytes), and keeps it alive until the enqueued
+ *     work has finished.  Buffers must be 16-byte aligned and must not overlap.
+ *   - Matrices are row-major and dense.  Row lengths in bytes (d_model, d_ff
+ *     times the element size) must be multiples of 16.
+ *   - Return value: MOE_OK, or an error code with nothing enqueued;
+ *     moe_last_error() then describes the problem (thread-local string).
+ *     No C++ exception crosses this boundary.
+ *   - Inputs are assumed finite.
+ *
+ * Element types.  `dtype` is the storage type of x, Wg, W1, W2, xe.  Gate logits,
+ * softmax and gate weights are fp32.  The expert outputs ye and the layer output y
+ * are fp32 for both dtypes: an expert's output stays in the accumulator's
+ * precision until the weighted sum over the selected experts is complete.
+ */
+#ifndef MOE_H
+#define MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_EINVAL = 1,       /* null / misaligned pointer, inconsistent sizes */
+    MOE_EUNSUPPORTED = 2, /* a size or option outside what the kernels handle */
+    MOE_EWORKSPACE = 3,   /* reserved */
+    MOE_EHIP = 4          /* a HIP runtime call failed */
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+
+typedef enum {
+    MOE_ACT_GELU_ERF = 0, /* 0.5 v (1 + erf(v / sqrt 2)) */
+    MOE_ACT_GELU_TANH = 1,
+    MOE_ACT_RELU = 2,     /* the activation the paper names in Sec. 2.1 */
+    MOE_ACT_IDENTITY = 3
+} moe_act;
+
+/* Shape of one layer.  T tokens, E experts (1..64), k experts per token
+ * (1..min(E,8)), capacity = slots per expert (>= 1; pass T for "never drop"). */
+typedef struct {
+    int32_t T;
+    int32_t d_model;
+    int32_t E;
+    int32_t d_ff;
+    int32_t k;
+    int32_t capacity;
+    int32_t dtype;       /* moe_dtype */
+    int32_t act;         /* moe_act */
+    int32_t renorm_topk; /* 0: gate weight = softmax probability;
+                            1: divided by the sum over the k selected experts */
+} moe_shape;
+
+/* Host, pure.  ceil(cf * k * T / E) evaluated in double; cf <= 0 returns T. */
+int64_t moe_capacity(int32_t T, int32_t E, int32_t k, double cf);
+
+/* Host, pure.  Upper bound of kept assignments: min(T*k, E*capacity).
+ * xe, ye and src_of must hold this many rows / entries. */
+int64_t moe_max_rows(const moe_shape *s);
+
+/* Host, pure.  Bytes of `workspace` the calls below need for this shape and up to
+ * n_chunks chunks (the same buffer serves all of them).  0 on an invalid shape. */
+size_t moe_workspace_bytes(const moe_shape *s, int32_t n_chunks);
+
+/* Host.  Description of the last error on the calling thread ("" if none). */
+const char *moe_last_error(void);
+
+/* Host, pure.  Bytes of each packed weight buffer (W1p and W2p have equal size). */
+size_t moe_packed_weight_bytes(const moe_shape *s);
+
+/* One-time re-layout of the expert weights for the FFN kernels (like loading a
+ * checkpoint; not part of the timed path).
+ *   W1 [E, d_model, d_ff], W2 [E, d_ff, d_model]: canonical layout, `dtype`.
+ *   W1p, W2p: moe_packed_weight_bytes each.
+ * MOE_BF16: W1p = bf16 [E, d_ff, d_model] (each expert transposed so that the
+ * contraction index is contiguous); W2p = fp16 [E, d_model, d_ff].  The hidden
+ * activations are held in fp16 (three more mantissa bits than bf16 at the same
+ * matrix-core rate); every bf16 weight of magnitude in [2^-17, 65504] converts
+ * exactly, smaller ones round to the nearest multiple of 2^-24.
+ * MOE_F32: plain copies. */
+moe_status moe_pack_weights(const moe_shape *s, const void *W1, const void *W2,
+                            void *W1p, void *W2p, void *stream);
+
+/* Host, pure.  Bytes of the packed gate matrix. */
+size_t moe_packed_gate_bytes(const moe_shape *s);
+
+/* One-time re-layout of the gating network's matrix (Sec. 2.1: "its trainable
+ * matrix"): Wg [d_model, E] in `dtype` -> Wgp fp32 [d_model, EP], EP = E rounded
+ * up to a power of two, zero padded.  Every bf16 value converts exactly. */
+moe_status moe_pack_gate(const moe_shape *s, const void *Wg, float *Wgp, void *stream);
+
+/* Gate (Sec. 2.1).  z[t,e] = sum_i x[t,i] Wg[i,e] accumulated in fp32 in
+ * ascending i with fused multiply-adds, then + gate_bias.  The k experts of a
+ * token are its k largest logits (in order of decreasing logit, ties: lower index
+ * first); gate[t,j] = softmax(z[t,:])[expert j] (optionally renormalised).
+ *   x [T, d_model] in `dtype`; Wgp from moe_pack_gate.
+ *   gate_bias: NULL, or fp32 [E] (bias_token_stride 0) or [T,E] (stride E).
+ *   expert_idx int32 [T*k], gate fp32 [T*k]: outputs. */
+moe_status moe_route(const moe_shape *s, const void *x, const float *Wgp,
+                     const float *gate_bias, int32_t bias_token_stride,
+                     int32_t *expert_idx, float *gate, void *stream);
+
+/* Dispatch = pack for the first all-to-all (end of Sec. 2.1).  Assignment
+ * i = t*k + j is kept iff fewer than `capacity` assignments with a smaller i chose
+ * the same expert; kept assignments of expert e fill slots
+ * [offsets[e], offsets[e+1]) in ascending i.
+ *   counts int32 [E]: assignments per expert before the capacity bound.
+ *   offsets int32 [E+1]: exclusive scan of min(counts, capacity).
+ *   slot_of int32 [T*k]: slot of assignment i, -1 if dropped.
+ *   src_of int32 [moe_max_rows]: assignment held by each slot < offsets[E].
+ *   xe [moe_max_rows, d_model] `dtype`: xe[slot,:] = x[t,:]; rows at or beyond
+ *   offsets[E] are left untouched. */
+moe_status moe_dispatch(const moe_shape *s, const void *x, const int32_t *expert_idx,
+                        int32_t *counts, int32_t *offsets, int32_t *slot_of,
+                        int32_t *src_of, void *xe, void *workspace, void *stream);
+
+/* Expert FFN (Sec. 2.1): for slot r of expert e,
+ *   ye[r,:] = act(xe[r,:] W1[e] + b1[e]) W2[e] + b2[e].
+ *   W1p, W2p from moe_pack_weights; b1 fp32 [E,d_ff] and b2 fp32 [E,d_model] may
+ *   be NULL; ye fp32 [moe_max_rows, d_model].  Experts with no rows read no
+ *   weights.  Rows at or beyond offsets[E] are left untouched. */
+moe_status moe_expert_ffn(const moe_shape *s, const void *xe, const int32_t *offsets,
+                          const void *W1p, const float *b1, const void *W2p,
+                          const float *b2, float *ye, void *workspace, void *stream);
+
+/* Combine = unpack after the second all-to-all (Sec. 2.2, forward-pass timeline):
+ *   y[t,:] = sum over kept j of gate[t,j] * ye[slot_of[t*k+j],:]  (fp32, ascending j),
+ * zero for a token with no kept assignment.
+ *   y fp32 [T, d_model].  y_act: NULL, or [T, d_model] in `dtype` receiving y
+ *   rounded to nearest-even (the next layer's input in a stack). */
+moe_status moe_combine(const moe_shape *s, const float *ye, const int32_t *slot_of,
+                       const float *gate, float *y, void *y_act, void *stream);
+
+/* The whole layer with the token stream cut into n_chunks contiguous parts
+ * (chunk c = tokens [floor(c*T/n), floor((c+1)*T/n)); 1 <= n_chunks <= 64).
+ * Routing and the dispatch plan are computed once over all T tokens, so every
+ * output is identical for every n_chunks (Sec. 7.1: the scheduling does not change
+ * what is computed).  Packing of chunk c+1 and unpacking of chunk c-1 run on side
+ * streams concurrently with the expert FFN of chunk c (Sec. 4.2).
+ * Arguments as in the calls above; all outputs are written.  The side streams
+ * and events are created on the first chunked call on a device and kept. */
+moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x,
+                             const float *Wgp, const float *gate_bias,
+                             int32_t bias_token_stride, const void *W1p,
+                             const float *b1, const void *W2p, const float *b2,
+                             int32_t *expert_idx, float *gate, int32_t *counts,
+                             int32_t *offsets, int32_t *slot_of, int32_t *src_of,
+                             void *xe, float *ye, float *y, void *y_act,
+                             void *workspace, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H */

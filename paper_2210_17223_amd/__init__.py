@@ -1,0 +1,16 @@
+"""MI355X-native one-GPU MoE-layer forward (libmoe) and its thin Python binding.
+
+The HIP kernels live in csrc/ behind the C-ABI declared in include/moe.h; this
+package only marshals arguments.  PyTorch is used for device memory and streams.
+"""
+from .binding import (ACT, DTYPE, MoeError, Shape, alloc_buffers, lib, lib_path,
+                      moe_capacity, moe_combine, moe_dispatch, moe_expert_ffn,
+                      moe_last_error, moe_layer_chunked, moe_max_rows, moe_pack_gate,
+                      moe_pack_weights, moe_packed_gate_bytes, moe_packed_weight_bytes,
+                      moe_route, moe_workspace_bytes)
+
+__all__ = ["ACT", "DTYPE", "MoeError", "Shape", "alloc_buffers", "lib", "lib_path",
+           "moe_capacity", "moe_combine", "moe_dispatch", "moe_expert_ffn",
+           "moe_last_error", "moe_layer_chunked", "moe_max_rows", "moe_pack_gate",
+           "moe_pack_weights", "moe_packed_gate_bytes", "moe_packed_weight_bytes",
+           "moe_route", "moe_workspace_bytes"]

@@ -1,0 +1,398 @@
+// C-ABI entry points of libmoe: argument checks, workspace layout, and the order in
+// which the kernels are enqueued.  No arithmetic of the layer happens here.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+#include "common.h"
+
+namespace moe {
+
+size_t packed_gate_bytes(const moe_shape &s);
+moe_status launch_pack_gate(const moe_shape &s, const void *Wg, float *Wgp, hipStream_t st);
+
+namespace {
+thread_local char g_error[512] = "";
+}
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+}
+
+moe_status hip_fail(hipError_t e, const char *what)
+{
+    set_error("HIP error %d (%s) in %s", static_cast<int>(e), hipGetErrorString(e), what);
+    return MOE_EHIP;
+}
+
+namespace {
+
+int elem_bytes(const moe_shape &s) { return s.dtype == MOE_BF16 ? 2 : 4; }
+
+bool check_shape(const moe_shape *s)
+{
+    if (s == nullptr) {
+        set_error("shape is NULL");
+        return false;
+    }
+    if (s->dtype != MOE_F32 && s->dtype != MOE_BF16) {
+        set_error("dtype %d is neither MOE_F32 nor MOE_BF16", s->dtype);
+        return false;
+    }
+    if (s->act < MOE_ACT_GELU_ERF || s->act > MOE_ACT_IDENTITY) {
+        set_error("unknown activation %d", s->act);
+        return false;
+    }
+    if (s->T < 1 || s->d_model < 1 || s->d_ff < 1 || s->E < 1 || s->k < 1 || s->capacity < 1) {
+        set_error("T, d_model, d_ff, E, k, capacity must all be >= 1");
+        return false;
+    }
+    if (s->k > s->E) {
+        set_error("k = %d exceeds E = %d", s->k, s->E);
+        return false;
+    }
+    if (static_cast<int64_t>(s->T) * s->k >= (1ll << 31) ||
+        static_cast<int64_t>(s->E) * s->capacity >= (1ll << 40)) {
+        set_error("T*k does not fit 31 bits");
+        return false;
+    }
+    return true;
+}
+
+// MOE_OK, or MOE_EUNSUPPORTED with the reason recorded.
+moe_status check_supported(const moe_shape &s)
+{
+    if (s.E > kMaxExperts) {
+        set_error("E = %d: at most %d experts are supported", s.E, kMaxExperts);
+        return MOE_EUNSUPPORTED;
+    }
+    if (s.k > kMaxTopK) {
+        set_error("k = %d: at most %d experts per token are supported", s.k, kMaxTopK);
+        return MOE_EUNSUPPORTED;
+    }
+    const int eb = elem_bytes(s);
+    if ((s.d_model * eb) % 16 != 0 || (s.d_ff * eb) % 16 != 0) {
+        set_error("row sizes must be multiples of 16 bytes (d_model=%d, d_ff=%d, %d-byte elements)",
+                  s.d_model, s.d_ff, eb);
+        return MOE_EUNSUPPORTED;
+    }
+    return MOE_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define MOE_REQUIRE_PTR(p)                                          \
+    do {                                                            \
+        if ((p) == nullptr || !aligned16(p)) {                      \
+            set_error(#p " is NULL or not 16-byte aligned");        \
+            return MOE_EINVAL;                                      \
+        }                                                           \
+    } while (0)
+#define MOE_OPTIONAL_PTR(p)                                         \
+    do {                                                            \
+        if ((p) != nullptr && !aligned16(p)) {                      \
+            set_error(#p " is not 16-byte aligned");                \
+            return MOE_EINVAL;                                      \
+        }                                                           \
+    } while (0)
+#define MOE_TRY(expr)                        \
+    do {                                     \
+        moe_status st_ = (expr);             \
+        if (st_ != MOE_OK) return st_;       \
+    } while (0)
+
+moe_status check_common(const moe_shape *s)
+{
+    if (!check_shape(s)) return MOE_EINVAL;
+    return check_supported(*s);
+}
+
+moe_status check_bias(const moe_shape &s, const float *gate_bias, int32_t stride)
+{
+    if (gate_bias != nullptr && stride != 0 && stride != s.E) {
+        set_error("bias_token_stride must be 0 or E (= %d), got %d", s.E, stride);
+        return MOE_EINVAL;
+    }
+    return MOE_OK;
+}
+
+// Side streams and events of moe_layer_chunked, created on first use per device and
+// kept until the process ends.
+struct ChunkResources {
+    bool ready = false;
+    hipStream_t pack = nullptr, unpack = nullptr;
+    hipEvent_t planned = nullptr, unpacked = nullptr;
+    hipEvent_t packed[kMaxChunks] = {};
+    hipEvent_t computed[kMaxChunks] = {};
+};
+std::mutex g_res_mutex;
+ChunkResources g_res[16];
+
+moe_status chunk_resources(ChunkResources **out)
+{
+    int dev = 0;
+    MOE_TRY_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 16) {
+        set_error("device index %d out of range", dev);
+        return MOE_EUNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(g_res_mutex);
+    ChunkResources &r = g_res[dev];
+    if (!r.ready) {
+        MOE_TRY_HIP(hipStreamCreateWithFlags(&r.pack, hipStreamNonBlocking));
+        MOE_TRY_HIP(hipStreamCreateWithFlags(&r.unpack, hipStreamNonBlocking));
+        MOE_TRY_HIP(hipEventCreateWithFlags(&r.planned, hipEventDisableTiming));
+        MOE_TRY_HIP(hipEventCreateWithFlags(&r.unpacked, hipEventDisableTiming));
+        for (int c = 0; c < kMaxChunks; ++c) {
+            MOE_TRY_HIP(hipEventCreateWithFlags(&r.packed[c], hipEventDisableTiming));
+            MOE_TRY_HIP(hipEventCreateWithFlags(&r.computed[c], hipEventDisableTiming));
+        }
+        r.ready = true;
+    }
+    *out = &r;
+    return MOE_OK;
+}
+
+}  // namespace
+
+bool layout_workspace(const moe_shape &s, int n_chunks, void *base, Workspace *w)
+{
+    if (n_chunks < 1 || n_chunks > kMaxChunks) return false;
+    const int64_t n = static_cast<int64_t>(s.T) * s.k;
+    const int64_t max_rows = moe_max_rows(&s);
+    w->nseg = static_cast<int32_t>((n + kSeg - 1) / kSeg);
+    w->tile_rows = ffn_tile_rows(s);
+    const int64_t chunk_tokens = (s.T + n_chunks - 1) / n_chunks;
+    int64_t chunk_rows = chunk_tokens * s.k;
+    if (chunk_rows > max_rows) chunk_rows = max_rows;
+    w->max_tiles = static_cast<int32_t>((chunk_rows + w->tile_rows - 1) / w->tile_rows + s.E);
+    char *p = static_cast<char *>(base);
+    size_t off = 0;
+    w->seg_cnt = reinterpret_cast<int32_t *>(p + off);
+    off += align_up(static_cast<size_t>(w->nseg) * kMaxExperts * sizeof(int32_t), 256);
+    w->tiles = reinterpret_cast<RowTile *>(p + off);
+    off += align_up(static_cast<size_t>(n_chunks) * w->max_tiles * sizeof(RowTile), 256);
+    w->ntiles = reinterpret_cast<int32_t *>(p + off);
+    off += align_up(static_cast<size_t>(n_chunks) * sizeof(int32_t), 256);
+    w->hidden = p + off;
+    const size_t hidden_elem = s.dtype == MOE_BF16 ? 2 : 4;
+    off += align_up(static_cast<size_t>(max_rows) * s.d_ff * hidden_elem, 256);
+    w->bytes = off;
+    return true;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+int64_t moe_capacity(int32_t T, int32_t E, int32_t k, double cf)
+{
+    if (T < 1 || E < 1 || k < 1) return 0;
+    if (!(cf > 0.0)) return T;
+    const double v = cf * static_cast<double>(k) * static_cast<double>(T) / static_cast<double>(E);
+    int64_t c = static_cast<int64_t>(v);
+    if (static_cast<double>(c) < v - 1e-9) c += 1;
+    return c < 1 ? 1 : c;
+}
+
+int64_t moe_max_rows(const moe_shape *s)
+{
+    if (s == nullptr) return 0;
+    const int64_t a = static_cast<int64_t>(s->T) * s->k;
+    const int64_t b = static_cast<int64_t>(s->E) * s->capacity;
+    return a < b ? a : b;
+}
+
+size_t moe_workspace_bytes(const moe_shape *s, int32_t n_chunks)
+{
+    if (check_common(s) != MOE_OK) return 0;
+    Workspace w;
+    if (!layout_workspace(*s, n_chunks, nullptr, &w)) {
+        set_error("n_chunks must be in 1..%d, got %d", kMaxChunks, n_chunks);
+        return 0;
+    }
+    return w.bytes;
+}
+
+const char *moe_last_error(void) { return g_error; }
+
+size_t moe_packed_weight_bytes(const moe_shape *s)
+{
+    if (check_common(s) != MOE_OK) return 0;
+    return static_cast<size_t>(s->E) * s->d_model * s->d_ff * elem_bytes(*s);
+}
+
+size_t moe_packed_gate_bytes(const moe_shape *s)
+{
+    if (check_common(s) != MOE_OK) return 0;
+    return packed_gate_bytes(*s);
+}
+
+moe_status moe_pack_weights(const moe_shape *s, const void *W1, const void *W2, void *W1p,
+                            void *W2p, void *stream)
+{
+    MOE_TRY(check_common(s));
+    MOE_REQUIRE_PTR(W1);
+    MOE_REQUIRE_PTR(W2);
+    MOE_REQUIRE_PTR(W1p);
+    MOE_REQUIRE_PTR(W2p);
+    return launch_pack(*s, W1, W2, W1p, W2p, static_cast<hipStream_t>(stream));
+}
+
+moe_status moe_pack_gate(const moe_shape *s, const void *Wg, float *Wgp, void *stream)
+{
+    MOE_TRY(check_common(s));
+    MOE_REQUIRE_PTR(Wg);
+    MOE_REQUIRE_PTR(Wgp);
+    return launch_pack_gate(*s, Wg, Wgp, static_cast<hipStream_t>(stream));
+}
+
+moe_status moe_route(const moe_shape *s, const void *x, const float *Wgp,
+                     const float *gate_bias, int32_t bias_token_stride, int32_t *expert_idx,
+                     float *gate, void *stream)
+{
+    MOE_TRY(check_common(s));
+    MOE_REQUIRE_PTR(x);
+    MOE_REQUIRE_PTR(Wgp);
+    MOE_REQUIRE_PTR(expert_idx);
+    MOE_REQUIRE_PTR(gate);
+    MOE_TRY(check_bias(*s, gate_bias, bias_token_stride));
+    return launch_route(*s, x, Wgp, gate_bias, bias_token_stride, expert_idx, gate,
+                        static_cast<hipStream_t>(stream));
+}
+
+moe_status moe_dispatch(const moe_shape *s, const void *x, const int32_t *expert_idx,
+                        int32_t *counts, int32_t *offsets, int32_t *slot_of, int32_t *src_of,
+                        void *xe, void *workspace, void *stream)
+{
+    MOE_TRY(check_common(s));
+    MOE_REQUIRE_PTR(x);
+    MOE_REQUIRE_PTR(expert_idx);
+    MOE_REQUIRE_PTR(counts);
+    MOE_REQUIRE_PTR(offsets);
+    MOE_REQUIRE_PTR(slot_of);
+    MOE_REQUIRE_PTR(src_of);
+    MOE_REQUIRE_PTR(xe);
+    MOE_REQUIRE_PTR(workspace);
+    Workspace w;
+    layout_workspace(*s, 1, workspace, &w);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    MOE_TRY(launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w, st));
+    return launch_scatter(*s, x, slot_of, xe, 0, s->T, st);
+}
+
+moe_status moe_expert_ffn(const moe_shape *s, const void *xe, const int32_t *offsets,
+                          const void *W1p, const float *b1, const void *W2p, const float *b2,
+                          float *ye, void *workspace, void *stream)
+{
+    MOE_TRY(check_common(s));
+    MOE_REQUIRE_PTR(xe);
+    MOE_REQUIRE_PTR(offsets);
+    MOE_REQUIRE_PTR(W1p);
+    MOE_REQUIRE_PTR(W2p);
+    MOE_OPTIONAL_PTR(b1);
+    MOE_OPTIONAL_PTR(b2);
+    MOE_REQUIRE_PTR(ye);
+    MOE_REQUIRE_PTR(workspace);
+    Workspace w;
+    layout_workspace(*s, 1, workspace, &w);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    MOE_TRY(launch_tiles(*s, 1, offsets, nullptr, w, st));
+    return launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, 0, st);
+}
+
+moe_status moe_combine(const moe_shape *s, const float *ye, const int32_t *slot_of,
+                       const float *gate, float *y, void *y_act, void *stream)
+{
+    MOE_TRY(check_common(s));
+    MOE_REQUIRE_PTR(ye);
+    MOE_REQUIRE_PTR(slot_of);
+    MOE_REQUIRE_PTR(gate);
+    MOE_REQUIRE_PTR(y);
+    MOE_OPTIONAL_PTR(y_act);
+    return launch_combine(*s, ye, slot_of, gate, y, y_act, 0, s->T,
+                          static_cast<hipStream_t>(stream));
+}
+
+moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x,
+                             const float *Wgp, const float *gate_bias,
+                             int32_t bias_token_stride, const void *W1p, const float *b1,
+                             const void *W2p, const float *b2, int32_t *expert_idx, float *gate,
+                             int32_t *counts, int32_t *offsets, int32_t *slot_of,
+                             int32_t *src_of, void *xe, float *ye, float *y, void *y_act,
+                             void *workspace, void *stream)
+{
+    MOE_TRY(check_common(s));
+    if (n_chunks < 1 || n_chunks > kMaxChunks) {
+        set_error("n_chunks must be in 1..%d, got %d", kMaxChunks, n_chunks);
+        return MOE_EINVAL;
+    }
+    MOE_REQUIRE_PTR(x);
+    MOE_REQUIRE_PTR(Wgp);
+    MOE_REQUIRE_PTR(W1p);
+    MOE_REQUIRE_PTR(W2p);
+    MOE_OPTIONAL_PTR(b1);
+    MOE_OPTIONAL_PTR(b2);
+    MOE_REQUIRE_PTR(expert_idx);
+    MOE_REQUIRE_PTR(gate);
+    MOE_REQUIRE_PTR(counts);
+    MOE_REQUIRE_PTR(offsets);
+    MOE_REQUIRE_PTR(slot_of);
+    MOE_REQUIRE_PTR(src_of);
+    MOE_REQUIRE_PTR(xe);
+    MOE_REQUIRE_PTR(ye);
+    MOE_REQUIRE_PTR(y);
+    MOE_OPTIONAL_PTR(y_act);
+    MOE_REQUIRE_PTR(workspace);
+    MOE_TRY(check_bias(*s, gate_bias, bias_token_stride));
+    if (n_chunks > s->T) n_chunks = s->T;
+
+    Workspace w;
+    layout_workspace(*s, n_chunks, workspace, &w);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    MOE_TRY(launch_route(*s, x, Wgp, gate_bias, bias_token_stride, expert_idx, gate, st));
+    MOE_TRY(launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w, st));
+    MOE_TRY(launch_tiles(*s, n_chunks, offsets, src_of, w, st));
+
+    if (n_chunks == 1) {
+        MOE_TRY(launch_scatter(*s, x, slot_of, xe, 0, s->T, st));
+        MOE_TRY(launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, 0, st));
+        return launch_combine(*s, ye, slot_of, gate, y, y_act, 0, s->T, st);
+    }
+
+    // pack stream: chunk after chunk; caller's stream: expert FFN of a chunk once it
+    // is packed; unpack stream: combine of a chunk once its FFN is done.
+    ChunkResources *r = nullptr;
+    MOE_TRY(chunk_resources(&r));
+    MOE_TRY_HIP(hipEventRecord(r->planned, st));
+    MOE_TRY_HIP(hipStreamWaitEvent(r->pack, r->planned, 0));
+    MOE_TRY_HIP(hipStreamWaitEvent(r->unpack, r->planned, 0));
+    for (int c = 0; c < n_chunks; ++c) {
+        const int t0 = static_cast<int>(static_cast<int64_t>(c) * s->T / n_chunks);
+        const int t1 = static_cast<int>(static_cast<int64_t>(c + 1) * s->T / n_chunks);
+        MOE_TRY(launch_scatter(*s, x, slot_of, xe, t0, t1, r->pack));
+        MOE_TRY_HIP(hipEventRecord(r->packed[c], r->pack));
+    }
+    for (int c = 0; c < n_chunks; ++c) {
+        const int t0 = static_cast<int>(static_cast<int64_t>(c) * s->T / n_chunks);
+        const int t1 = static_cast<int>(static_cast<int64_t>(c + 1) * s->T / n_chunks);
+        MOE_TRY_HIP(hipStreamWaitEvent(st, r->packed[c], 0));
+        MOE_TRY(launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, c, st));
+        MOE_TRY_HIP(hipEventRecord(r->computed[c], st));
+        MOE_TRY_HIP(hipStreamWaitEvent(r->unpack, r->computed[c], 0));
+        MOE_TRY(launch_combine(*s, ye, slot_of, gate, y, y_act, t0, t1, r->unpack));
+    }
+    MOE_TRY_HIP(hipEventRecord(r->unpacked, r->unpack));
+    MOE_TRY_HIP(hipStreamWaitEvent(st, r->unpacked, 0));
+    return MOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,90 @@
+// Shared declarations of libmoe's translation units (host helpers, device
+// conversions, kernel launch prototypes).  gfx950 only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+namespace moe {
+
+constexpr int kWave = 64;          // wavefront width on CDNA
+constexpr int kMaxExperts = 64;    // one ballot bit / one lane per expert
+constexpr int kMaxTopK = 8;
+constexpr int kSeg = 512;          // assignments ranked by one wavefront in the plan
+constexpr int kMaxChunks = 64;
+
+// ---- host side -------------------------------------------------------------
+void set_error(const char *fmt, ...);
+moe_status hip_fail(hipError_t e, const char *what);
+
+#define MOE_TRY_HIP(expr)                                             \
+    do {                                                              \
+        hipError_t e_ = (expr);                                       \
+        if (e_ != hipSuccess) return ::moe::hip_fail(e_, #expr);      \
+    } while (0)
+
+__host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+__host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// One row tile of the grouped GEMM: rows [row0, row1) of the expert-major buffer,
+// all owned by `expert`.
+struct RowTile {
+    int32_t expert;
+    int32_t row0;
+    int32_t row1;
+    int32_t pad;
+};
+
+// Where each piece of the caller's workspace lives.
+struct Workspace {
+    int32_t *seg_cnt;    // [nseg][kMaxExperts] per-segment expert counts -> bases
+    RowTile *tiles;      // [n_chunks][max_tiles]
+    int32_t *ntiles;     // [n_chunks]
+    void *hidden;        // [max_rows][d_ff] hidden activations
+    int32_t nseg;
+    int32_t max_tiles;   // per chunk
+    int32_t tile_rows;   // rows per row tile of the FFN kernels
+    size_t bytes;
+};
+bool layout_workspace(const moe_shape &s, int n_chunks, void *base, Workspace *w);
+int ffn_tile_rows(const moe_shape &s);
+
+// ---- kernel launchers (each only enqueues on `st`) ---------------------------
+moe_status launch_route(const moe_shape &s, const void *x, const void *Wg,
+                        const float *bias, int bias_stride, int32_t *expert_idx,
+                        float *gate, hipStream_t st);
+moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *counts,
+                       int32_t *offsets, int32_t *slot_of, int32_t *src_of,
+                       const Workspace &w, hipStream_t st);
+moe_status launch_tiles(const moe_shape &s, int n_chunks, const int32_t *offsets,
+                        const int32_t *src_of, const Workspace &w, hipStream_t st);
+moe_status launch_scatter(const moe_shape &s, const void *x, const int32_t *slot_of,
+                          void *xe, int t0, int t1, hipStream_t st);
+moe_status launch_combine(const moe_shape &s, const float *ye, const int32_t *slot_of,
+                          const float *gate, float *y, void *y_act, int t0, int t1,
+                          hipStream_t st);
+moe_status launch_ffn(const moe_shape &s, const void *xe, const void *W1p,
+                      const float *b1, const void *W2p, const float *b2, float *ye,
+                      const Workspace &w, int chunk, hipStream_t st);
+moe_status launch_pack(const moe_shape &s, const void *W1, const void *W2, void *W1p,
+                       void *W2p, hipStream_t st);
+
+// ---- device helpers --------------------------------------------------------
+#if defined(__HIPCC__)
+__device__ __forceinline__ float bf16_to_f32(uint16_t b)
+{
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+// round to nearest, ties to even; finite inputs
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+#endif
+
+}  // namespace moe

@@ -1,0 +1,85 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared entry
+point, its pure host functions are right, and bad arguments are refused before
+anything is enqueued (so none of this needs a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2210_17223_amd as moe
+import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    syms = declared_symbols()
+    assert {"moe_route", "moe_dispatch", "moe_expert_ffn", "moe_combine",
+            "moe_layer_chunked"} <= set(syms)
+    L = moe.lib()
+    for name in syms:
+        assert hasattr(L, name), f"{name} is declared in include/moe.h but not exported"
+
+
+def test_capacity_matches_generator_formula():
+    for c in wl.CONFIGS.values():
+        want = wl.capacity(c["T"], c["E"], c["k"], c["cf"])
+        assert moe.moe_capacity(c["T"], c["E"], c["k"], c["cf"] or 0.0) == want
+    assert moe.moe_capacity(10, 4, 1, 1.0) == 3
+    assert moe.moe_capacity(8, 4, 1, 1.0) == 2
+
+
+def test_sizes():
+    s = moe.Shape.make(4096, 768, 16, 3072, 2, 640)
+    assert moe.moe_max_rows(s) == 8192
+    assert moe.moe_packed_weight_bytes(s) == 16 * 768 * 3072 * 2
+    assert moe.moe_packed_gate_bytes(s) == 768 * 16 * 4
+    assert moe.moe_workspace_bytes(s, 1) >= 8192 * 3072 * 2
+    assert moe.moe_workspace_bytes(s, 8) >= moe.moe_workspace_bytes(s, 1) - (1 << 16)
+    s2 = moe.Shape.make(100, 64, 6, 128, 2, 5, dtype="f32")
+    assert moe.moe_max_rows(s2) == 30
+    assert moe.moe_packed_gate_bytes(s2) == 64 * 8 * 4
+
+
+@pytest.mark.parametrize("kw,frag", [
+    (dict(E=65), "at most 64"),
+    (dict(k=9, E=16), "at most 8"),
+    (dict(k=5, E=4), "exceeds"),
+    (dict(d_model=100), "multiples of 16"),
+    (dict(T=0), ">= 1"),
+    (dict(capacity=0), ">= 1"),
+])
+def test_bad_shapes_are_refused(kw, frag):
+    base = dict(T=64, d_model=64, E=4, d_ff=128, k=2, capacity=32)
+    base.update(kw)
+    s = moe.Shape.make(**base)
+    assert moe.moe_workspace_bytes(s, 1) == 0
+    assert frag in moe.moe_last_error()
+
+
+def test_null_and_misaligned_pointers_are_refused_before_any_launch():
+    s = moe.Shape.make(64, 64, 4, 128, 2, 32)
+    L = moe.lib()
+    z = C.c_void_p(0)
+    ok = C.c_void_p(4096)
+    odd = C.c_void_p(4100)
+    assert L.moe_route(C.byref(s), z, ok, z, 0, ok, ok, z) == 1
+    assert "x is NULL" in moe.moe_last_error()
+    assert L.moe_route(C.byref(s), odd, ok, z, 0, ok, ok, z) == 1
+    assert L.moe_route(C.byref(s), ok, ok, ok, 3, ok, ok, z) == 1
+    assert "bias_token_stride" in moe.moe_last_error()
+    assert L.moe_combine(C.byref(s), ok, ok, ok, z, z, z) == 1
+    assert L.moe_dispatch(C.byref(s), ok, ok, ok, ok, ok, ok, ok, z, z) == 1
+    assert L.moe_expert_ffn(C.byref(s), ok, ok, z, z, ok, z, ok, ok, z) == 1
+    args = [ok] * 16
+    assert L.moe_layer_chunked(C.byref(s), 0, ok, ok, z, 0, *args) == 1
+    assert "n_chunks" in moe.moe_last_error()
+    assert L.moe_layer_chunked(C.byref(s), 65, ok, ok, z, 0, *args) == 1
+    assert L.moe_route(None, ok, ok, z, 0, ok, ok, z) == 1

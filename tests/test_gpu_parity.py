@@ -1,0 +1,172 @@
+"""Parity of the HIP path against the CPU oracle, entry point by entry point and as
+a whole layer, at sizes the oracle finishes in seconds.  Integers bit-exact; gate
+weights within 1e-6 relative; row copies bit-exact; floating-point outputs within
+2e-2 (bf16) / 1e-5 (fp32) of the oracle's output RMS, max-abs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2210_17223_amd as moe
+import workloads as wl
+from gpu_util import (DEV, DeviceLayer, assert_ints_equal, download, rel_rms_err, shape_of,
+                      upload)
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-2, "f32": 1e-5}
+
+SMALL = {
+    "tiny_fp32": wl.CONFIGS["tiny_fp32"],
+    "tiny_fp32_ragged": wl.scaled("tiny_fp32", T=333, d=72, h=100, E=5, k=2, cf=0.8),
+    "gpt2s_small": wl.scaled("gpt2s_moe", T=1000, d=256, h=512),
+    "gpt2s_k1_e6": wl.scaled("gpt2s_moe", T=700, d=192, h=320, E=6, k=1, cf=1.0),
+    "gpt2s_k3": wl.scaled("gpt2s_moe", T=512, d=128, h=264, E=8, k=3, cf=1.1),
+    "skewed_small": wl.scaled("skewed", T=2048, d=256, h=384),
+    "chunked_small": wl.scaled("large_chunked", T=2048, d=128, h=256),
+    "stack_layer": wl.scaled("infer_stack", T=256, d=256, h=512),
+}
+
+
+def run_oracle(li, act="gelu", renorm=False, b1=None, b2=None, capacity=None):
+    return oracle.moe_layer(li.x, li.Wg, li.W1, li.W2, k=li.k,
+                            capacity=li.C if capacity is None else capacity, act=act,
+                            bias=li.gate_bias, bias_stride=li.bias_token_stride, b1=b1, b2=b2,
+                            renorm=renorm)
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_entry_points_one_by_one(name):
+    li = wl.make_layer(SMALL[name], seed=0)
+    o = run_oracle(li)
+    s = shape_of(li)
+    L = DeviceLayer(li, s)
+    b = L.b
+    # --- gate
+    moe.moe_route(s, L.x, b["Wgp"], L.bias, L.bias_stride, b["expert_idx"], b["gate"])
+    torch.cuda.synchronize()
+    assert np.array_equal(b["expert_idx"].cpu().numpy().reshape(li.T, li.k), o.expert_idx)
+    np.testing.assert_allclose(b["gate"].cpu().numpy().reshape(li.T, li.k), o.gate, rtol=1e-6)
+    # --- dispatch, fed with the oracle's expert choice
+    idx = torch.from_numpy(o.expert_idx.reshape(-1)).to(DEV)
+    b["xe"].zero_()
+    moe.moe_dispatch(s, L.x, idx, b["counts"], b["offsets"], b["slot_of"], b["src_of"], b["xe"],
+                     b["workspace"])
+    torch.cuda.synchronize()
+    got = L.ints()
+    got["expert_idx"] = o.expert_idx
+    assert_ints_equal(got, o)
+    xe = download(b["xe"]).reshape(-1, li.d)
+    assert np.array_equal(xe[:o.A].view(np.uint32), o.xe.view(np.uint32))
+    assert not xe[o.A:].any()                         # rows past offsets[E] untouched
+    # --- expert FFN on the oracle's buffer
+    rows = np.arange(o.A, dtype=np.int32)
+    ye_ref = oracle.ffn_rows(o.xe, o.off, li.W1, li.W2, rows)
+    b["ye"].zero_()
+    moe.moe_expert_ffn(s, b["xe"], b["offsets"], b["W1p"], None, b["W2p"], None, b["ye"],
+                       b["workspace"])
+    torch.cuda.synchronize()
+    ye = b["ye"].cpu().numpy().reshape(-1, li.d)
+    assert rel_rms_err(ye[:o.A], ye_ref) <= TOL[li.dtype]
+    assert not ye[o.A:].any()
+    # --- combine on the oracle's expert outputs (rounded to fp32)
+    ye_dev = torch.zeros_like(b["ye"])
+    ye_dev[:o.A * li.d] = torch.from_numpy(ye_ref.astype(np.float32).reshape(-1)).to(DEV)
+    slot = torch.from_numpy(o.slot_of).to(DEV)
+    gate = torch.from_numpy(o.gate.reshape(-1)).to(DEV)
+    moe.moe_combine(s, ye_dev, slot, gate, b["y"])
+    torch.cuda.synchronize()
+    y = b["y"].cpu().numpy().reshape(li.T, li.d)
+    assert rel_rms_err(y, o.y) <= 1e-5
+    dropped = (o.slot_of.reshape(li.T, li.k) < 0).all(1)
+    assert not y[dropped].any()
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_whole_layer_and_chunk_invariance(name):
+    li = wl.make_layer(SMALL[name], seed=1)
+    o = run_oracle(li)
+    s = shape_of(li)
+    L = DeviceLayer(li, s, n_chunks=64, y_act=True)
+    ref_bits = None
+    for n_chunks in (1, 2, 3, 4, 8, 64):
+        for key in ("y", "ye", "xe"):
+            L.b[key].zero_()
+        L.layer(n_chunks)
+        assert_ints_equal(L.ints(), o)
+        np.testing.assert_allclose(L.b["gate"].cpu().numpy().reshape(li.T, li.k), o.gate, rtol=1e-6)
+        y = L.b["y"].cpu().numpy().reshape(li.T, li.d)
+        assert rel_rms_err(y, o.y) <= TOL[li.dtype], f"n_chunks={n_chunks}"
+        if ref_bits is None:
+            ref_bits = y.view(np.uint32).copy()
+        else:                                          # chunking changes no bit of the output
+            assert np.array_equal(y.view(np.uint32), ref_bits), f"n_chunks={n_chunks}"
+        y_act = download(L.b["y_act"]).reshape(li.T, li.d)
+        want = wl.bf16_round(y) if li.dtype == "bf16" else y
+        assert np.array_equal(y_act.view(np.uint32), want.view(np.uint32))
+
+
+@pytest.mark.parametrize("act", ["gelu", "gelu_tanh", "relu", "identity"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_activations_biases_and_renorm(act, dtype):
+    cfg = wl.scaled("gpt2s_moe", T=300, d=64, h=136, E=4, k=2, cf=1.5, dtype=dtype)
+    li = wl.make_layer(cfg, seed=2)
+    rng = np.random.default_rng(5)
+    b1 = (rng.standard_normal((li.E, li.h)) * 0.1).astype(np.float32)
+    b2 = (rng.standard_normal((li.E, li.d)) * 0.1).astype(np.float32)
+    o = run_oracle(li, act=act, renorm=True, b1=b1, b2=b2)
+    s = shape_of(li, act=act, renorm=True)
+    L = DeviceLayer(li, s, b1=b1, b2=b2)
+    L.layer(1)
+    assert_ints_equal(L.ints(), o)
+    np.testing.assert_allclose(L.b["gate"].cpu().numpy().reshape(li.T, li.k), o.gate, rtol=1e-6)
+    assert rel_rms_err(L.b["y"].cpu().numpy().reshape(li.T, li.d), o.y) <= TOL[dtype]
+
+
+def test_identity_experts_return_gate_times_x():
+    # the layer-level invariant: with identity experts and k = 1 the output is gate * x
+    cfg = wl.scaled("tiny_fp32", T=256, d=64, h=64, E=4, k=1, cf=None)
+    li = wl.make_layer(cfg, seed=3)
+    eye = np.tile(np.eye(li.d, dtype=np.float32), (li.E, 1, 1))
+    li.W1, li.W2 = eye, eye.copy()
+    s = shape_of(li, act="identity")
+    L = DeviceLayer(li, s)
+    L.layer(1)
+    y = L.b["y"].cpu().numpy().reshape(li.T, li.d)
+    g = L.b["gate"].cpu().numpy().reshape(li.T, 1)
+    np.testing.assert_allclose(y, g * li.x, rtol=1e-6, atol=1e-7)
+
+
+@pytest.mark.parametrize("T,E,k,C", [(1, 1, 1, 1), (1, 4, 2, 1), (65, 3, 2, 7), (130, 64, 8, 3),
+                                     (513, 2, 1, 600), (64, 8, 8, 64)])
+def test_edge_shapes(T, E, k, C):
+    cfg = dict(T=T, d=64, E=E, h=72, k=k, cf=None, dtype="bf16", skew=None, layers=1)
+    li = wl.make_layer(cfg, seed=4)
+    li.C = C
+    o = run_oracle(li)
+    s = shape_of(li)
+    L = DeviceLayer(li, s, n_chunks=4)
+    for n_chunks in (1, 4):
+        L.layer(n_chunks)
+        assert_ints_equal(L.ints(), o)
+        assert rel_rms_err(L.b["y"].cpu().numpy().reshape(li.T, li.d), o.y) <= TOL["bf16"]
+
+
+def test_everything_to_one_expert_and_empty_experts():
+    # a bias that sends every token to expert 2: the other experts own no rows
+    cfg = wl.scaled("gpt2s_moe", T=700, d=128, h=256, E=8, k=1, cf=None)
+    li = wl.make_layer(cfg, seed=5)
+    bias = np.zeros(li.E, np.float32)
+    bias[2] = 40.0
+    li.gate_bias, li.bias_token_stride, li.C = bias, 0, 300
+    o = run_oracle(li)
+    assert o.count[2] == li.T and o.A == 300
+    s = shape_of(li)
+    L = DeviceLayer(li, s, n_chunks=8)
+    for n_chunks in (1, 8):                             # the later chunks are fully dropped
+        L.b["y"].fill_(7.0)
+        L.layer(n_chunks)
+        assert_ints_equal(L.ints(), o)
+        y = L.b["y"].cpu().numpy().reshape(li.T, li.d)
+        assert rel_rms_err(y, o.y) <= TOL["bf16"]
+        assert not y[300:].any()
