@@ -172,6 +172,20 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
                              void *xe, float *ye, float *y, void *y_act,
                              void *workspace, void *stream);
 
+/* Measurement aid, off by default (not part of the layer).  Stage numbers:
+ * 0 gate, 1 dispatch plan, 2 row-tile table, 3 pack (scatter), 4 first expert GEMM
+ * (+ activation), 5 second expert GEMM, 6 combine.
+ * moe_profile_enable: for every stage whose bit is set in stage_mask, the next
+ * max_samples launches of that stage are bracketed by a pair of timing events
+ * recorded on the stream the stage runs on.  (0, 0) switches it off and frees the
+ * events.  Host; creates events; not thread-safe; call it while no libmoe call is
+ * in progress.
+ * moe_profile_read: waits for the recorded events of `stage`, writes the elapsed
+ * milliseconds of each bracket to ms[0..n) (host pointer, -1 where a read failed),
+ * returns n <= cap and forgets the samples. */
+moe_status moe_profile_enable(uint32_t stage_mask, int32_t max_samples);
+int32_t moe_profile_read(int32_t stage, float *ms, int32_t cap);
+
 #ifdef __cplusplus
 }
 #endif

@@ -57,6 +57,10 @@ def _p(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
 
 
+def threads() -> int:
+    return int(_load().oracle_threads())
+
+
 def act_value(v: float, act: str) -> float:
     return float(_load().oracle_act(float(v), ACT[act]))
 

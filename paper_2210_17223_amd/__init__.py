@@ -7,10 +7,12 @@ from .binding import (ACT, DTYPE, MoeError, Shape, alloc_buffers, lib, lib_path,
                       moe_capacity, moe_combine, moe_dispatch, moe_expert_ffn,
                       moe_last_error, moe_layer_chunked, moe_max_rows, moe_pack_gate,
                       moe_pack_weights, moe_packed_gate_bytes, moe_packed_weight_bytes,
-                      moe_route, moe_workspace_bytes)
+                      moe_profile_enable, moe_profile_read, moe_route, moe_workspace_bytes,
+                      STAGES)
 
 __all__ = ["ACT", "DTYPE", "MoeError", "Shape", "alloc_buffers", "lib", "lib_path",
            "moe_capacity", "moe_combine", "moe_dispatch", "moe_expert_ffn",
            "moe_last_error", "moe_layer_chunked", "moe_max_rows", "moe_pack_gate",
            "moe_pack_weights", "moe_packed_gate_bytes", "moe_packed_weight_bytes",
-           "moe_route", "moe_workspace_bytes"]
+           "moe_profile_enable", "moe_profile_read", "moe_route", "moe_workspace_bytes",
+           "STAGES"]

@@ -75,6 +75,10 @@ def lib() -> C.CDLL:
         L.moe_expert_ffn.argtypes = [sp] + [vp] * 9
         L.moe_combine.argtypes = [sp] + [vp] * 6
         L.moe_layer_chunked.argtypes = [sp, i32, vp, vp, vp, i32] + [vp] * 16
+        L.moe_profile_enable.restype = C.c_int
+        L.moe_profile_enable.argtypes = [C.c_uint32, i32]
+        L.moe_profile_read.restype = i32
+        L.moe_profile_read.argtypes = [i32, C.POINTER(C.c_float), i32]
         for name in ("moe_pack_weights", "moe_pack_gate", "moe_route", "moe_dispatch",
                      "moe_expert_ffn", "moe_combine", "moe_layer_chunked"):
             getattr(L, name).restype = C.c_int
@@ -214,6 +218,19 @@ def moe_layer_chunked(s: Shape, n_chunks: int, x, Wgp, gate_bias, bias_token_str
         _ptr(W1p), _ptr(b1), _ptr(W2p), _ptr(b2), _ptr(expert_idx), _ptr(gate), _ptr(counts),
         _ptr(offsets), _ptr(slot_of), _ptr(src_of), _ptr(xe), _ptr(ye), _ptr(y), _ptr(y_act),
         _ptr(workspace), _stream(stream)))
+
+
+STAGES = ("route", "plan", "tiles", "scatter", "gemm1", "gemm2", "combine")
+
+
+def moe_profile_enable(stage_mask: int, max_samples: int) -> None:
+    _check(lib().moe_profile_enable(stage_mask, max_samples))
+
+
+def moe_profile_read(stage: int, cap: int = 4096):
+    buf = (C.c_float * cap)()
+    n = lib().moe_profile_read(stage, buf, cap)
+    return [float(buf[i]) for i in range(n)]
 
 
 def alloc_buffers(s: Shape, n_chunks: int = 1, device="cuda:0", y_act: bool = False) -> Dict[str, torch.Tensor]:

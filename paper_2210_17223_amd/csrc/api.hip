@@ -30,6 +30,31 @@ moe_status hip_fail(hipError_t e, const char *what)
     return MOE_EHIP;
 }
 
+// ---- optional per-stage timing ------------------------------------------------
+namespace {
+struct Profiler {
+    uint32_t mask = 0;
+    int cap = 0;
+    int n[kNumStages] = {};
+    hipEvent_t *start[kNumStages] = {};
+    hipEvent_t *stop[kNumStages] = {};
+};
+Profiler g_prof;
+}  // namespace
+
+void prof_begin(int stage, hipStream_t st)
+{
+    if (!((g_prof.mask >> stage) & 1u) || g_prof.n[stage] >= g_prof.cap) return;
+    (void)hipEventRecord(g_prof.start[stage][g_prof.n[stage]], st);
+}
+
+void prof_end(int stage, hipStream_t st)
+{
+    if (!((g_prof.mask >> stage) & 1u) || g_prof.n[stage] >= g_prof.cap) return;
+    (void)hipEventRecord(g_prof.stop[stage][g_prof.n[stage]], st);
+    g_prof.n[stage] += 1;
+}
+
 namespace {
 
 int elem_bytes(const moe_shape &s) { return s.dtype == MOE_BF16 ? 2 : 4; }
@@ -99,6 +124,13 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
             set_error(#p " is not 16-byte aligned");                \
             return MOE_EINVAL;                                      \
         }                                                           \
+    } while (0)
+#define MOE_TIMED(stage, stream, expr)        \
+    do {                                     \
+        prof_begin(stage, stream);           \
+        moe_status st_ = (expr);             \
+        prof_end(stage, stream);             \
+        if (st_ != MOE_OK) return st_;       \
     } while (0)
 #define MOE_TRY(expr)                        \
     do {                                     \
@@ -223,6 +255,52 @@ size_t moe_workspace_bytes(const moe_shape *s, int32_t n_chunks)
 
 const char *moe_last_error(void) { return g_error; }
 
+moe_status moe_profile_enable(uint32_t stage_mask, int32_t max_samples)
+{
+    if (max_samples < 0 || stage_mask >= (1u << kNumStages)) {
+        set_error("moe_profile_enable: bad stage mask or sample count");
+        return MOE_EINVAL;
+    }
+    for (int st = 0; st < kNumStages; ++st) {
+        for (int i = 0; i < g_prof.cap; ++i) {
+            if (g_prof.start[st]) (void)hipEventDestroy(g_prof.start[st][i]);
+            if (g_prof.stop[st]) (void)hipEventDestroy(g_prof.stop[st][i]);
+        }
+        delete[] g_prof.start[st];
+        delete[] g_prof.stop[st];
+        g_prof.start[st] = g_prof.stop[st] = nullptr;
+        g_prof.n[st] = 0;
+    }
+    g_prof.mask = 0;
+    g_prof.cap = 0;
+    if (stage_mask == 0 || max_samples == 0) return MOE_OK;
+    for (int st = 0; st < kNumStages; ++st) {
+        if (!((stage_mask >> st) & 1u)) continue;
+        g_prof.start[st] = new hipEvent_t[max_samples];
+        g_prof.stop[st] = new hipEvent_t[max_samples];
+        for (int i = 0; i < max_samples; ++i) {
+            MOE_TRY_HIP(hipEventCreate(&g_prof.start[st][i]));
+            MOE_TRY_HIP(hipEventCreate(&g_prof.stop[st][i]));
+        }
+    }
+    g_prof.cap = max_samples;
+    g_prof.mask = stage_mask;
+    return MOE_OK;
+}
+
+int32_t moe_profile_read(int32_t stage, float *ms, int32_t cap)
+{
+    if (stage < 0 || stage >= kNumStages || ms == nullptr) return 0;
+    const int n = g_prof.n[stage] < cap ? g_prof.n[stage] : cap;
+    for (int i = 0; i < n; ++i) {
+        ms[i] = -1.0f;
+        if (hipEventSynchronize(g_prof.stop[stage][i]) != hipSuccess) continue;
+        (void)hipEventElapsedTime(&ms[i], g_prof.start[stage][i], g_prof.stop[stage][i]);
+    }
+    g_prof.n[stage] = 0;
+    return n;
+}
+
 size_t moe_packed_weight_bytes(const moe_shape *s)
 {
     if (check_common(s) != MOE_OK) return 0;
@@ -264,8 +342,9 @@ moe_status moe_route(const moe_shape *s, const void *x, const float *Wgp,
     MOE_REQUIRE_PTR(expert_idx);
     MOE_REQUIRE_PTR(gate);
     MOE_TRY(check_bias(*s, gate_bias, bias_token_stride));
-    return launch_route(*s, x, Wgp, gate_bias, bias_token_stride, expert_idx, gate,
-                        static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    MOE_TIMED(kStageRoute, st, launch_route(*s, x, Wgp, gate_bias, bias_token_stride, expert_idx, gate, st));
+    return MOE_OK;
 }
 
 moe_status moe_dispatch(const moe_shape *s, const void *x, const int32_t *expert_idx,
@@ -284,8 +363,9 @@ moe_status moe_dispatch(const moe_shape *s, const void *x, const int32_t *expert
     Workspace w;
     layout_workspace(*s, 1, workspace, &w);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    MOE_TRY(launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w, st));
-    return launch_scatter(*s, x, slot_of, xe, 0, s->T, st);
+    MOE_TIMED(kStagePlan, st, launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w, st));
+    MOE_TIMED(kStageScatter, st, launch_scatter(*s, x, slot_of, xe, 0, s->T, st));
+    return MOE_OK;
 }
 
 moe_status moe_expert_ffn(const moe_shape *s, const void *xe, const int32_t *offsets,
@@ -304,7 +384,7 @@ moe_status moe_expert_ffn(const moe_shape *s, const void *xe, const int32_t *off
     Workspace w;
     layout_workspace(*s, 1, workspace, &w);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    MOE_TRY(launch_tiles(*s, 1, offsets, nullptr, w, st));
+    MOE_TIMED(kStageTiles, st, launch_tiles(*s, 1, offsets, nullptr, w, st));
     return launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, 0, st);
 }
 
@@ -317,8 +397,9 @@ moe_status moe_combine(const moe_shape *s, const float *ye, const int32_t *slot_
     MOE_REQUIRE_PTR(gate);
     MOE_REQUIRE_PTR(y);
     MOE_OPTIONAL_PTR(y_act);
-    return launch_combine(*s, ye, slot_of, gate, y, y_act, 0, s->T,
-                          static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    MOE_TIMED(kStageCombine, st, launch_combine(*s, ye, slot_of, gate, y, y_act, 0, s->T, st));
+    return MOE_OK;
 }
 
 moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x,
@@ -358,14 +439,18 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
     layout_workspace(*s, n_chunks, workspace, &w);
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    MOE_TRY(launch_route(*s, x, Wgp, gate_bias, bias_token_stride, expert_idx, gate, st));
-    MOE_TRY(launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w, st));
-    MOE_TRY(launch_tiles(*s, n_chunks, offsets, src_of, w, st));
+    MOE_TIMED(kStageRoute, st,
+              launch_route(*s, x, Wgp, gate_bias, bias_token_stride, expert_idx, gate, st));
+    MOE_TIMED(kStagePlan, st,
+              launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w, st));
+    MOE_TIMED(kStageTiles, st, launch_tiles(*s, n_chunks, offsets, src_of, w, st));
 
     if (n_chunks == 1) {
-        MOE_TRY(launch_scatter(*s, x, slot_of, xe, 0, s->T, st));
+        MOE_TIMED(kStageScatter, st, launch_scatter(*s, x, slot_of, xe, 0, s->T, st));
         MOE_TRY(launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, 0, st));
-        return launch_combine(*s, ye, slot_of, gate, y, y_act, 0, s->T, st);
+        MOE_TIMED(kStageCombine, st,
+                  launch_combine(*s, ye, slot_of, gate, y, y_act, 0, s->T, st));
+        return MOE_OK;
     }
 
     // pack stream: chunk after chunk; caller's stream: expert FFN of a chunk once it
@@ -378,7 +463,7 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
     for (int c = 0; c < n_chunks; ++c) {
         const int t0 = static_cast<int>(static_cast<int64_t>(c) * s->T / n_chunks);
         const int t1 = static_cast<int>(static_cast<int64_t>(c + 1) * s->T / n_chunks);
-        MOE_TRY(launch_scatter(*s, x, slot_of, xe, t0, t1, r->pack));
+        MOE_TIMED(kStageScatter, r->pack, launch_scatter(*s, x, slot_of, xe, t0, t1, r->pack));
         MOE_TRY_HIP(hipEventRecord(r->packed[c], r->pack));
     }
     for (int c = 0; c < n_chunks; ++c) {
@@ -388,7 +473,8 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
         MOE_TRY(launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, c, st));
         MOE_TRY_HIP(hipEventRecord(r->computed[c], st));
         MOE_TRY_HIP(hipStreamWaitEvent(r->unpack, r->computed[c], 0));
-        MOE_TRY(launch_combine(*s, ye, slot_of, gate, y, y_act, t0, t1, r->unpack));
+        MOE_TIMED(kStageCombine, r->unpack,
+                  launch_combine(*s, ye, slot_of, gate, y, y_act, t0, t1, r->unpack));
     }
     MOE_TRY_HIP(hipEventRecord(r->unpacked, r->unpack));
     MOE_TRY_HIP(hipStreamWaitEvent(st, r->unpacked, 0));

@@ -51,6 +51,13 @@ struct Workspace {
 bool layout_workspace(const moe_shape &s, int n_chunks, void *base, Workspace *w);
 int ffn_tile_rows(const moe_shape &s);
 
+// Optional per-stage timing (moe_profile_enable): when a stage is enabled, its
+// launches are bracketed by a pair of timing events on the stream they run on.
+enum Stage { kStageRoute = 0, kStagePlan, kStageTiles, kStageScatter, kStageGemm1, kStageGemm2,
+             kStageCombine, kNumStages };
+void prof_begin(int stage, hipStream_t st);
+void prof_end(int stage, hipStream_t st);
+
 // ---- kernel launchers (each only enqueues on `st`) ---------------------------
 moe_status launch_route(const moe_shape &s, const void *x, const void *Wg,
                         const float *bias, int bias_stride, int32_t *expert_idx,

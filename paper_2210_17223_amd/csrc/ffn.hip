@@ -324,12 +324,16 @@ void launch_f32_pair(const moe_shape &s, const float *xe, const float *W1, const
     const RowTile *tiles = w.tiles + static_cast<size_t>(chunk) * w.max_tiles;
     const int32_t *nt = w.ntiles + chunk;
     float *H = static_cast<float *>(w.hidden);
+    prof_begin(kStageGemm1, st);
     hipLaunchKernelGGL(grouped_gemm_f32_kernel<ACT>,
                        dim3(w.max_tiles * ceil_div(s.d_ff, kF32Tile)), dim3(256), 0, st, xe, W1,
                        b1, H, tiles, nt, s.d_ff, s.d_model, w.max_tiles);
+    prof_end(kStageGemm1, st);
+    prof_begin(kStageGemm2, st);
     hipLaunchKernelGGL(grouped_gemm_f32_kernel<MOE_ACT_IDENTITY>,
                        dim3(w.max_tiles * ceil_div(s.d_model, kF32Tile)), dim3(256), 0, st, H, W2,
                        b2, ye, tiles, nt, s.d_model, s.d_ff, w.max_tiles);
+    prof_end(kStageGemm2, st);
 }
 
 template <int ACT>
@@ -342,11 +346,15 @@ void launch_mfma_pair(const moe_shape &s, const uint16_t *xe, const uint16_t *W1
     _Float16 *H = static_cast<_Float16 *>(w.hidden);
     const int g1 = static_cast<int>(align_up(static_cast<size_t>(w.max_tiles) * ceil_div(s.d_ff, kBN), 8));
     const int g2 = static_cast<int>(align_up(static_cast<size_t>(w.max_tiles) * ceil_div(s.d_model, kBN), 8));
+    prof_begin(kStageGemm1, st);
     hipLaunchKernelGGL((grouped_gemm_mfma_kernel<false, _Float16, ACT>), dim3(g1), dim3(256), 0, st,
                        xe, W1p, b1, H, tiles, nt, s.d_ff, s.d_model, w.max_tiles);
+    prof_end(kStageGemm1, st);
+    prof_begin(kStageGemm2, st);
     hipLaunchKernelGGL((grouped_gemm_mfma_kernel<true, float, MOE_ACT_IDENTITY>), dim3(g2),
                        dim3(256), 0, st, reinterpret_cast<const uint16_t *>(H), W2p, b2, ye, tiles,
                        nt, s.d_model, s.d_ff, w.max_tiles);
+    prof_end(kStageGemm2, st);
 }
 
 }  // namespace
