@@ -198,19 +198,17 @@ bool layout_workspace(const moe_shape &s, int n_chunks, void *base, Workspace *w
     const int64_t n = static_cast<int64_t>(s.T) * s.k;
     const int64_t max_rows = moe_max_rows(&s);
     w->nseg = static_cast<int32_t>((n + kSeg - 1) / kSeg);
-    w->tile_rows = ffn_tile_rows(s);
-    const int64_t chunk_tokens = (s.T + n_chunks - 1) / n_chunks;
-    int64_t chunk_rows = chunk_tokens * s.k;
-    if (chunk_rows > max_rows) chunk_rows = max_rows;
-    w->max_tiles = static_cast<int32_t>((chunk_rows + w->tile_rows - 1) / w->tile_rows + s.E);
     char *p = static_cast<char *>(base);
     size_t off = 0;
     w->seg_cnt = reinterpret_cast<int32_t *>(p + off);
     off += align_up(static_cast<size_t>(w->nseg) * kMaxExperts * sizeof(int32_t), 256);
-    w->tiles = reinterpret_cast<RowTile *>(p + off);
-    off += align_up(static_cast<size_t>(n_chunks) * w->max_tiles * sizeof(RowTile), 256);
-    w->ntiles = reinterpret_cast<int32_t *>(p + off);
-    off += align_up(static_cast<size_t>(n_chunks) * sizeof(int32_t), 256);
+    for (int g = 0; g < 2; ++g) {
+        w->gp[g] = choose_gemm_plan(s, g, n_chunks);
+        w->items[g] = reinterpret_cast<WorkItem *>(p + off);
+        off += align_up(static_cast<size_t>(n_chunks) * w->gp[g].max_items * sizeof(WorkItem), 256);
+        w->nitems[g] = reinterpret_cast<int32_t *>(p + off);
+        off += align_up(static_cast<size_t>(n_chunks) * sizeof(int32_t), 256);
+    }
     w->hidden = p + off;
     const size_t hidden_elem = s.dtype == MOE_BF16 ? 2 : 4;
     off += align_up(static_cast<size_t>(max_rows) * s.d_ff * hidden_elem, 256);

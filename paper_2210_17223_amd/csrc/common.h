@@ -28,28 +28,36 @@ moe_status hip_fail(hipError_t e, const char *what);
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// One row tile of the grouped GEMM: rows [row0, row1) of the expert-major buffer,
-// all owned by `expert`.
-struct RowTile {
+// One output tile of a grouped GEMM: rows [row0, row1) of the expert-major buffer, all
+// owned by `expert`, output columns [n0, n0 + tile width).
+struct WorkItem {
     int32_t expert;
     int32_t row0;
     int32_t row1;
-    int32_t pad;
+    int32_t n0;
 };
+
+// Tile shape and work-list bounds of one of the two expert GEMMs.
+struct GemmPlan {
+    int32_t bm, bn;          // rows / columns per output tile
+    int32_t tiles_n;         // column tiles
+    int32_t max_row_tiles;   // upper bound of row tiles per chunk
+    int32_t max_items;       // upper bound of work items per chunk
+    int32_t concurrent;      // work items in flight per XCD (sets the panel width)
+};
+GemmPlan choose_gemm_plan(const moe_shape &s, int which, int n_chunks);
 
 // Where each piece of the caller's workspace lives.
 struct Workspace {
-    int32_t *seg_cnt;    // [nseg][kMaxExperts] per-segment expert counts -> bases
-    RowTile *tiles;      // [n_chunks][max_tiles]
-    int32_t *ntiles;     // [n_chunks]
-    void *hidden;        // [max_rows][d_ff] hidden activations
+    int32_t *seg_cnt;      // [nseg][kMaxExperts] per-segment expert counts -> bases
+    WorkItem *items[2];    // per GEMM: [n_chunks][gp.max_items]
+    int32_t *nitems[2];    // per GEMM: [n_chunks]
+    void *hidden;          // [max_rows][d_ff] hidden activations
+    GemmPlan gp[2];
     int32_t nseg;
-    int32_t max_tiles;   // per chunk
-    int32_t tile_rows;   // rows per row tile of the FFN kernels
     size_t bytes;
 };
 bool layout_workspace(const moe_shape &s, int n_chunks, void *base, Workspace *w);
-int ffn_tile_rows(const moe_shape &s);
 
 // Optional per-stage timing (moe_profile_enable): when a stage is enabled, its
 // launches are bracketed by a pair of timing events on the stream they run on.

@@ -63,14 +63,12 @@ constexpr int kF32BK = 16;
 template <int ACT>
 __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
     const float *__restrict__ A, const float *__restrict__ B, const float *__restrict__ bias,
-    float *__restrict__ C, const RowTile *__restrict__ tiles,
-    const int32_t *__restrict__ ntiles, int N, int K, int max_tiles)
+    float *__restrict__ C, const WorkItem *__restrict__ items,
+    const int32_t *__restrict__ nitems, int N, int K)
 {
-    const int mt = blockIdx.x % max_tiles;
-    const int nt = blockIdx.x / max_tiles;
-    if (mt >= *ntiles) return;
-    const RowTile tile = tiles[mt];
-    const int n0 = nt * kF32Tile;
+    if (static_cast<int>(blockIdx.x) >= *nitems) return;
+    const WorkItem tile = items[blockIdx.x];
+    const int n0 = tile.n0;
 
     __shared__ float As[kF32BK][kF32Tile + 4];
     __shared__ float Bs[kF32BK][kF32Tile + 4];
@@ -127,13 +125,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
 }
 
 // ---------------------------------------------------------------- MFMA GEMM
-constexpr int kBM = 128;       // activation rows per block
-constexpr int kBN = 128;       // output columns (weight rows) per block
-constexpr int kBK = 64;        // contraction depth per LDS stage
-constexpr int kLd = kBK + 8;   // LDS row pitch in elements (16 bytes of padding)
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 template <bool F16>
-__device__ __forceinline__ f32x16 mfma_32x32x16(const uint4 &a, const uint4 &b, const f32x16 &c)
+__device__ __forceinline__ f32x16 mfma_32x32x16(const u32x4 &a, const u32x4 &b, const f32x16 &c)
 {
     if constexpr (F16)
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
@@ -159,119 +154,165 @@ __device__ __forceinline__ void store4(_Float16 *p, const float (&v)[4])
 
 // C[r, n] = act(sum_k A[r,k] W[e][n,k] + bias[e][n]);  A [rows, K], W [E, N, K],
 // 16-bit elements (bf16, or fp16 when F16), C [rows, N] of TOut.
-// 256 threads = 2 x 2 wavefronts, each owning a 64 x 64 patch = 2 x 2 MFMA tiles.
-template <bool F16, typename TOut, int ACT>
-__global__ __launch_bounds__(256) void grouped_gemm_mfma_kernel(
+// WM x WN wavefronts, each owning (TM*32) rows x (TN*32) columns of the block's
+// (WM*TM*32) x (WN*TN*32) output tile.  K is walked in stages of 64 through a
+// double-buffered LDS tile; the global loads of stage kt+2 are in flight while stage
+// kt is multiplied, and the barrier of a stage sits before its last 16-deep step so
+// that the MFMAs of that step cover the LDS latency of the next stage's first
+// fragments.  The work list (one entry per output tile) is ordered so that each XCD
+// walks a contiguous share of it: neighbouring blocks then reuse operand tiles in that
+// XCD's L2.  32-row sub-tiles past the end of a ragged row tile are skipped.
+template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN, bool KTAIL>
+__global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_mfma_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W,
-    const float *__restrict__ bias, TOut *__restrict__ C, const RowTile *__restrict__ tiles,
-    const int32_t *__restrict__ ntiles, int N, int K, int max_tiles)
+    const float *__restrict__ bias, TOut *__restrict__ C, const WorkItem *__restrict__ items,
+    const int32_t *__restrict__ nitems, int N, int K)
 {
-    // Blocks are dealt round-robin to the 8 XCDs; renumber them so that each XCD
-    // walks a contiguous range of tiles and neighbours share operands in its L2.
-    const int nb = gridDim.x;
-    const int lid = (blockIdx.x % 8) * (nb / 8) + blockIdx.x / 8;
-    const int mt = lid % max_tiles;
-    const int nt = lid / max_tiles;
-    if (mt >= *ntiles || nt * kBN >= N) return;
-    const RowTile tile = tiles[mt];
-    const int n0 = nt * kBN;
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64, LD = BK + 8;
+    constexpr int NT = 64 * WM * WN;
+    constexpr int AV = BM * 8 / NT, WV = BN * 8 / NT;   // 16-byte vectors per thread per stage
+    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile does not divide over the threads");
 
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][kBM][kLd];
-    __shared__ __attribute__((aligned(16))) uint16_t Ws[2][kBN][kLd];
+    const int total = *nitems;
+    const int per_xcd = (total + 7) / 8;
+    const int slot = blockIdx.x / 8;
+    const int item_idx = (blockIdx.x % 8) * per_xcd + slot;
+    if (slot >= per_xcd || item_idx >= total) return;
+    const WorkItem item = items[item_idx];
+    const int n0 = item.n0;
+    const int rows = item.row1 - item.row0;
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1;
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    constexpr int A_BUF = BM * LD, W_BUF = BN * LD;
+    uint16_t *As = smem;               // [2][BM][LD]
+    uint16_t *Ws = smem + 2 * A_BUF;   // [2][BN][LD]
 
-    // global -> LDS mapping: 1024 16-byte vectors per operand tile, 4 per thread
-    const uint16_t *a_src[4];
-    const uint16_t *w_src[4];
-    int ld_row[4], ld_col[4];
-    const uint16_t *Wexp = W + static_cast<size_t>(tile.expert) * N * K;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM;
+    const uint16_t *Wexp = W + static_cast<size_t>(item.expert) * N * K;
+
+    const uint16_t *a_src[AV];
+    const uint16_t *w_src[WV];
+    int a_off[AV], w_off[WV];
+    const int ld_col = (tid & 7) * 8;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int v = tid + 256 * q;
-        ld_row[q] = v >> 3;
-        ld_col[q] = (v & 7) * 8;
-        const int r = min(tile.row0 + ld_row[q], tile.row1 - 1);
-        const int n = min(n0 + ld_row[q], N - 1);
-        a_src[q] = A + static_cast<size_t>(r) * K + ld_col[q];
-        w_src[q] = Wexp + static_cast<size_t>(n) * K + ld_col[q];
+    for (int q = 0; q < AV; ++q) {
+        const int r = (tid + NT * q) >> 3;
+        a_off[q] = r * LD + ld_col;
+        a_src[q] = A + static_cast<size_t>(min(item.row0 + r, item.row1 - 1)) * K + ld_col;
     }
+#pragma unroll
+    for (int q = 0; q < WV; ++q) {
+        const int r = (tid + NT * q) >> 3;
+        w_off[q] = r * LD + ld_col;
+        w_src[q] = Wexp + static_cast<size_t>(min(n0 + r, N - 1)) * K + ld_col;
+    }
+    // 32-row sub-tiles of this wavefront that hold real rows
+    const int jact = min(TM, max(0, (rows - wm * TM * 32 + 31) / 32));
 
-    f32x16 acc[2][2];
+    f32x16 acc[TN][TM];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TM; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    uint4 a_reg[4], w_reg[4];
-#define MOE_LOAD_GLOBAL(k0)                                                              \
-    _Pragma("unroll") for (int q = 0; q < 4; ++q)                                        \
-    {                                                                                    \
-        if ((k0) + ld_col[q] < K) {                                                      \
-            a_reg[q] = *reinterpret_cast<const uint4 *>(a_src[q] + (k0));                \
-            w_reg[q] = *reinterpret_cast<const uint4 *>(w_src[q] + (k0));                \
-        } else {                                                                         \
-            a_reg[q].x = a_reg[q].y = a_reg[q].z = a_reg[q].w = 0u;                      \
-            w_reg[q].x = w_reg[q].y = w_reg[q].z = w_reg[q].w = 0u;                      \
-        }                                                                                \
+    u32x4 a_reg[AV], w_reg[WV];
+    u32x4 wf[2][TN], af[2][TM];
+    const int KT = (K + BK - 1) / BK;
+    const int fr = lane & 31, fk = (lane >> 5) * 8;
+    const int wfrag = (wn * TN * 32 + fr) * LD + fk;
+    const int afrag = (wm * TM * 32 + fr) * LD + fk;
+
+#define MOE_LOADG(kt_)                                                                          \
+    {                                                                                           \
+        const int k0_ = (kt_) * BK;                                                             \
+        const bool in_ = !KTAIL || k0_ + ld_col < K;                                           \
+        _Pragma("unroll") for (int q = 0; q < AV; ++q)                                          \
+        {                                                                                       \
+            if (in_) a_reg[q] = *reinterpret_cast<const u32x4 *>(a_src[q] + k0_);               \
+            else a_reg[q] = (u32x4){0u, 0u, 0u, 0u};                                            \
+        }                                                                                       \
+        _Pragma("unroll") for (int q = 0; q < WV; ++q)                                          \
+        {                                                                                       \
+            if (in_) w_reg[q] = *reinterpret_cast<const u32x4 *>(w_src[q] + k0_);               \
+            else w_reg[q] = (u32x4){0u, 0u, 0u, 0u};                                            \
+        }                                                                                       \
     }
-#define MOE_STORE_LDS(buf)                                                               \
-    _Pragma("unroll") for (int q = 0; q < 4; ++q)                                        \
-    {                                                                                    \
-        *reinterpret_cast<uint4 *>(&As[buf][ld_row[q]][ld_col[q]]) = a_reg[q];           \
-        *reinterpret_cast<uint4 *>(&Ws[buf][ld_row[q]][ld_col[q]]) = w_reg[q];           \
+#define MOE_STOREL(buf)                                                                         \
+    {                                                                                           \
+        _Pragma("unroll") for (int q = 0; q < AV; ++q)                                          \
+            *reinterpret_cast<u32x4 *>(As + (buf) * A_BUF + a_off[q]) = a_reg[q];               \
+        _Pragma("unroll") for (int q = 0; q < WV; ++q)                                          \
+            *reinterpret_cast<u32x4 *>(Ws + (buf) * W_BUF + w_off[q]) = w_reg[q];               \
+    }
+#define MOE_READF(slot_, buf, ks)                                                               \
+    {                                                                                           \
+        _Pragma("unroll") for (int i = 0; i < TN; ++i) wf[slot_][i] =                           \
+            *reinterpret_cast<const u32x4 *>(Ws + (buf) * W_BUF + wfrag + i * 32 * LD + (ks) * 16); \
+        _Pragma("unroll") for (int j = 0; j < TM; ++j) af[slot_][j] =                           \
+            *reinterpret_cast<const u32x4 *>(As + (buf) * A_BUF + afrag + j * 32 * LD + (ks) * 16); \
+    }
+#define MOE_MMA(slot_)                                                                          \
+    {                                                                                           \
+        _Pragma("unroll") for (int j = 0; j < TM; ++j)                                          \
+        {                                                                                       \
+            if (FULL || j < jact) {                                                             \
+                _Pragma("unroll") for (int i = 0; i < TN; ++i)                                  \
+                    acc[i][j] = mfma_32x32x16<F16>(wf[slot_][i], af[slot_][j], acc[i][j]);      \
+            }                                                                                   \
+        }                                                                                       \
+    }
+#define MOE_MAIN_LOOP                                                                           \
+    for (int kt = 0; kt < KT; ++kt) {                                                           \
+        const int buf = kt & 1;                                                                 \
+        const bool next1 = kt + 1 < KT, next2 = kt + 2 < KT;                                    \
+        if (next1) MOE_STOREL(buf ^ 1)                                                          \
+        if (next2) MOE_LOADG(kt + 2)                                                            \
+        MOE_READF(1, buf, 1)                                                                    \
+        MOE_MMA(0)                                                                              \
+        MOE_READF(0, buf, 2)                                                                    \
+        MOE_MMA(1)                                                                              \
+        MOE_READF(1, buf, 3)                                                                    \
+        MOE_MMA(0)                                                                              \
+        __syncthreads();                                                                        \
+        __builtin_amdgcn_sched_barrier(0);                                                      \
+        if (next1) MOE_READF(0, buf ^ 1, 0)                                                     \
+        MOE_MMA(1)                                                                              \
     }
 
-    const int KT = ceil_div(K, kBK);
-    MOE_LOAD_GLOBAL(0)
-    MOE_STORE_LDS(0)
+    MOE_LOADG(0)
+    MOE_STOREL(0)
+    if (KT > 1) MOE_LOADG(1)
     __syncthreads();
-    const int fr = lane & 31;            // fragment row inside a 32-row MFMA tile
-    const int fk = (lane >> 5) * 8;      // k offset of this lane's 8 elements
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) {
-            MOE_LOAD_GLOBAL((kt + 1) * kBK)
-        }
-#pragma unroll
-        for (int ks = 0; ks < kBK / 16; ++ks) {
-            uint4 wf[2], af[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                wf[i] = *reinterpret_cast<const uint4 *>(&Ws[buf][wn * 64 + i * 32 + fr][ks * 16 + fk]);
-                af[i] = *reinterpret_cast<const uint4 *>(&As[buf][wm * 64 + i * 32 + fr][ks * 16 + fk]);
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x16<F16>(wf[i], af[j], acc[i][j]);
-        }
-        if (kt + 1 < KT) {
-            MOE_STORE_LDS(buf ^ 1)
-        }
-        __syncthreads();
+    MOE_READF(0, 0, 0)
+    if (jact == TM) {          // every sub-tile of this wavefront holds rows: branch-free loop
+        constexpr bool FULL = true;
+        MOE_MAIN_LOOP
+    } else {
+        constexpr bool FULL = false;
+        MOE_MAIN_LOOP
     }
+#undef MOE_MAIN_LOOP
+#undef MOE_LOADG
+#undef MOE_STOREL
+#undef MOE_READF
+#undef MOE_MMA
 
-#undef MOE_LOAD_GLOBAL
-#undef MOE_STORE_LDS
-
-    // acc[i][j][4*g + c]: output column n0 + wn*64 + i*32 + 8*g + 4*(lane/32) + c,
-    //                     row tile.row0 + wm*64 + j*32 + lane%32
-    const float *bexp = bias != nullptr ? bias + static_cast<size_t>(tile.expert) * N : nullptr;
+    // acc[i][j][4*g + c]: column n0 + (wn*TN + i)*32 + 8*g + 4*(lane/32) + c,
+    //                     row item.row0 + (wm*TM + j)*32 + lane%32
+    const float *bexp = bias != nullptr ? bias + static_cast<size_t>(item.expert) * N : nullptr;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int r = tile.row0 + wm * 64 + j * 32 + fr;
-        if (r >= tile.row1) continue;
+    for (int j = 0; j < TM; ++j) {
+        const int r = item.row0 + (wm * TM + j) * 32 + fr;
+        if (r >= item.row1) continue;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < TN; ++i) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * 64 + i * 32 + 8 * g + 4 * (lane >> 5);
+                const int n = n0 + (wn * TN + i) * 32 + 8 * g + 4 * (lane >> 5);
                 if (n >= N) continue;
                 float v[4];
 #pragma unroll
@@ -321,19 +362,65 @@ void launch_f32_pair(const moe_shape &s, const float *xe, const float *W1, const
                      const float *W2, const float *b2, float *ye, const Workspace &w,
                      int chunk, hipStream_t st)
 {
-    const RowTile *tiles = w.tiles + static_cast<size_t>(chunk) * w.max_tiles;
-    const int32_t *nt = w.ntiles + chunk;
     float *H = static_cast<float *>(w.hidden);
+    const WorkItem *it1 = w.items[0] + static_cast<size_t>(chunk) * w.gp[0].max_items;
+    const WorkItem *it2 = w.items[1] + static_cast<size_t>(chunk) * w.gp[1].max_items;
     prof_begin(kStageGemm1, st);
-    hipLaunchKernelGGL(grouped_gemm_f32_kernel<ACT>,
-                       dim3(w.max_tiles * ceil_div(s.d_ff, kF32Tile)), dim3(256), 0, st, xe, W1,
-                       b1, H, tiles, nt, s.d_ff, s.d_model, w.max_tiles);
+    hipLaunchKernelGGL(grouped_gemm_f32_kernel<ACT>, dim3(w.gp[0].max_items), dim3(256), 0, st,
+                       xe, W1, b1, H, it1, w.nitems[0] + chunk, s.d_ff, s.d_model);
     prof_end(kStageGemm1, st);
     prof_begin(kStageGemm2, st);
-    hipLaunchKernelGGL(grouped_gemm_f32_kernel<MOE_ACT_IDENTITY>,
-                       dim3(w.max_tiles * ceil_div(s.d_model, kF32Tile)), dim3(256), 0, st, H, W2,
-                       b2, ye, tiles, nt, s.d_model, s.d_ff, w.max_tiles);
+    hipLaunchKernelGGL(grouped_gemm_f32_kernel<MOE_ACT_IDENTITY>, dim3(w.gp[1].max_items),
+                       dim3(256), 0, st, H, W2, b2, ye, it2, w.nitems[1] + chunk, s.d_model,
+                       s.d_ff);
     prof_end(kStageGemm2, st);
+}
+
+template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN, bool KTAIL>
+void launch_mfma_cfg_k(const uint16_t *A, const uint16_t *W, const float *bias, TOut *C,
+                     const WorkItem *items, const int32_t *nitems, int max_items, int N, int K,
+                     hipStream_t st)
+{
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr size_t lds = 2 * (BM + BN) * (64 + 8) * sizeof(uint16_t);
+    auto kern = grouped_gemm_mfma_kernel<F16, TOut, ACT, WM, WN, TM, TN, KTAIL>;
+    static bool configured = false;   // raising the dynamic LDS limit is needed once per kernel
+    if (!configured) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        configured = true;
+    }
+    const int grid = static_cast<int>(align_up(static_cast<size_t>(max_items), 8));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, st, A, W, bias, C, items, nitems,
+                       N, K);
+}
+
+// The contraction depth is a multiple of the 64-deep stage in every benchmark shape;
+// other depths take a variant that zero-fills the last stage.
+template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN>
+void launch_mfma_cfg(const uint16_t *A, const uint16_t *W, const float *bias, TOut *C,
+                     const WorkItem *items, const int32_t *nitems, int max_items, int N, int K,
+                     hipStream_t st)
+{
+    if (K % 64 == 0)
+        launch_mfma_cfg_k<F16, TOut, ACT, WM, WN, TM, TN, false>(A, W, bias, C, items, nitems,
+                                                                 max_items, N, K, st);
+    else
+        launch_mfma_cfg_k<F16, TOut, ACT, WM, WN, TM, TN, true>(A, W, bias, C, items, nitems,
+                                                                max_items, N, K, st);
+}
+
+template <bool F16, typename TOut, int ACT>
+void launch_mfma(const GemmPlan &gp, const uint16_t *A, const uint16_t *W, const float *bias,
+                 TOut *C, const WorkItem *items, const int32_t *nitems, int N, int K,
+                 hipStream_t st)
+{
+    if (gp.bm == 256)
+        launch_mfma_cfg<F16, TOut, ACT, 2, 4, 4, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, st);
+    else if (gp.bn == 256)
+        launch_mfma_cfg<F16, TOut, ACT, 2, 4, 2, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, st);
+    else
+        launch_mfma_cfg<F16, TOut, ACT, 2, 2, 2, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, st);
 }
 
 template <int ACT>
@@ -341,25 +428,51 @@ void launch_mfma_pair(const moe_shape &s, const uint16_t *xe, const uint16_t *W1
                       const float *b1, const uint16_t *W2p, const float *b2, float *ye,
                       const Workspace &w, int chunk, hipStream_t st)
 {
-    const RowTile *tiles = w.tiles + static_cast<size_t>(chunk) * w.max_tiles;
-    const int32_t *nt = w.ntiles + chunk;
     _Float16 *H = static_cast<_Float16 *>(w.hidden);
-    const int g1 = static_cast<int>(align_up(static_cast<size_t>(w.max_tiles) * ceil_div(s.d_ff, kBN), 8));
-    const int g2 = static_cast<int>(align_up(static_cast<size_t>(w.max_tiles) * ceil_div(s.d_model, kBN), 8));
+    const WorkItem *it1 = w.items[0] + static_cast<size_t>(chunk) * w.gp[0].max_items;
+    const WorkItem *it2 = w.items[1] + static_cast<size_t>(chunk) * w.gp[1].max_items;
     prof_begin(kStageGemm1, st);
-    hipLaunchKernelGGL((grouped_gemm_mfma_kernel<false, _Float16, ACT>), dim3(g1), dim3(256), 0, st,
-                       xe, W1p, b1, H, tiles, nt, s.d_ff, s.d_model, w.max_tiles);
+    launch_mfma<false, _Float16, ACT>(w.gp[0], xe, W1p, b1, H, it1, w.nitems[0] + chunk, s.d_ff,
+                                      s.d_model, st);
     prof_end(kStageGemm1, st);
     prof_begin(kStageGemm2, st);
-    hipLaunchKernelGGL((grouped_gemm_mfma_kernel<true, float, MOE_ACT_IDENTITY>), dim3(g2),
-                       dim3(256), 0, st, reinterpret_cast<const uint16_t *>(H), W2p, b2, ye, tiles,
-                       nt, s.d_model, s.d_ff, w.max_tiles);
+    launch_mfma<true, float, MOE_ACT_IDENTITY>(w.gp[1], reinterpret_cast<const uint16_t *>(H), W2p,
+                                               b2, ye, it2, w.nitems[1] + chunk, s.d_model,
+                                               s.d_ff, st);
     prof_end(kStageGemm2, st);
 }
 
 }  // namespace
 
-int ffn_tile_rows(const moe_shape &s) { return s.dtype == MOE_BF16 ? kBM : kF32Tile; }
+// Tile shape of expert GEMM `which` (0: xe.W1, 1: H.W2) for this layer shape.  Large
+// tiles cut the operand traffic per flop; they need enough output tiles to fill 256
+// compute units, and a long contraction to amortise their prologue and epilogue.
+GemmPlan choose_gemm_plan(const moe_shape &s, int which, int n_chunks)
+{
+    GemmPlan gp;
+    const int N = which == 0 ? s.d_ff : s.d_model;
+    const int K = which == 0 ? s.d_model : s.d_ff;
+    const int64_t max_rows = moe_max_rows(&s);
+    const int64_t chunk_tokens = (s.T + n_chunks - 1) / n_chunks;
+    const int64_t chunk_rows = chunk_tokens * s.k < max_rows ? chunk_tokens * s.k : max_rows;
+    if (s.dtype != MOE_BF16) {
+        gp.bm = gp.bn = kF32Tile;
+        gp.concurrent = 256;
+    } else {
+        const int64_t big_tiles = (chunk_rows / 256 + s.E / 2) * ((N + 255) / 256);
+        if (big_tiles >= 768) {
+            gp.bm = 256; gp.bn = 256; gp.concurrent = 32;
+        } else if (K >= 2048 && N >= 256) {
+            gp.bm = 128; gp.bn = 256; gp.concurrent = 32;
+        } else {
+            gp.bm = 128; gp.bn = 128; gp.concurrent = 64;
+        }
+    }
+    gp.tiles_n = (N + gp.bn - 1) / gp.bn;
+    gp.max_row_tiles = static_cast<int32_t>((chunk_rows + gp.bm - 1) / gp.bm + s.E);
+    gp.max_items = gp.max_row_tiles * gp.tiles_n;
+    return gp;
+}
 
 moe_status launch_ffn(const moe_shape &s, const void *xe, const void *W1p, const float *b1,
                       const void *W2p, const float *b2, float *ye, const Workspace &w,

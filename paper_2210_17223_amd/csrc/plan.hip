@@ -10,7 +10,7 @@
 //   plan_scan  : one block; exclusive scan over segments per expert, totals,
 //                capacity clamp, offsets
 //   plan_rank  : per-segment ranks -> slot_of / src_of
-//   plan_tiles : row tiles of the grouped GEMM per chunk (binary search in src_of)
+//   plan_items : work lists of the two expert GEMMs per chunk
 #include "common.h"
 
 namespace moe {
@@ -141,61 +141,91 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rank_kernel(
     }
 }
 
-// Row tiles of chunk c (block c): expert e's rows of the chunk are the slots whose
-// source assignment lies in [t0*k, t1*k); src_of ascends inside an expert, so both
-// ends are binary searches.  Lane e owns expert e.
-__global__ __launch_bounds__(kWave) void plan_tiles_kernel(
+// Work lists of the two expert GEMMs for chunk c (blockIdx.x) and GEMM g (blockIdx.y).
+// Expert e's rows of the chunk are the slots whose source assignment lies in
+// [t0*k, t1*k); src_of ascends inside an expert, so both ends are binary searches
+// (lane e of the first wavefront owns expert e).  Its rows are cut into row tiles of
+// equal height (a multiple of 32, at most gp.bm), and its output tiles are listed
+// panel by panel -- `concurrent / row_tiles` column tiles wide, row tiles inside -- so
+// that the blocks in flight on one XCD share both their weight and their activation
+// tiles.  Every thread then decodes list positions independently.
+__global__ __launch_bounds__(256) void plan_items_kernel(
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ src_of,
-    RowTile *__restrict__ tiles, int32_t *__restrict__ ntiles, int T, int k, int E,
-    int n_chunks, int tile_rows, int max_tiles)
+    WorkItem *__restrict__ items0, int32_t *__restrict__ nitems0, GemmPlan gp0,
+    WorkItem *__restrict__ items1, int32_t *__restrict__ nitems1, GemmPlan gp1, int T, int k,
+    int E, int n_chunks)
 {
+    __shared__ int32_t lo_s[kMaxExperts], hi_s[kMaxExperts], mt_s[kMaxExperts];
+    __shared__ int32_t cum_s[kMaxExperts + 1];
     const int c = blockIdx.x;
-    const int e = threadIdx.x;
-    const long t0 = static_cast<long>(c) * T / n_chunks;
-    const long t1 = static_cast<long>(c + 1) * T / n_chunks;
-    int lo = 0, hi = 0;
-    if (e < E) {
-        const int b = offsets[e], end = offsets[e + 1];
-        if (n_chunks == 1) {
-            lo = b;
-            hi = end;
-        } else {
-            const int keys[2] = {static_cast<int>(t0 * k), static_cast<int>(t1 * k)};
-            int res[2];
+    const GemmPlan gp = blockIdx.y == 0 ? gp0 : gp1;
+    WorkItem *items = (blockIdx.y == 0 ? items0 : items1) + static_cast<size_t>(c) * gp.max_items;
+    int32_t *nitems = blockIdx.y == 0 ? nitems0 : nitems1;
+
+    if (threadIdx.x < kWave) {
+        const int e = threadIdx.x;
+        const long t0 = static_cast<long>(c) * T / n_chunks;
+        const long t1 = static_cast<long>(c + 1) * T / n_chunks;
+        int lo = 0, hi = 0;
+        if (e < E) {
+            const int b = offsets[e], end = offsets[e + 1];
+            if (n_chunks == 1) {
+                lo = b;
+                hi = end;
+            } else {
+                const int keys[2] = {static_cast<int>(t0 * k), static_cast<int>(t1 * k)};
+                int res[2];
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                int l = b, r = end;             // first slot in [b,end) with src >= key
-                while (l < r) {
-                    const int m = (l + r) >> 1;
-                    if (src_of[m] < keys[q]) l = m + 1; else r = m;
+                for (int q = 0; q < 2; ++q) {
+                    int l = b, r = end;             // first slot in [b,end) with src >= key
+                    while (l < r) {
+                        const int m = (l + r) >> 1;
+                        if (src_of[m] < keys[q]) l = m + 1; else r = m;
+                    }
+                    res[q] = l;
                 }
-                res[q] = l;
+                lo = res[0];
+                hi = res[1];
             }
-            lo = res[0];
-            hi = res[1];
         }
-    }
-    const int mine = ceil_div(hi - lo, tile_rows);
-    // exclusive prefix sum over the 64 lanes
-    int incl = mine;
+        const int mt = ceil_div(hi - lo, gp.bm);
+        int incl = mt * gp.tiles_n;
 #pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int v = __shfl_up(incl, d);
-        if (e >= d) incl += v;
-    }
-    const int first = incl - mine;
-    RowTile *out = tiles + static_cast<size_t>(c) * max_tiles;
-    for (int q = 0; q < mine; ++q) {
-        if (first + q < max_tiles) {
-            RowTile rt;
-            rt.expert = e;
-            rt.row0 = lo + q * tile_rows;
-            rt.row1 = min(hi, lo + (q + 1) * tile_rows);
-            rt.pad = 0;
-            out[first + q] = rt;
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int v = __shfl_up(incl, d);
+            if (e >= d) incl += v;
         }
+        lo_s[e] = lo;
+        hi_s[e] = hi;
+        mt_s[e] = mt;
+        cum_s[e + 1] = incl;
+        if (e == 0) cum_s[0] = 0;
     }
-    if (e == kWave - 1) ntiles[c] = min(incl, max_tiles);
+    __syncthreads();
+    const int total = min(cum_s[kMaxExperts], gp.max_items);
+    if (blockIdx.z == 0 && threadIdx.x == 0) nitems[c] = total;
+    for (int L = blockIdx.z * blockDim.x + threadIdx.x; L < total; L += gridDim.z * blockDim.x) {
+        int e = 0;                                  // largest e with cum_s[e] <= L
+#pragma unroll
+        for (int step = kMaxExperts / 2; step > 0; step >>= 1)
+            if (cum_s[e + step] <= L) e += step;
+        const int l = L - cum_s[e];
+        const int mt = mt_s[e];
+        const int gn = min(gp.tiles_n, max(1, gp.concurrent / mt));
+        const int panel = l / (mt * gn);
+        const int within = l - panel * (mt * gn);
+        const int width = min(gn, gp.tiles_n - panel * gn);
+        const int m = within / width;
+        const int nt = panel * gn + within % width;
+        const int rows = hi_s[e] - lo_s[e];
+        const int per_tile = min(gp.bm, ceil_div(ceil_div(rows, mt), 32) * 32);
+        WorkItem it;
+        it.expert = e;
+        it.row0 = lo_s[e] + m * per_tile;
+        it.row1 = min(hi_s[e], it.row0 + per_tile);
+        it.n0 = nt * gp.bn;
+        items[L] = it;
+    }
 }
 
 }  // namespace
@@ -219,9 +249,9 @@ moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *c
 moe_status launch_tiles(const moe_shape &s, int n_chunks, const int32_t *offsets,
                         const int32_t *src_of, const Workspace &w, hipStream_t st)
 {
-    hipLaunchKernelGGL(plan_tiles_kernel, dim3(n_chunks), dim3(kWave), 0, st, offsets,
-                       src_of, w.tiles, w.ntiles, s.T, s.k, s.E, n_chunks, w.tile_rows,
-                       w.max_tiles);
+    hipLaunchKernelGGL(plan_items_kernel, dim3(n_chunks, 2, 8), dim3(256), 0, st, offsets, src_of,
+                       w.items[0], w.nitems[0], w.gp[0], w.items[1], w.nitems[1], w.gp[1], s.T,
+                       s.k, s.E, n_chunks);
     MOE_TRY_HIP(hipGetLastError());
     return MOE_OK;
 }
