@@ -1,0 +1,131 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+Integers (expert choice, counts, offsets, slots, sources) are compared in full and
+bit-exactly; packed rows in full and bit-exactly; layer outputs on sampled tokens the
+oracle computes one by one (random tokens plus the tokens with the largest gate weights,
+where the error bound is tightest), plus properties that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from gpu_util import DeviceLayer, assert_ints_equal, download, rel_rms_err, shape_of, upload
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+
+
+def oracle_routing(li):
+    z = oracle.gate_logits(li.x, li.Wg, li.gate_bias, li.bias_token_stride)
+    idx, gate = oracle.topk_softmax(z, li.k)
+    count, off, slot_of, src_of = oracle.plan(idx, li.E, li.C)
+    return idx, gate, count, off, slot_of, src_of
+
+
+def sample_tokens(li, gate, n_random=768, n_top=256, seed=123):
+    rng = np.random.default_rng(seed)
+    rnd = rng.choice(li.T, size=min(n_random, li.T), replace=False)
+    top = np.argsort(-gate.max(1))[:n_top]
+    return np.unique(np.concatenate([rnd, top])).astype(np.int32)
+
+
+@pytest.mark.parametrize("name,chunk_list", [("gpt2s_moe", (1,)), ("skewed", (1,)),
+                                             ("large_chunked", (1, 4, 8))])
+def test_full_size_layer(name, chunk_list):
+    li = wl.make_layer(wl.CONFIGS[name], seed=0, threads=16)
+    idx, gate, count, off, slot_of, src_of = oracle_routing(li)
+    A = int(off[-1])
+    toks = sample_tokens(li, gate)
+    o = oracle.moe_layer(li.x, li.Wg, li.W1, li.W2, k=li.k, capacity=li.C, bias=li.gate_bias,
+                         bias_stride=li.bias_token_stride, tokens=toks)
+    assert np.array_equal(o.slot_of, slot_of)
+    rms = float(np.sqrt(np.mean(np.square(o.y.astype(np.float64)))))
+    fully_dropped = (slot_of.reshape(li.T, li.k) < 0).all(1)
+
+    s = shape_of(li)
+    L = DeviceLayer(li, s, n_chunks=max(chunk_list))
+    li.W1 = li.W2 = None                     # the device holds the packed copies now
+    ref_bits = None
+    for n_chunks in chunk_list:
+        L.b["y"].fill_(float("nan"))
+        L.b["xe"].zero_()
+        L.layer(n_chunks)
+        assert_ints_equal(L.ints(), o)
+        np.testing.assert_allclose(L.b["gate"].cpu().numpy().reshape(li.T, li.k), gate, rtol=1e-6)
+        xe = download(L.b["xe"]).reshape(-1, li.d)
+        assert np.array_equal(xe[:A].view(np.uint32), li.x[src_of // li.k].view(np.uint32))
+        y = L.b["y"].cpu().numpy().reshape(li.T, li.d)
+        assert np.isfinite(y).all()
+        err = float(np.abs(y[toks].astype(np.float64) - o.y).max() / rms)
+        assert err <= TOL_BF16, f"{name} n_chunks={n_chunks}: max-abs err / RMS = {err}"
+        assert not y[fully_dropped].any()                 # dropped tokens give zeros
+        if ref_bits is None:
+            ref_bits = y.view(np.uint32).copy()
+        else:                                              # chunking changes no output bit
+            assert np.array_equal(y.view(np.uint32), ref_bits), f"n_chunks={n_chunks}"
+    if name == "skewed":
+        assert (slot_of < 0).mean() > 0.4                  # the Zipf bias really overflows
+        assert count.max() > li.C > count.min()
+
+
+def canon(expert_idx, slot_of, gate, T, k):
+    """Per-token (expert, slot, gate) triples sorted by expert: what is unique about a
+    token's routing when the order of its two choices is a near-tie."""
+    e = expert_idx.reshape(T, k)
+    order = np.argsort(e, axis=1, kind="stable")
+    take = lambda a: np.take_along_axis(a.reshape(T, k), order, 1)
+    return take(e), take(slot_of), take(gate)
+
+
+def test_inference_stack():
+    cfg = wl.CONFIGS["infer_stack"]
+    layers = wl.make_stack(cfg, seed=0, threads=16)
+    T, d, E, k = cfg["T"], cfg["d"], cfg["E"], cfg["k"]
+
+    # oracle chain: layer l+1 reads layer l's output rounded to the activation dtype
+    x_l = layers[0].x
+    oracle_in, oracle_out = [], []
+    for li in layers:
+        li.x = x_l
+        o = oracle.moe_layer(li.x, li.Wg, li.W1, li.W2, k=k, capacity=li.C, bias=li.gate_bias,
+                             bias_stride=li.bias_token_stride)
+        # the bias decides which two experts, the gate only their order
+        assert np.array_equal(np.sort(o.expert_idx, 1), np.sort(li.forced_experts, 1))
+        assert (o.slot_of >= 0).all()
+        oracle_in.append(x_l)
+        oracle_out.append(o)
+        x_l = wl.bf16_round(o.y)
+
+    s = shape_of(layers[0])
+    dev = []
+    for li in layers:
+        dev.append(DeviceLayer(li, s, y_act=True))
+        li.W1 = li.W2 = None
+
+    # (a) every layer on the oracle chain's input: bit-exact routing, toleranced output
+    for l, (L, o) in enumerate(zip(dev, oracle_out)):
+        L.x = upload(oracle_in[l], "bf16")
+        L.layer(1)
+        assert_ints_equal(L.ints(), o)
+        y = L.b["y"].cpu().numpy().reshape(T, d)
+        assert rel_rms_err(y, o.y) <= TOL_BF16, f"layer {l}"
+        y_act = download(L.b["y_act"]).reshape(T, d)
+        assert np.array_equal(y_act.view(np.uint32), wl.bf16_round(y).view(np.uint32))
+
+    # (b) the free-running stack on the device: layer l+1 reads layer l's y_act
+    x_dev = upload(oracle_in[0], "bf16")
+    for l, (L, o) in enumerate(zip(dev, oracle_out)):
+        L.x = x_dev
+        L.layer(1)
+        got = L.ints()
+        assert np.array_equal(got["count"], o.count) and np.array_equal(got["off"], o.off)
+        ge, gs, gg = canon(got["expert_idx"], got["slot_of"], L.b["gate"].cpu().numpy(), T, k)
+        we, ws, wg = canon(o.expert_idx, o.slot_of, o.gate, T, k)
+        assert np.array_equal(ge, we) and np.array_equal(gs, ws)
+        # the two chains' inputs differ by accumulated rounding, and a gate weight is a
+        # softmax of logits: compare it absolutely
+        np.testing.assert_allclose(gg, wg, rtol=0, atol=3e-2)
+        y = L.b["y"].cpu().numpy().reshape(T, d)
+        assert rel_rms_err(y, o.y) <= TOL_BF16 * (l + 1), f"layer {l}"
+        x_dev = L.b["y_act"].view(T, d)
