@@ -197,7 +197,8 @@ bool layout_workspace(const moe_shape &s, int n_chunks, void *base, Workspace *w
     if (n_chunks < 1 || n_chunks > kMaxChunks) return false;
     const int64_t n = static_cast<int64_t>(s.T) * s.k;
     const int64_t max_rows = moe_max_rows(&s);
-    w->nseg = static_cast<int32_t>((n + kSeg - 1) / kSeg);
+    (void)n;
+    w->nseg = (s.T + kSegTok - 1) / kSegTok;
     char *p = static_cast<char *>(base);
     size_t off = 0;
     w->seg_cnt = reinterpret_cast<int32_t *>(p + off);
@@ -341,7 +342,8 @@ moe_status moe_route(const moe_shape *s, const void *x, const float *Wgp,
     MOE_REQUIRE_PTR(gate);
     MOE_TRY(check_bias(*s, gate_bias, bias_token_stride));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    MOE_TIMED(kStageRoute, st, launch_route(*s, x, Wgp, gate_bias, bias_token_stride, expert_idx, gate, st));
+    MOE_TIMED(kStageRoute, st, launch_route(*s, x, Wgp, gate_bias, bias_token_stride, expert_idx,
+                                            gate, nullptr, st));
     return MOE_OK;
 }
 
@@ -361,7 +363,8 @@ moe_status moe_dispatch(const moe_shape *s, const void *x, const int32_t *expert
     Workspace w;
     layout_workspace(*s, 1, workspace, &w);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    MOE_TIMED(kStagePlan, st, launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w, st));
+    MOE_TIMED(kStagePlan, st, launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w,
+                                          false, 0, st));
     MOE_TIMED(kStageScatter, st, launch_scatter(*s, x, slot_of, xe, 0, s->T, st));
     return MOE_OK;
 }
@@ -382,7 +385,7 @@ moe_status moe_expert_ffn(const moe_shape *s, const void *xe, const int32_t *off
     Workspace w;
     layout_workspace(*s, 1, workspace, &w);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    MOE_TIMED(kStageTiles, st, launch_tiles(*s, 1, offsets, nullptr, w, st));
+    MOE_TIMED(kStageTiles, st, launch_items(*s, 1, offsets, nullptr, w, st));
     return launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, 0, st);
 }
 
@@ -438,10 +441,12 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     MOE_TIMED(kStageRoute, st,
-              launch_route(*s, x, Wgp, gate_bias, bias_token_stride, expert_idx, gate, st));
+              launch_route(*s, x, Wgp, gate_bias, bias_token_stride, expert_idx, gate,
+                           w.seg_cnt, st));
     MOE_TIMED(kStagePlan, st,
-              launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w, st));
-    MOE_TIMED(kStageTiles, st, launch_tiles(*s, n_chunks, offsets, src_of, w, st));
+              launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w, true, n_chunks, st));
+    if (n_chunks > 1)
+        MOE_TIMED(kStageTiles, st, launch_items(*s, n_chunks, offsets, src_of, w, st));
 
     if (n_chunks == 1) {
         MOE_TIMED(kStageScatter, st, launch_scatter(*s, x, slot_of, xe, 0, s->T, st));

@@ -12,7 +12,7 @@ namespace moe {
 constexpr int kWave = 64;          // wavefront width on CDNA
 constexpr int kMaxExperts = 64;    // one ballot bit / one lane per expert
 constexpr int kMaxTopK = 8;
-constexpr int kSeg = 512;          // assignments ranked by one wavefront in the plan
+constexpr int kSegTok = 64;        // tokens per plan segment = tokens per gate block
 constexpr int kMaxChunks = 64;
 
 // ---- host side -------------------------------------------------------------
@@ -67,13 +67,17 @@ void prof_begin(int stage, hipStream_t st);
 void prof_end(int stage, hipStream_t st);
 
 // ---- kernel launchers (each only enqueues on `st`) ---------------------------
+// when seg_cnt is not NULL the per-segment expert histogram of the dispatch plan is
+// produced in the same pass
 moe_status launch_route(const moe_shape &s, const void *x, const void *Wg,
                         const float *bias, int bias_stride, int32_t *expert_idx,
-                        float *gate, hipStream_t st);
+                        float *gate, int32_t *seg_cnt, hipStream_t st);
+// counted = the per-segment histogram is already in w.seg_cnt (launch_route made it);
+// n_chunks == 1 also builds the GEMM work lists (otherwise launch_items does, after the ranks)
 moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *counts,
                        int32_t *offsets, int32_t *slot_of, int32_t *src_of,
-                       const Workspace &w, hipStream_t st);
-moe_status launch_tiles(const moe_shape &s, int n_chunks, const int32_t *offsets,
+                       const Workspace &w, bool counted, int n_chunks, hipStream_t st);
+moe_status launch_items(const moe_shape &s, int n_chunks, const int32_t *offsets,
                         const int32_t *src_of, const Workspace &w, hipStream_t st);
 moe_status launch_scatter(const moe_shape &s, const void *x, const int32_t *slot_of,
                           void *xe, int t0, int t1, hipStream_t st);

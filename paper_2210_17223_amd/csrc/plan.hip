@@ -2,13 +2,14 @@
 // exclusive scan, slot of every assignment -- the layout of the expert-major
 // buffer that the first all-to-all would carry (paper, end of Sec. 2.1).
 //
-// Integer work only.  A wavefront ranks a segment of kSeg consecutive assignments,
-// 64 at a time: lanes that chose the same expert find each other with six ballots
-// (one per bit of the expert index), the rank inside the 64 is a popcount of the
-// lower lanes, and the running per-expert count lives in LDS.
-//   plan_count : per-segment expert histograms
+// Integer work only.  A wavefront ranks one segment (the assignments of kSegTok
+// consecutive tokens), 64 at a time: lanes that chose the same expert find each other
+// with six ballots (one per bit of the expert index), the rank inside the 64 is a
+// popcount of the lower lanes, and the running per-expert count lives in LDS.
+//   plan_count : per-segment expert histograms (the layer call gets them from the
+//                gate's top-k kernel instead)
 //   plan_scan  : one block; exclusive scan over segments per expert, totals,
-//                capacity clamp, offsets
+//                capacity clamp, offsets; for an unchunked layer also the work lists
 //   plan_rank  : per-segment ranks -> slot_of / src_of
 //   plan_items : work lists of the two expert GEMMs per chunk
 #include "common.h"
@@ -42,8 +43,14 @@ __device__ __forceinline__ int clamp_expert(int e, int E)
     return static_cast<unsigned>(e) < static_cast<unsigned>(E) ? e : E - 1;
 }
 
+__device__ void build_items(const GemmPlan &gp, WorkItem *__restrict__ items,
+                            int32_t *__restrict__ nitems_out, const int32_t *lo_s,
+                            const int32_t *hi_s, int32_t *mt_s, int32_t *cum_s, int part,
+                            int nparts);
+
 __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(
-    const int32_t *__restrict__ expert_idx, int32_t *__restrict__ seg_cnt, int n, int E)
+    const int32_t *__restrict__ expert_idx, int32_t *__restrict__ seg_cnt, int n, int E,
+    int seg_len)
 {
     __shared__ int32_t run[kPlanWaves][kMaxExperts];
     const int lane = lane_id();
@@ -51,10 +58,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(
     const int seg = blockIdx.x * kPlanWaves + wave;
     run[wave][lane] = 0;
     __builtin_amdgcn_wave_barrier();
-    const int base = seg * kSeg;
-    for (int off = 0; off < kSeg; off += kWave) {
+    const int base = seg * seg_len;
+    for (int off = 0; off < seg_len; off += kWave) {
         const int i = base + off + lane;
-        const bool valid = i < n;
+        const bool valid = i < n && off + lane < seg_len;
         const int e = valid ? clamp_expert(expert_idx[i], E) : 0;
         const uint64_t peers = same_expert_lanes(e, valid);
         const bool leader = valid && (peers & lanes_below(lane)) == 0;
@@ -68,10 +75,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(
 // assignments to e in all earlier segments.
 __global__ __launch_bounds__(1024) void plan_scan_kernel(
     int32_t *__restrict__ seg_cnt, int32_t *__restrict__ counts,
-    int32_t *__restrict__ offsets, int nseg, int E, int capacity)
+    int32_t *__restrict__ offsets, int nseg, int E, int capacity, int with_items,
+    WorkItem *__restrict__ items0, int32_t *__restrict__ nitems0, GemmPlan gp0,
+    WorkItem *__restrict__ items1, int32_t *__restrict__ nitems1, GemmPlan gp1)
 {
     __shared__ int32_t gsum[16][kMaxExperts];
     __shared__ int32_t kept[kMaxExperts];
+    __shared__ int32_t lo_s[kMaxExperts], hi_s[kMaxExperts], mt_s[kMaxExperts];
+    __shared__ int32_t cum_s[kMaxExperts + 1];
     const int e = threadIdx.x % kMaxExperts;
     const int g = threadIdx.x / kMaxExperts;
     const int per = ceil_div(nseg, 16);
@@ -98,33 +109,43 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(
         kept[e] = e < E ? min(total, capacity) : 0;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int32_t acc = 0;
-        for (int ee = 0; ee < E; ++ee) {
-            offsets[ee] = acc;
-            acc += kept[ee];
+    if (threadIdx.x < kWave) {                      // exclusive scan of kept[] by one wavefront
+        const int ee = threadIdx.x;
+        int incl = kept[ee];
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int v = __shfl_up(incl, d);
+            if (ee >= d) incl += v;
         }
-        offsets[E] = acc;
+        lo_s[ee] = incl - kept[ee];
+        hi_s[ee] = incl;
+        if (ee < E) offsets[ee] = incl - kept[ee];
+        if (ee == E - 1) offsets[E] = incl;
+    }
+    __syncthreads();
+    if (with_items) {
+        build_items(gp0, items0, nitems0, lo_s, hi_s, mt_s, cum_s, 0, 1);
+        build_items(gp1, items1, nitems1, lo_s, hi_s, mt_s, cum_s, 0, 1);
     }
 }
 
 __global__ __launch_bounds__(kPlanThreads) void plan_rank_kernel(
     const int32_t *__restrict__ expert_idx, const int32_t *__restrict__ seg_base,
     const int32_t *__restrict__ offsets, int32_t *__restrict__ slot_of,
-    int32_t *__restrict__ src_of, int n, int E, int capacity)
+    int32_t *__restrict__ src_of, int n, int E, int capacity, int seg_len)
 {
     __shared__ int32_t run[kPlanWaves][kMaxExperts];
     __shared__ int32_t off_s[kMaxExperts];
     const int lane = lane_id();
     const int wave = threadIdx.x / kWave;
     const int seg = blockIdx.x * kPlanWaves + wave;
-    const int base = seg * kSeg;
+    const int base = seg * seg_len;
     if (threadIdx.x < kMaxExperts) off_s[threadIdx.x] = threadIdx.x < E ? offsets[threadIdx.x] : 0;
     run[wave][lane] = base < n ? seg_base[static_cast<size_t>(seg) * kMaxExperts + lane] : 0;
     __syncthreads();
-    for (int off = 0; off < kSeg; off += kWave) {
+    for (int off = 0; off < seg_len; off += kWave) {
         const int i = base + off + lane;
-        const bool valid = i < n;
+        const bool valid = i < n && off + lane < seg_len;
         const int e = valid ? clamp_expert(expert_idx[i], E) : 0;
         const uint64_t peers = same_expert_lanes(e, valid);
         const int rank = __popcll(peers & lanes_below(lane));
@@ -141,14 +162,61 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rank_kernel(
     }
 }
 
-// Work lists of the two expert GEMMs for chunk c (blockIdx.x) and GEMM g (blockIdx.y).
-// Expert e's rows of the chunk are the slots whose source assignment lies in
-// [t0*k, t1*k); src_of ascends inside an expert, so both ends are binary searches
-// (lane e of the first wavefront owns expert e).  Its rows are cut into row tiles of
-// equal height (a multiple of 32, at most gp.bm), and its output tiles are listed
-// panel by panel -- `concurrent / row_tiles` column tiles wide, row tiles inside -- so
-// that the blocks in flight on one XCD share both their weight and their activation
-// tiles.  Every thread then decodes list positions independently.
+// Work list of one expert GEMM from the per-expert row ranges [lo_s[e], hi_s[e]) held in
+// LDS (entries at or beyond E are empty).  An expert's rows are cut into row tiles of equal
+// height (a multiple of 32, at most gp.bm), and its output tiles are listed panel by panel --
+// `concurrent / row_tiles` column tiles wide, row tiles inside -- so that the blocks in
+// flight on one XCD share both their weight and their activation tiles.  Called by every
+// thread of the block; part `part` of `nparts` blocks emits its share of the entries.
+__device__ void build_items(const GemmPlan &gp, WorkItem *__restrict__ items,
+                            int32_t *__restrict__ nitems_out, const int32_t *lo_s,
+                            const int32_t *hi_s, int32_t *mt_s, int32_t *cum_s, int part,
+                            int nparts)
+{
+    if (threadIdx.x < kWave) {
+        const int e = threadIdx.x;
+        const int mt = ceil_div(hi_s[e] - lo_s[e], gp.bm);
+        int incl = mt * gp.tiles_n;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int v = __shfl_up(incl, d);
+            if (e >= d) incl += v;
+        }
+        mt_s[e] = mt;
+        cum_s[e + 1] = incl;
+        if (e == 0) cum_s[0] = 0;
+    }
+    __syncthreads();
+    const int total = min(cum_s[kMaxExperts], gp.max_items);
+    if (part == 0 && threadIdx.x == 0) *nitems_out = total;
+    for (int L = part * blockDim.x + threadIdx.x; L < total; L += nparts * blockDim.x) {
+        int e = 0;                                  // largest e with cum_s[e] <= L
+#pragma unroll
+        for (int step = kMaxExperts / 2; step > 0; step >>= 1)
+            if (cum_s[e + step] <= L) e += step;
+        const int l = L - cum_s[e];
+        const int mt = mt_s[e];
+        const int gn = min(gp.tiles_n, max(1, gp.concurrent / mt));
+        const int panel = l / (mt * gn);
+        const int within = l - panel * (mt * gn);
+        const int width = min(gn, gp.tiles_n - panel * gn);
+        const int m = within / width;
+        const int nt = panel * gn + within % width;
+        const int rows = hi_s[e] - lo_s[e];
+        const int per_tile = min(gp.bm, ceil_div(ceil_div(rows, mt), 32) * 32);
+        WorkItem it;
+        it.expert = e;
+        it.row0 = lo_s[e] + m * per_tile;
+        it.row1 = min(hi_s[e], it.row0 + per_tile);
+        it.n0 = nt * gp.bn;
+        items[L] = it;
+    }
+    __syncthreads();
+}
+
+// Work lists for chunk c (blockIdx.x) and GEMM g (blockIdx.y).  Expert e's rows of the chunk
+// are the slots whose source assignment lies in [t0*k, t1*k); src_of ascends inside an
+// expert, so both ends are binary searches (lane e of the first wavefront owns expert e).
 __global__ __launch_bounds__(256) void plan_items_kernel(
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ src_of,
     WorkItem *__restrict__ items0, int32_t *__restrict__ nitems0, GemmPlan gp0,
@@ -160,7 +228,7 @@ __global__ __launch_bounds__(256) void plan_items_kernel(
     const int c = blockIdx.x;
     const GemmPlan gp = blockIdx.y == 0 ? gp0 : gp1;
     WorkItem *items = (blockIdx.y == 0 ? items0 : items1) + static_cast<size_t>(c) * gp.max_items;
-    int32_t *nitems = blockIdx.y == 0 ? nitems0 : nitems1;
+    int32_t *nitems = (blockIdx.y == 0 ? nitems0 : nitems1) + c;
 
     if (threadIdx.x < kWave) {
         const int e = threadIdx.x;
@@ -188,65 +256,36 @@ __global__ __launch_bounds__(256) void plan_items_kernel(
                 hi = res[1];
             }
         }
-        const int mt = ceil_div(hi - lo, gp.bm);
-        int incl = mt * gp.tiles_n;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int v = __shfl_up(incl, d);
-            if (e >= d) incl += v;
-        }
         lo_s[e] = lo;
         hi_s[e] = hi;
-        mt_s[e] = mt;
-        cum_s[e + 1] = incl;
-        if (e == 0) cum_s[0] = 0;
     }
     __syncthreads();
-    const int total = min(cum_s[kMaxExperts], gp.max_items);
-    if (blockIdx.z == 0 && threadIdx.x == 0) nitems[c] = total;
-    for (int L = blockIdx.z * blockDim.x + threadIdx.x; L < total; L += gridDim.z * blockDim.x) {
-        int e = 0;                                  // largest e with cum_s[e] <= L
-#pragma unroll
-        for (int step = kMaxExperts / 2; step > 0; step >>= 1)
-            if (cum_s[e + step] <= L) e += step;
-        const int l = L - cum_s[e];
-        const int mt = mt_s[e];
-        const int gn = min(gp.tiles_n, max(1, gp.concurrent / mt));
-        const int panel = l / (mt * gn);
-        const int within = l - panel * (mt * gn);
-        const int width = min(gn, gp.tiles_n - panel * gn);
-        const int m = within / width;
-        const int nt = panel * gn + within % width;
-        const int rows = hi_s[e] - lo_s[e];
-        const int per_tile = min(gp.bm, ceil_div(ceil_div(rows, mt), 32) * 32);
-        WorkItem it;
-        it.expert = e;
-        it.row0 = lo_s[e] + m * per_tile;
-        it.row1 = min(hi_s[e], it.row0 + per_tile);
-        it.n0 = nt * gp.bn;
-        items[L] = it;
-    }
+    build_items(gp, items, nitems, lo_s, hi_s, mt_s, cum_s, blockIdx.z, gridDim.z);
 }
 
 }  // namespace
 
 moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *counts,
                        int32_t *offsets, int32_t *slot_of, int32_t *src_of,
-                       const Workspace &w, hipStream_t st)
+                       const Workspace &w, bool counted, int n_chunks, hipStream_t st)
 {
     const int n = s.T * s.k;
+    const int seg_len = kSegTok * s.k;
     const int blocks = ceil_div(w.nseg, kPlanWaves);
-    hipLaunchKernelGGL(plan_count_kernel, dim3(blocks), dim3(kPlanThreads), 0, st,
-                       expert_idx, w.seg_cnt, n, s.E);
+    if (!counted)
+        hipLaunchKernelGGL(plan_count_kernel, dim3(blocks), dim3(kPlanThreads), 0, st,
+                           expert_idx, w.seg_cnt, n, s.E, seg_len);
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, w.seg_cnt, counts,
-                       offsets, w.nseg, s.E, s.capacity);
+                       offsets, w.nseg, s.E, s.capacity, n_chunks == 1 ? 1 : 0, w.items[0],
+                       w.nitems[0], w.gp[0], w.items[1], w.nitems[1], w.gp[1]);
     hipLaunchKernelGGL(plan_rank_kernel, dim3(blocks), dim3(kPlanThreads), 0, st,
-                       expert_idx, w.seg_cnt, offsets, slot_of, src_of, n, s.E, s.capacity);
+                       expert_idx, w.seg_cnt, offsets, slot_of, src_of, n, s.E, s.capacity,
+                       seg_len);
     MOE_TRY_HIP(hipGetLastError());
     return MOE_OK;
 }
 
-moe_status launch_tiles(const moe_shape &s, int n_chunks, const int32_t *offsets,
+moe_status launch_items(const moe_shape &s, int n_chunks, const int32_t *offsets,
                         const int32_t *src_of, const Workspace &w, hipStream_t st)
 {
     hipLaunchKernelGGL(plan_items_kernel, dim3(n_chunks, 2, 8), dim3(256), 0, st, offsets, src_of,

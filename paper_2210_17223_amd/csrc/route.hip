@@ -45,7 +45,8 @@ template <typename XT, int EPT, int NW>
 __global__ __launch_bounds__(NW * 64) void route_kernel(
     const XT *__restrict__ x, const float *__restrict__ Wgp,
     const float *__restrict__ bias, int bias_stride, int32_t *__restrict__ expert_idx,
-    float *__restrict__ gate, int T, int d, int dP, int E, int k, int renorm)
+    float *__restrict__ gate, int32_t *__restrict__ seg_cnt, int T, int d, int dP, int E, int k,
+    int renorm)
 {
     constexpr int KC = Stage<XT>::kc;            // 128 (bf16) or 64 (fp32)
     constexpr int VE = 16 / sizeof(XT);          // elements per 16-byte vector
@@ -55,7 +56,7 @@ __global__ __launch_bounds__(NW * 64) void route_kernel(
     static_assert(NVEC == VPT * NW * kWave, "staging map");
     constexpr int PD = NW >= 8 ? 4 : (NW == 4 ? 2 : 1);   // stages of global loads kept in flight
     __shared__ __attribute__((aligned(16))) float xs[2][kTok][LDX];
-    static_assert(sizeof(float) * 2 * kTok * LDX >= sizeof(float) * kTok * (kMaxExperts + 1), "zs alias");
+    static_assert(sizeof(float) * 2 * kTok * LDX >= sizeof(float) * (kTok + 1) * (kMaxExperts + 1), "zs alias");
     float (*zs)[kMaxExperts + 1] = reinterpret_cast<float (*)[kMaxExperts + 1]>(&xs[0][0][0]);
 
     const int lane = lane_id();
@@ -146,8 +147,14 @@ __global__ __launch_bounds__(NW * 64) void route_kernel(
         }
     }
     __syncthreads();
-    if (wave != 0 || t >= T) return;
-
+    if (wave != 0) return;
+    // The first wavefront finishes the block's 64 tokens: top-k, softmax weights and, for the
+    // layer call, the expert histogram of these tokens (one segment of the dispatch plan).
+    // The histogram sits behind the logits in the reused token-tile memory.
+    int32_t *cnt = reinterpret_cast<int32_t *>(&zs[kTok][0]);
+    if (seg_cnt != nullptr) cnt[lane] = 0;
+    __builtin_amdgcn_wave_barrier();
+    if (t < T) {
     // softmax denominator over all E experts
     float zmax = zs[lane][0];
     for (int e = 1; e < E; ++e) zmax = fmaxf(zmax, zs[lane][e]);
@@ -183,6 +190,12 @@ __global__ __launch_bounds__(NW * 64) void route_kernel(
         const float g = expf(bz - zmax) / denom;
         expert_idx[static_cast<size_t>(t) * k + j] = best;
         gate[static_cast<size_t>(t) * k + j] = renorm ? g / gsum : g;
+        if (seg_cnt != nullptr) atomicAdd(&cnt[best], 1);
+    }
+    }
+    if (seg_cnt != nullptr) {
+        __builtin_amdgcn_wave_barrier();
+        seg_cnt[static_cast<size_t>(blockIdx.x) * kMaxExperts + lane] = cnt[lane];
     }
 }
 
@@ -216,7 +229,7 @@ int padded_dim(int d) { return (d + kGatePad - 1) / kGatePad * kGatePad; }
 template <typename XT>
 moe_status launch_route_t(const moe_shape &s, const XT *x, const float *Wgp,
                           const float *bias, int bias_stride, int32_t *expert_idx,
-                          float *gate, hipStream_t st)
+                          float *gate, int32_t *seg_cnt, hipStream_t st)
 {
     const int EP = pow2_ceil(s.E);
     const int dP = padded_dim(s.d_model);
@@ -232,8 +245,8 @@ moe_status launch_route_t(const moe_shape &s, const XT *x, const float *Wgp,
 #define MOE_ROUTE_CASE(EPT_, NW_)                                                            \
     if (ept == EPT_ && nw == NW_) {                                                          \
         hipLaunchKernelGGL((route_kernel<XT, EPT_, NW_>), grid, block, 0, st, x, Wgp, bias,  \
-                           bias_stride, expert_idx, gate, s.T, s.d_model, dP, s.E, s.k,      \
-                           s.renorm_topk);                                                   \
+                           bias_stride, expert_idx, gate, seg_cnt, s.T, s.d_model, dP, s.E,  \
+                           s.k, s.renorm_topk);                                              \
         launched = true;                                                                     \
     }
     bool launched = false;
@@ -274,15 +287,15 @@ moe_status launch_pack_gate(const moe_shape &s, const void *Wg, float *Wgp, hipS
 
 moe_status launch_route(const moe_shape &s, const void *x, const void *Wgp,
                         const float *bias, int bias_stride, int32_t *expert_idx,
-                        float *gate, hipStream_t st)
+                        float *gate, int32_t *seg_cnt, hipStream_t st)
 {
     if (s.dtype == MOE_BF16)
         return launch_route_t<uint16_t>(s, static_cast<const uint16_t *>(x),
                                         static_cast<const float *>(Wgp), bias, bias_stride,
-                                        expert_idx, gate, st);
+                                        expert_idx, gate, seg_cnt, st);
     return launch_route_t<float>(s, static_cast<const float *>(x),
                                  static_cast<const float *>(Wgp), bias, bias_stride,
-                                 expert_idx, gate, st);
+                                 expert_idx, gate, seg_cnt, st);
 }
 
 }  // namespace moe

@@ -45,7 +45,7 @@ def test_sizes():
     assert moe.moe_workspace_bytes(s, 8) >= moe.moe_workspace_bytes(s, 1) - (1 << 16)
     s2 = moe.Shape.make(100, 64, 6, 128, 2, 5, dtype="f32")
     assert moe.moe_max_rows(s2) == 30
-    assert moe.moe_packed_gate_bytes(s2) == 64 * 8 * 4
+    assert moe.moe_packed_gate_bytes(s2) == 128 * 8 * 4      # d padded to 128, E to a power of two
 
 
 @pytest.mark.parametrize("kw,frag", [
