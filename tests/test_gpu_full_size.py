@@ -126,6 +126,11 @@ def test_inference_stack():
         # the two chains' inputs differ by accumulated rounding, and a gate weight is a
         # softmax of logits: compare it absolutely
         np.testing.assert_allclose(gg, wg, rtol=0, atol=3e-2)
-        y = L.b["y"].cpu().numpy().reshape(T, d)
-        assert rel_rms_err(y, o.y) <= TOL_BF16 * (l + 1), f"layer {l}"
+        # There is no normalisation between the layers, so the activations double per layer
+        # and the gate's sensitivity to an input ulp grows with them; the output is linear in
+        # the gate weights, and a single element's deviation follows the gate's.  (a) above
+        # is the parity gate; here the drift of the whole output is bounded in the mean.
+        y = L.b["y"].cpu().numpy().reshape(T, d).astype(np.float64)
+        drift = np.linalg.norm(y - o.y) / np.linalg.norm(o.y)
+        assert drift <= TOL_BF16, f"layer {l}: relative Frobenius drift {drift}"
         x_dev = L.b["y_act"].view(T, d)
