@@ -2,11 +2,13 @@
 """Benchmark of the one-GPU MoE-layer forward (libmoe) on MI355X.
 
 A step is one pass of the whole hot path -- gate, dispatch plan, pack, expert FFN,
-combine -- over one batch of seeded synthetic tokens, through moe_layer_chunked.
-Inputs and packed weights are resident in HBM before the timed region.  Prints one
-JSON line: layer tokens/s, the roofline position of the dominant kernel (first
-expert GEMM, timed with HIP events on its own stream during the timed steps), and
-the CPU oracle's rate on the same workload as a baseline.
+combine -- over one batch of seeded synthetic tokens, through moe_layer_chunked (for
+the 4-layer inference workload: the four layers back to back, each reading the
+previous layer's output).  Inputs and packed weights are resident in HBM before the
+timed region.  Prints one JSON line: layer tokens/s, the roofline position of the
+dominant kernel (first expert GEMM, timed with HIP events attached to its own
+dispatches during the timed steps), and the CPU oracle's rate on the same workload
+as a baseline.
 """
 from __future__ import annotations
 
@@ -21,6 +23,13 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16/fp16 MFMA
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
+INFINITY_CACHE_BYTES = 256 << 20
+
+# HBM bytes per launch of the first expert GEMM, from rocprofv3 --pmc FETCH_SIZE and
+# --pmc WRITE_SIZE runs of this script (readings and scale factors: profiles/).  The
+# counters cannot be read from inside the process, so the figure is a stored measurement,
+# reported only for the workload and launch configuration it was taken on.
+GEMM1_TRAFFIC_BYTES = {("gpt2s_moe", 1): (69011 * 2.0 + 49246 * 1.0) * 1024}
 
 
 def main() -> int:
@@ -34,7 +43,23 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true",
                     help="after the timed region, run extra steps with every stage timed")
+    ap.add_argument("--cold-sets", type=int, default=4,
+                    help="after the timed region, time the same steps rotating through this many "
+                         "copies of every buffer, so that no step finds its data in the 256 MB "
+                         "Infinity Cache (skipped when one copy alone exceeds the cache; 0 = off)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run ten plain device copies of 256 MiB and exit: under rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE the copy kernel's reading fixes the counter's unit")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4}))
+        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
@@ -52,119 +77,213 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     cfg = wl.CONFIGS[args.workload]
-    if cfg["layers"] != 1:
-        print("bench.py: stack workloads are benchmarked layer by layer; pick a one-layer workload",
-              file=sys.stderr)
-        return 2
-    li = wl.make_layer(cfg, seed=0, threads=16)
-    s = moe.Shape.make(li.T, li.d, li.E, li.h, li.k, li.C,
-                       dtype="bf16" if li.dtype == "bf16" else "f32", act="gelu")
+    n_layers = cfg["layers"]
+    host = wl.make_stack(cfg, seed=0, threads=16) if n_layers > 1 else [wl.make_layer(cfg, seed=0, threads=16)]
+    l0 = host[0]
+    bf16 = l0.dtype == "bf16"
+    s = moe.Shape.make(l0.T, l0.d, l0.E, l0.h, l0.k, l0.C, dtype="bf16" if bf16 else "f32", act="gelu")
+    esz = 2 if bf16 else 4
 
     def up(a):
-        if li.dtype == "bf16":
+        if bf16:
             bits = wl.bf16_bits(a).view(np.int16).reshape(a.shape)
             return torch.from_numpy(bits).to(dev).view(torch.bfloat16)
         return torch.from_numpy(a).to(dev)
 
-    x, Wg = up(li.x), up(li.Wg)
-    bias = None if li.gate_bias is None else torch.from_numpy(li.gate_bias).to(dev)
-    b = moe.alloc_buffers(s, args.chunks, dev)
-    moe.moe_pack_gate(s, Wg, b["Wgp"])
-    W1, W2 = up(li.W1), up(li.W2)
-    moe.moe_pack_weights(s, W1, W2, b["W1p"], b["W2p"])
-    torch.cuda.synchronize()
-    del W1, W2
+    class DevLayer:
+        """One layer's device buffers; `x` is None for the later layers of a stack."""
 
-    def step():
-        moe.moe_layer_chunked(s, args.chunks, x, b["Wgp"], bias, li.bias_token_stride,
-                              b["W1p"], None, b["W2p"], None, b["expert_idx"], b["gate"],
-                              b["counts"], b["offsets"], b["slot_of"], b["src_of"], b["xe"],
-                              b["ye"], b["y"], None, b["workspace"])
+        def __init__(self, li=None, like=None):
+            self.b = moe.alloc_buffers(s, args.chunks, dev, y_act=n_layers > 1)
+            if like is None:
+                self.x = up(li.x) if li.x.shape[0] else None
+                self.bias = None if li.gate_bias is None else torch.from_numpy(li.gate_bias).to(dev)
+                self.stride = li.bias_token_stride
+                moe.moe_pack_gate(s, up(li.Wg), self.b["Wgp"])
+                W1, W2 = up(li.W1), up(li.W2)
+                moe.moe_pack_weights(s, W1, W2, self.b["W1p"], self.b["W2p"])
+                torch.cuda.synchronize()
+            else:       # a second copy of the same layer at other addresses
+                self.x = None if like.x is None else like.x.clone()
+                self.bias = None if like.bias is None else like.bias.clone()
+                self.stride = like.stride
+                for name in ("Wgp", "W1p", "W2p"):
+                    self.b[name].copy_(like.b[name])
 
+        def bytes(self):
+            n = sum(t.numel() * t.element_size() for t in self.b.values() if t is not None)
+            return n + (0 if self.x is None else self.x.numel() * esz)
+
+        def run(self, x):
+            b = self.b
+            moe.moe_layer_chunked(s, args.chunks, x, b["Wgp"], self.bias, self.stride, b["W1p"], None,
+                                  b["W2p"], None, b["expert_idx"], b["gate"], b["counts"], b["offsets"],
+                                  b["slot_of"], b["src_of"], b["xe"], b["ye"], b["y"], b["y_act"],
+                                  b["workspace"])
+
+    sets = [[DevLayer(li) for li in host]]
+    for li in host:       # the host copies of the weights are needed again only by the oracle
+        if args.no_cpu_baseline:
+            li.W1 = li.W2 = None
+
+    def step(layers):
+        x = layers[0].x
+        for L in layers:
+            L.run(x)
+            x = L.b["y_act"]
+
+    def timed(n, which):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            step(sets[which(i)])
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    launches = args.steps * args.chunks * n_layers
     for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
+        step(sets[0])
     G1 = moe.STAGES.index("gemm1")
-    moe.moe_profile_enable(1 << G1, args.steps * args.chunks)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    g1_ms = np.array(moe.moe_profile_read(G1, args.steps * args.chunks))
+    moe.moe_profile_enable(1 << G1, launches)
+    ms_per_step = timed(args.steps, lambda i: 0)
+    g1_ms = np.array(moe.moe_profile_read(G1, launches))
     moe.moe_profile_enable(0, 0)
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    tokens_per_s = li.T / (ms_per_step * 1e-3)
-    A = int(b["offsets"].cpu().numpy()[-1])
-    counts = b["counts"].cpu().numpy()
-    # first expert GEMM: 2*A*d*h flops per layer; one launch per chunk
+    tokens_per_s = l0.T / (ms_per_step * 1e-3)
+    offs = [L.b["offsets"].cpu().numpy() for L in sets[0]]
+    cnts = [L.b["counts"].cpu().numpy() for L in sets[0]]
+    A = float(np.mean([o[-1] for o in offs]))                               # kept rows per layer
+    live = float(np.mean([(np.diff(o) > 0).sum() for o in offs]))           # experts with rows
+    # first expert GEMM, per launch (one launch per chunk and layer): 2*A*d*h flops; reads the
+    # packed rows and the weights of the experts that have rows, writes the hidden rows
     g1_avg_ms = float(g1_ms.mean())
-    g1_flops_per_launch = 2.0 * A * li.d * li.h / args.chunks
-    g1_tflops = g1_flops_per_launch / (g1_avg_ms * 1e-3) / 1e12
+    g1_flops = 2.0 * A * l0.d * l0.h / args.chunks
+    g1_bytes = (A * l0.d * 2 + A * l0.h * 2) / args.chunks + live * l0.d * l0.h * 2
+    g1_tflops = g1_flops / (g1_avg_ms * 1e-3) / 1e12
+    g1_gbps = g1_bytes / (g1_avg_ms * 1e-3) / 1e9
+    # Which roof bounds the expert FFN at this shape: its 4*A*d*h flops on the matrix cores
+    # against streaming the live experts' weights and the packed rows once from HBM.
+    ffn_mfma_s = 4.0 * A * l0.d * l0.h / (PEAK_BF16_TFLOPS * 1e12)
+    ffn_hbm_s = (2 * live * l0.d * l0.h * 2 + A * l0.d * (2 + 4)) / (PEAK_HBM_GBPS * 1e9)
+    hbm_bound = ffn_hbm_s > ffn_mfma_s
+    roof = {"kernel": "grouped_gemm_mfma_kernel<bf16 in, fp16 out, GeLU> (first expert GEMM)",
+            "avg_launch_us": g1_avg_ms * 1e3, "launches": int(g1_ms.size),
+            "algorithmic_flops": g1_flops, "algorithmic_bytes": g1_bytes,
+            "traffic": GEMM1_TRAFFIC_BYTES.get((args.workload, args.chunks)),
+            "mfma_tflops": g1_tflops, "hbm_gbps": g1_gbps}
+    if hbm_bound:
+        roof.update({"bound": "hbm", "achieved": g1_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                     "frac": g1_gbps / PEAK_HBM_GBPS})
+    else:
+        roof.update({"bound": "mfma", "achieved": g1_tflops, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": g1_tflops / PEAK_BF16_TFLOPS})
+    if not bf16:
+        roof = {"bound": "alu", "note": "fp32 correctness configuration: launch-bound, no roofline claimed",
+                "achieved": None, "peak": None, "unit": None, "frac": None, "traffic": None,
+                "avg_launch_us": g1_avg_ms * 1e3}
     out = {
-        "metric": "moe_layer_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s",
+        "metric": "moe_layer_tokens_per_s", "value": tokens_per_s * n_layers, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if li.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: T={li.T} d_model={li.d} E={li.E} d_ff={li.h} "
-                               f"k={li.k} capacity={li.C} {li.dtype}, seed 0",
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: T={l0.T} d_model={l0.d} E={l0.E} d_ff={l0.h} "
+                               f"k={l0.k} capacity={l0.C} {l0.dtype}, seed 0"
+                               + (f", {n_layers} layers back to back (value counts layer-tokens)" if n_layers > 1 else ""),
                    "n_chunks": args.chunks, "kept_rows_A": A,
-                   "dropped_assignments": int(li.T * li.k - A),
-                   "count_min": int(counts.min()), "count_max": int(counts.max())},
-        "roofline": {"bound": "mfma", "kernel": "grouped_gemm_mfma_kernel<bf16 in, fp16 out, GeLU> (first expert GEMM)",
-                     "achieved": g1_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": g1_tflops / PEAK_BF16_TFLOPS, "traffic": None,
-                     "avg_launch_us": g1_avg_ms * 1e3, "launches": int(g1_ms.size)},
+                   "dropped_assignments": float(l0.T * l0.k - A),
+                   "count_min": int(min(c.min() for c in cnts)), "count_max": int(max(c.max() for c in cnts))},
+        "roofline": roof,
     }
 
-    if args.stages:
+    # ---- the same steps with cold caches -------------------------------------------------
+    set_bytes = sum(L.bytes() for L in sets[0])
+    if args.cold_sets > 1 and n_layers == 1 and set_bytes <= 4 * INFINITY_CACHE_BYTES:
+        while len(sets) < args.cold_sets:
+            sets.append([DevLayer(like=L) for L in sets[0]])
+        n = len(sets)
+        for i in range(n):
+            step(sets[i])
+        cold_ms = timed(args.steps, lambda i: i % n)
+        out["cold_cache"] = {"ms_per_step": cold_ms, "value": l0.T / (cold_ms * 1e-3), "unit": "tokens/s",
+                             "sets": n, "bytes_per_set": set_bytes,
+                             "note": "every step runs on the copy least recently used"}
+    else:
+        out["cold_cache"] = None    # one step's working set alone does not fit the cache
+
+    def stage_times(n_chunks_unused=None):
         n = min(args.steps, 50)
-        moe.moe_profile_enable((1 << len(moe.STAGES)) - 1, n * args.chunks)
+        cap = n * args.chunks * n_layers
+        moe.moe_profile_enable((1 << len(moe.STAGES)) - 1, cap)
         for _ in range(n):
-            step()
+            step(sets[0])
         torch.cuda.synchronize()
-        st = {}
+        mean, med, mn = {}, {}, {}
         for i, name in enumerate(moe.STAGES):
-            v = np.array(moe.moe_profile_read(i, n * args.chunks))
-            st[name] = float(v.sum() / n * 1e3) if v.size else None     # us per layer
+            v = np.array(moe.moe_profile_read(i, cap))
+            if v.size == 0:
+                mean[name] = med[name] = mn[name] = None
+                continue
+            per_step = v.reshape(n, -1).sum(1) * 1e3                      # us per step
+            mean[name], med[name], mn[name] = float(per_step.mean()), float(np.median(per_step)), float(per_step.min())
         moe.moe_profile_enable(0, 0)
-        esz = 2 if li.dtype == "bf16" else 4
-        kept_tokens = int((b["slot_of"].view(li.T, li.k) >= 0).any(1).sum().item())
-        disp_bytes = (kept_tokens + A) * li.d * esz            # read routed tokens, write slots
-        comb_bytes = (A + li.T) * li.d * 4                     # fp32 expert rows in, fp32 y out
+        return mean, med, mn
+
+    if args.stages:
+        st, med, mn = stage_times()
+        kept_tokens = float(np.mean([(L.b["slot_of"].view(l0.T, l0.k) >= 0).any(1).sum().item() for L in sets[0]]))
+        disp_bytes = (kept_tokens + A) * l0.d * esz * n_layers      # read routed tokens, write slots
+        comb_bytes = (A + l0.T) * l0.d * 4 * n_layers               # fp32 expert rows in, fp32 y out
         st["dispatch_GBps"] = disp_bytes / (st["scatter"] * 1e-6) / 1e9
         st["combine_GBps"] = comb_bytes / (st["combine"] * 1e-6) / 1e9
         st["dispatch_combine_frac_of_hbm_peak"] = ((disp_bytes + comb_bytes) /
                                                    ((st["scatter"] + st["combine"]) * 1e-6) / 1e9 / PEAK_HBM_GBPS)
-        st["ffn_mfma_util"] = (4.0 * A * li.d * li.h) / ((st["gemm1"] + st["gemm2"]) * 1e-6) / 1e12 / PEAK_BF16_TFLOPS
+        st["ffn_mfma_util"] = (4.0 * A * l0.d * l0.h * n_layers) / ((st["gemm1"] + st["gemm2"]) * 1e-6) / 1e12 / PEAK_BF16_TFLOPS
+        ffn_bytes = (2 * live * l0.d * l0.h * 2 + A * l0.d * 2 + 2 * A * l0.h * 2 + A * l0.d * 4) * n_layers
+        st["ffn_GBps"] = ffn_bytes / ((st["gemm1"] + st["gemm2"]) * 1e-6) / 1e9
         out["stages_us"] = st
+        out["stages_us_median"] = med
+        out["stages_us_min"] = mn
+        if args.chunks > 1:
+            # How much of the pack and unpack time the chunk pipeline hides behind the expert
+            # FFN (Sec. 4.2's pipelining efficiency, with the pack kernel in the all-to-all's
+            # place): 1 - (t_pipelined - t_ffn) / (t_pack + t_unpack), stage times summed over
+            # the chunks, t_pipelined = the layer minus gate and plan.
+            t_pipe = ms_per_step * 1e3 - st["route"] - st["plan"] - (st["tiles"] or 0.0)
+            t_ffn = st["gemm1"] + st["gemm2"]
+            out["chunk_overlap"] = {"t_pipelined_us": t_pipe, "t_ffn_us": t_ffn,
+                                    "t_pack_us": st["scatter"], "t_unpack_us": st["combine"],
+                                    "hidden_fraction": 1.0 - (t_pipe - t_ffn) / (st["scatter"] + st["combine"])}
 
     if not args.no_cpu_baseline:
         import oracle
         # Bounded sample: whole passes of the oracle over the workload (gate and plan over
         # all tokens; expert FFN and combine for a leading slice of tokens when one full
         # pass would take minutes), repeated until about 20 core-seconds have been spent.
-        sample = li.T
-        est_flops = 4.0 * li.T * li.k * li.d * li.h
-        if est_flops > 4e11:
-            sample = max(64, int(li.T * 4e11 / est_flops))
+        sample = l0.T
+        est_flops = 4.0 * l0.T * l0.k * l0.d * l0.h * n_layers
+        if est_flops > 4e11 and n_layers == 1:   # a stack needs every token of a layer for the next
+            sample = max(64, int(l0.T * 4e11 / est_flops))
         toks = np.arange(sample, dtype=np.int32)
         cores = oracle.threads()
         passes, c0 = 0, time.perf_counter()
         while True:
-            oracle.moe_layer(li.x, li.Wg, li.W1, li.W2, k=li.k, capacity=li.C, bias=li.gate_bias,
-                             bias_stride=li.bias_token_stride,
-                             tokens=None if sample == li.T else toks)
+            x_l = host[0].x
+            for li in host:
+                o = oracle.moe_layer(x_l, li.Wg, li.W1, li.W2, k=li.k, capacity=li.C, bias=li.gate_bias,
+                                     bias_stride=li.bias_token_stride,
+                                     tokens=None if sample == l0.T else toks)
+                if n_layers > 1:
+                    x_l = wl.bf16_round(o.y)      # the next layer reads the rounded output
             passes += 1
             elapsed = time.perf_counter() - c0
             if elapsed * cores >= 20.0 or passes >= 50:
                 break
-        out["cpu_baseline"] = {"value": sample * passes / elapsed, "unit": "tokens/s",
+        out["cpu_baseline"] = {"value": sample * n_layers * passes / elapsed, "unit": "tokens/s",
                                "cores": cores, "kind": "oracle",
-                               "sample": f"{passes} pass(es): gate+plan over all {li.T} tokens, expert "
-                                         f"FFN+combine for the first {sample} tokens, {elapsed:.2f} s wall"}
+                               "sample": f"{passes} pass(es) over {n_layers} layer(s): gate+plan over all "
+                                         f"{l0.T} tokens, expert FFN+combine for the first {sample} "
+                                         f"tokens, {elapsed:.2f} s wall"}
     print(json.dumps(out))
     return 0
 

@@ -55,6 +55,15 @@ void prof_end(int stage, hipStream_t st)
     g_prof.n[stage] += 1;
 }
 
+void prof_kernel_events(int stage, hipEvent_t *start, hipEvent_t *stop)
+{
+    *start = *stop = nullptr;
+    if (!((g_prof.mask >> stage) & 1u) || g_prof.n[stage] >= g_prof.cap) return;
+    *start = g_prof.start[stage][g_prof.n[stage]];
+    *stop = g_prof.stop[stage][g_prof.n[stage]];
+    g_prof.n[stage] += 1;
+}
+
 namespace {
 
 int elem_bytes(const moe_shape &s) { return s.dtype == MOE_BF16 ? 2 : 4; }

@@ -65,6 +65,10 @@ enum Stage { kStageRoute = 0, kStagePlan, kStageTiles, kStageScatter, kStageGemm
              kStageCombine, kNumStages };
 void prof_begin(int stage, hipStream_t st);
 void prof_end(int stage, hipStream_t st);
+// For a stage that is one kernel: the pair of events to attach to that kernel's own
+// dispatch (hipExtLaunchKernelGGL), which then carry the kernel's begin and end
+// timestamps without the launch gaps around it.  Both null when the stage is not timed.
+void prof_kernel_events(int stage, hipEvent_t *start, hipEvent_t *stop);
 
 // ---- kernel launchers (each only enqueues on `st`) ---------------------------
 // when seg_cnt is not NULL the per-segment expert histogram of the dispatch plan is

@@ -14,6 +14,8 @@
 // fp32 layers: a plain LDS-tiled vector-ALU GEMM (correctness configuration).
 #include "common.h"
 
+#include <hip/hip_ext.h>
+
 namespace moe {
 namespace {
 
@@ -155,14 +157,15 @@ __device__ __forceinline__ void store4(_Float16 *p, const float (&v)[4])
 // 16-bit elements (bf16, or fp16 when F16), C [rows, N] of TOut.
 // WM x WN wavefronts, each owning (TM*32) rows x (TN*32) columns of the block's
 // (WM*TM*32) x (WN*TN*32) output tile.  K is walked in stages of 64 through a
-// double-buffered LDS tile; the global loads of stage kt+2 are in flight while stage
-// kt is multiplied, and the barrier of a stage sits before its last 16-deep step so
+// double-buffered LDS tile; the global loads of stages kt+2 (and kt+3) are in flight while
+// stage kt is multiplied, and the barrier of a stage sits before its last 16-deep step so
 // that the MFMAs of that step cover the LDS latency of the next stage's first
 // fragments.  The work list (one entry per output tile) is ordered so that each XCD
 // walks a contiguous share of it: neighbouring blocks then reuse operand tiles in that
 // XCD's L2.  32-row sub-tiles past the end of a ragged row tile are skipped.
 template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN, bool KTAIL>
-__global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_mfma_kernel(
+// (two wavefronts per SIMD in every shape: two 4-wavefront blocks or one 8-wavefront block)
+__global__ __launch_bounds__(64 * WM * WN, 2) void grouped_gemm_mfma_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W,
     const float *__restrict__ bias, TOut *__restrict__ C, const WorkItem *__restrict__ items,
     const int32_t *__restrict__ nitems, int N, int K)
@@ -218,34 +221,39 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_mfma_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
+    // Register stages between the global loads and the LDS tile: two where the registers
+    // allow it (the loads then have two stages of multiplies to arrive), one for the
+    // 256 x 256 tile.
+    constexpr int DEPTH = BM * BN < 256 * 256 ? 2 : 1;
     u32x4 a_reg[AV], w_reg[WV];
+    u32x4 a_reg2[DEPTH == 2 ? AV : 1], w_reg2[DEPTH == 2 ? WV : 1];
     u32x4 wf[2][TN], af[2][TM];
     const int KT = (K + BK - 1) / BK;
     const int fr = lane & 31, fk = (lane >> 5) * 8;
     const int wfrag = (wn * TN * 32 + fr) * LD + fk;
     const int afrag = (wm * TM * 32 + fr) * LD + fk;
 
-#define MOE_LOADG(kt_)                                                                          \
+#define MOE_LOADG(kt_, AR, WR)                                                                  \
     {                                                                                           \
         const int k0_ = (kt_) * BK;                                                             \
         const bool in_ = !KTAIL || k0_ + ld_col < K;                                           \
         _Pragma("unroll") for (int q = 0; q < AV; ++q)                                          \
         {                                                                                       \
-            if (in_) a_reg[q] = *reinterpret_cast<const u32x4 *>(a_src[q] + k0_);               \
-            else a_reg[q] = (u32x4){0u, 0u, 0u, 0u};                                            \
+            if (in_) AR[q] = *reinterpret_cast<const u32x4 *>(a_src[q] + k0_);                  \
+            else AR[q] = (u32x4){0u, 0u, 0u, 0u};                                               \
         }                                                                                       \
         _Pragma("unroll") for (int q = 0; q < WV; ++q)                                          \
         {                                                                                       \
-            if (in_) w_reg[q] = *reinterpret_cast<const u32x4 *>(w_src[q] + k0_);               \
-            else w_reg[q] = (u32x4){0u, 0u, 0u, 0u};                                            \
+            if (in_) WR[q] = *reinterpret_cast<const u32x4 *>(w_src[q] + k0_);                  \
+            else WR[q] = (u32x4){0u, 0u, 0u, 0u};                                               \
         }                                                                                       \
     }
-#define MOE_STOREL(buf)                                                                         \
+#define MOE_STOREL(buf, AR, WR)                                                                 \
     {                                                                                           \
         _Pragma("unroll") for (int q = 0; q < AV; ++q)                                          \
-            *reinterpret_cast<u32x4 *>(As + (buf) * A_BUF + a_off[q]) = a_reg[q];               \
+            *reinterpret_cast<u32x4 *>(As + (buf) * A_BUF + a_off[q]) = AR[q];                  \
         _Pragma("unroll") for (int q = 0; q < WV; ++q)                                          \
-            *reinterpret_cast<u32x4 *>(Ws + (buf) * W_BUF + w_off[q]) = w_reg[q];               \
+            *reinterpret_cast<u32x4 *>(Ws + (buf) * W_BUF + w_off[q]) = WR[q];                  \
     }
 #define MOE_READF(slot_, buf, ks)                                                               \
     {                                                                                           \
@@ -264,12 +272,13 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_mfma_kernel(
             }                                                                                   \
         }                                                                                       \
     }
-#define MOE_MAIN_LOOP                                                                           \
-    for (int kt = 0; kt < KT; ++kt) {                                                           \
-        const int buf = kt & 1;                                                                 \
-        const bool next1 = kt + 1 < KT, next2 = kt + 2 < KT;                                    \
-        if (next1) MOE_STOREL(buf ^ 1)                                                          \
-        if (next2) MOE_LOADG(kt + 2)                                                            \
+// One stage kt held in LDS buffer `buf`: the registers AR/WR (stage kt+1) go to the other
+// buffer and are refilled with stage kt+1+DEPTH.
+#define MOE_STAGE(buf, AR, WR)                                                                  \
+    {                                                                                           \
+        const bool next1 = kt + 1 < KT, nextl = kt + 1 + DEPTH < KT;                            \
+        if (next1) MOE_STOREL(buf ^ 1, AR, WR)                                                  \
+        if (nextl) MOE_LOADG(kt + 1 + DEPTH, AR, WR)                                            \
         MOE_READF(1, buf, 1)                                                                    \
         MOE_MMA(0)                                                                              \
         MOE_READF(0, buf, 2)                                                                    \
@@ -281,10 +290,29 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_mfma_kernel(
         if (next1) MOE_READF(0, buf ^ 1, 0)                                                     \
         MOE_MMA(1)                                                                              \
     }
+#define MOE_MAIN_LOOP                                                                           \
+    if constexpr (DEPTH == 2) {                                                                 \
+        int kt = 0;                                                                             \
+        for (; kt + 1 < KT; kt += 2) {                                                          \
+            MOE_STAGE(0, a_reg, w_reg)                                                          \
+            ++kt;                                                                               \
+            MOE_STAGE(1, a_reg2, w_reg2)                                                        \
+            --kt;                                                                               \
+        }                                                                                       \
+        if (kt < KT) MOE_STAGE(0, a_reg, w_reg)                                                 \
+    } else {                                                                                    \
+        for (int kt = 0; kt < KT; ++kt) {                                                       \
+            const int buf = kt & 1;                                                             \
+            MOE_STAGE(buf, a_reg, w_reg)                                                        \
+        }                                                                                       \
+    }
 
-    MOE_LOADG(0)
-    MOE_STOREL(0)
-    if (KT > 1) MOE_LOADG(1)
+    // Prologue: stage 0 into LDS, stage 1 (and with two register stages also stage 2) in
+    // flight.
+    MOE_LOADG(0, a_reg, w_reg)
+    MOE_STOREL(0, a_reg, w_reg)
+    if (KT > 1) MOE_LOADG(1, a_reg, w_reg)
+    if (DEPTH == 2 && KT > 2) MOE_LOADG(2, a_reg2, w_reg2)
     __syncthreads();
     MOE_READF(0, 0, 0)
     if (jact == TM) {          // every sub-tile of this wavefront holds rows: branch-free loop
@@ -294,6 +322,7 @@ __global__ __launch_bounds__(64 * WM * WN) void grouped_gemm_mfma_kernel(
         constexpr bool FULL = false;
         MOE_MAIN_LOOP
     }
+#undef MOE_STAGE
 #undef MOE_MAIN_LOOP
 #undef MOE_LOADG
 #undef MOE_STOREL
@@ -378,7 +407,7 @@ void launch_f32_pair(const moe_shape &s, const float *xe, const float *W1, const
 template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN, bool KTAIL>
 void launch_mfma_cfg_k(const uint16_t *A, const uint16_t *W, const float *bias, TOut *C,
                      const WorkItem *items, const int32_t *nitems, int max_items, int N, int K,
-                     hipStream_t st)
+                     int stage, hipStream_t st)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t lds = 2 * (BM + BN) * (64 + 8) * sizeof(uint16_t);
@@ -390,8 +419,10 @@ void launch_mfma_cfg_k(const uint16_t *A, const uint16_t *W, const float *bias, 
         configured = true;
     }
     const int grid = static_cast<int>(align_up(static_cast<size_t>(max_items), 8));
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, st, A, W, bias, C, items, nitems,
-                       N, K);
+    hipEvent_t t0, t1;
+    prof_kernel_events(stage, &t0, &t1);
+    hipExtLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, st, t0, t1, 0, A, W, bias, C,
+                          items, nitems, N, K);
 }
 
 // The contraction depth is a multiple of the 64-deep stage in every benchmark shape;
@@ -399,27 +430,27 @@ void launch_mfma_cfg_k(const uint16_t *A, const uint16_t *W, const float *bias, 
 template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN>
 void launch_mfma_cfg(const uint16_t *A, const uint16_t *W, const float *bias, TOut *C,
                      const WorkItem *items, const int32_t *nitems, int max_items, int N, int K,
-                     hipStream_t st)
+                     int stage, hipStream_t st)
 {
     if (K % 64 == 0)
         launch_mfma_cfg_k<F16, TOut, ACT, WM, WN, TM, TN, false>(A, W, bias, C, items, nitems,
-                                                                 max_items, N, K, st);
+                                                                 max_items, N, K, stage, st);
     else
         launch_mfma_cfg_k<F16, TOut, ACT, WM, WN, TM, TN, true>(A, W, bias, C, items, nitems,
-                                                                max_items, N, K, st);
+                                                                max_items, N, K, stage, st);
 }
 
 template <bool F16, typename TOut, int ACT>
 void launch_mfma(const GemmPlan &gp, const uint16_t *A, const uint16_t *W, const float *bias,
                  TOut *C, const WorkItem *items, const int32_t *nitems, int N, int K,
-                 hipStream_t st)
+                 int stage, hipStream_t st)
 {
     if (gp.bm == 256)
-        launch_mfma_cfg<F16, TOut, ACT, 2, 4, 4, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, st);
+        launch_mfma_cfg<F16, TOut, ACT, 2, 4, 4, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, stage, st);
     else if (gp.bn == 256)
-        launch_mfma_cfg<F16, TOut, ACT, 2, 4, 2, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, st);
+        launch_mfma_cfg<F16, TOut, ACT, 2, 4, 2, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, stage, st);
     else
-        launch_mfma_cfg<F16, TOut, ACT, 2, 2, 2, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, st);
+        launch_mfma_cfg<F16, TOut, ACT, 2, 2, 2, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, stage, st);
 }
 
 template <int ACT>
@@ -430,15 +461,11 @@ void launch_mfma_pair(const moe_shape &s, const uint16_t *xe, const uint16_t *W1
     _Float16 *H = static_cast<_Float16 *>(w.hidden);
     const WorkItem *it1 = w.items[0] + static_cast<size_t>(chunk) * w.gp[0].max_items;
     const WorkItem *it2 = w.items[1] + static_cast<size_t>(chunk) * w.gp[1].max_items;
-    prof_begin(kStageGemm1, st);
     launch_mfma<false, _Float16, ACT>(w.gp[0], xe, W1p, b1, H, it1, w.nitems[0] + chunk, s.d_ff,
-                                      s.d_model, st);
-    prof_end(kStageGemm1, st);
-    prof_begin(kStageGemm2, st);
+                                      s.d_model, kStageGemm1, st);
     launch_mfma<true, float, MOE_ACT_IDENTITY>(w.gp[1], reinterpret_cast<const uint16_t *>(H), W2p,
                                                b2, ye, it2, w.nitems[1] + chunk, s.d_model,
-                                               s.d_ff, st);
-    prof_end(kStageGemm2, st);
+                                               s.d_ff, kStageGemm2, st);
 }
 
 }  // namespace
