@@ -207,7 +207,8 @@ bool layout_workspace(const moe_shape &s, int n_chunks, void *base, Workspace *w
     const int64_t n = static_cast<int64_t>(s.T) * s.k;
     const int64_t max_rows = moe_max_rows(&s);
     (void)n;
-    w->nseg = (s.T + kSegTok - 1) / kSegTok;
+    w->seg_tok = route_segment_tokens(s);
+    w->nseg = (s.T + w->seg_tok - 1) / w->seg_tok;
     char *p = static_cast<char *>(base);
     size_t off = 0;
     w->seg_cnt = reinterpret_cast<int32_t *>(p + off);

@@ -12,7 +12,7 @@ namespace moe {
 constexpr int kWave = 64;          // wavefront width on CDNA
 constexpr int kMaxExperts = 64;    // one ballot bit / one lane per expert
 constexpr int kMaxTopK = 8;
-constexpr int kSegTok = 64;        // tokens per plan segment = tokens per gate block
+constexpr int kSegTok = 64;        // most tokens per plan segment (= tokens per gate block)
 constexpr int kMaxChunks = 64;
 
 // ---- host side -------------------------------------------------------------
@@ -55,6 +55,7 @@ struct Workspace {
     void *hidden;          // [max_rows][d_ff] hidden activations
     GemmPlan gp[2];
     int32_t nseg;
+    int32_t seg_tok;       // tokens per segment (route_segment_tokens)
     size_t bytes;
 };
 bool layout_workspace(const moe_shape &s, int n_chunks, void *base, Workspace *w);
@@ -63,6 +64,8 @@ bool layout_workspace(const moe_shape &s, int n_chunks, void *base, Workspace *w
 // launches are bracketed by a pair of timing events on the stream they run on.
 enum Stage { kStageRoute = 0, kStagePlan, kStageTiles, kStageScatter, kStageGemm1, kStageGemm2,
              kStageCombine, kNumStages };
+// Tokens per block of the gate kernel for this shape = tokens per segment of the plan.
+int route_segment_tokens(const moe_shape &s);
 void prof_begin(int stage, hipStream_t st);
 void prof_end(int stage, hipStream_t st);
 // For a stage that is one kernel: the pair of events to attach to that kernel's own

@@ -71,29 +71,33 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(
     if (base < n) seg_cnt[static_cast<size_t>(seg) * kMaxExperts + lane] = run[wave][lane];
 }
 
-// One block of 16 groups x 64 experts.  seg_cnt[seg][e] becomes the number of
-// assignments to e in all earlier segments.
+// One block of 1024 lanes = G groups x EPs experts (EPs = E rounded up to a power of two),
+// each group walking its contiguous share of the segments.  seg_cnt[seg][e] becomes the
+// number of assignments to e in all earlier segments.
 __global__ __launch_bounds__(1024) void plan_scan_kernel(
     int32_t *__restrict__ seg_cnt, int32_t *__restrict__ counts,
-    int32_t *__restrict__ offsets, int nseg, int E, int capacity, int with_items,
+    int32_t *__restrict__ offsets, int nseg, int E, int EPs, int capacity, int with_items,
     WorkItem *__restrict__ items0, int32_t *__restrict__ nitems0, GemmPlan gp0,
     WorkItem *__restrict__ items1, int32_t *__restrict__ nitems1, GemmPlan gp1)
 {
-    __shared__ int32_t gsum[16][kMaxExperts];
+    __shared__ int32_t gsum[1024];                 // [G][EPs]
     __shared__ int32_t kept[kMaxExperts];
     __shared__ int32_t lo_s[kMaxExperts], hi_s[kMaxExperts], mt_s[kMaxExperts];
     __shared__ int32_t cum_s[kMaxExperts + 1];
-    const int e = threadIdx.x % kMaxExperts;
-    const int g = threadIdx.x / kMaxExperts;
-    const int per = ceil_div(nseg, 16);
+    // groups: about four segments each, at least 16, at most what 1024 lanes hold
+    const int G = min(1024 / EPs, max(16, nseg / 4));
+    const int e = threadIdx.x % EPs;
+    const int g = threadIdx.x / EPs;
+    const int per = ceil_div(nseg, G);
     const int s0 = min(g * per, nseg), s1 = min(s0 + per, nseg);
     int32_t local = 0;
     for (int s = s0; s < s1; ++s) local += seg_cnt[static_cast<size_t>(s) * kMaxExperts + e];
-    gsum[g][e] = local;
+    if (g < G) gsum[g * EPs + e] = local;
+    if (threadIdx.x < kMaxExperts) kept[threadIdx.x] = 0;
     __syncthreads();
     int32_t before = 0, total = 0;
-    for (int gg = 0; gg < 16; ++gg) {
-        const int32_t v = gsum[gg][e];
+    for (int gg = 0; gg < G; ++gg) {
+        const int32_t v = gsum[gg * EPs + e];
         if (gg < g) before += v;
         total += v;
     }
@@ -104,9 +108,9 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(
         seg_cnt[at] = running;
         running += c;
     }
-    if (g == 0) {
-        if (e < E) counts[e] = total;
-        kept[e] = e < E ? min(total, capacity) : 0;
+    if (g == 0 && e < E) {
+        counts[e] = total;
+        kept[e] = min(total, capacity);
     }
     __syncthreads();
     if (threadIdx.x < kWave) {                      // exclusive scan of kept[] by one wavefront
@@ -270,13 +274,15 @@ moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *c
                        const Workspace &w, bool counted, int n_chunks, hipStream_t st)
 {
     const int n = s.T * s.k;
-    const int seg_len = kSegTok * s.k;
+    const int seg_len = w.seg_tok * s.k;
+    int eps = 1;
+    while (eps < s.E) eps <<= 1;
     const int blocks = ceil_div(w.nseg, kPlanWaves);
     if (!counted)
         hipLaunchKernelGGL(plan_count_kernel, dim3(blocks), dim3(kPlanThreads), 0, st,
                            expert_idx, w.seg_cnt, n, s.E, seg_len);
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, w.seg_cnt, counts,
-                       offsets, w.nseg, s.E, s.capacity, n_chunks == 1 ? 1 : 0, w.items[0],
+                       offsets, w.nseg, s.E, eps, s.capacity, n_chunks == 1 ? 1 : 0, w.items[0],
                        w.nitems[0], w.gp[0], w.items[1], w.nitems[1], w.gp[1]);
     hipLaunchKernelGGL(plan_rank_kernel, dim3(blocks), dim3(kPlanThreads), 0, st,
                        expert_idx, w.seg_cnt, offsets, slot_of, src_of, n, s.E, s.capacity,

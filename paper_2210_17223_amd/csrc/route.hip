@@ -3,23 +3,24 @@
 // The logit of (token, expert) is one fp32 accumulator walked over the model
 // dimension in ascending order with fused multiply-adds, so that the top-k
 // decision (an integer result) does not depend on a reduction tree.  The work is
-// therefore plain fp32 vector arithmetic: a lane owns one token and EPT experts,
-// the token's embedding comes from a double-buffered LDS tile, and the gate matrix,
-// which is uniform across the lanes of a wavefront, is fetched with scalar loads and
-// fed to v_fma_f32 from scalar registers.
+// therefore plain fp32 vector arithmetic on T x E independent chains.  A lane owns
+// TPL tokens x EPL experts (a register block of chains, sized on the host so that the
+// chip still has enough wavefronts); both operands come from LDS tiles of the token
+// rows and of the packed gate matrix, 64 columns of the model dimension per stage,
+// double buffered, with two or three further stages of global loads in flight in registers.
 #include "common.h"
+
+#include <algorithm>
 
 namespace moe {
 namespace {
 
-constexpr int kTok = 64;      // tokens per block (= lanes of one wavefront)
 constexpr int kGatePad = 128; // the packed gate matrix pads the model dimension to this
+constexpr int kKC = 64;       // model-dimension columns per stage
+constexpr int kLDX = kKC + 4; // LDS row pitch in floats: rows 4 banks apart, 16-byte aligned
 
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
-
-// Model-dimension chunk staged in LDS per step: 16 vectors of 16 bytes per token row.
-template <typename XT> struct Stage { static constexpr int kc = 256 / sizeof(XT); };
 
 __device__ __forceinline__ void store_row_vec(float *dst, const u32x4 &q, float)
 {
@@ -36,125 +37,155 @@ __device__ __forceinline__ void store_row_vec(float *dst, const u32x4 &q, uint16
     *reinterpret_cast<f32x4 *>(dst + 4) = hi;
 }
 
-// Block = NW wavefronts over the same 64 tokens; wavefront w owns experts
-// [w*EPT, (w+1)*EPT) and lane t owns token t0 + t.  Wgp is the packed gate matrix:
-// fp32 [EP][dP], expert-major, zero padded, so that eight consecutive weights of one
-// expert arrive with one scalar load.  The token tile is staged through LDS as fp32
-// (double buffered, the next stage's global loads in flight during the FMAs).
-template <typename XT, int EPT, int NW>
-__global__ __launch_bounds__(NW * 64) void route_kernel(
+// Block = TB tokens x EP experts (EP = E rounded up to a power of two), NG = EP / EPL
+// expert groups x TB / TPL token groups of lanes.  Lane (tg, eg) owns tokens
+// a * TG + tg and experts b * NG + eg (interleaved, so that the lanes of a wavefront read
+// neighbouring LDS rows).  Wgp is the packed gate matrix: fp32 [EP][dP], expert-major,
+// zero padded.  After the chains the logits go to LDS and the first wavefront finishes
+// the block's tokens: top-k, softmax weights and, for the layer call, the expert
+// histogram of these TB tokens (one segment of the dispatch plan).
+template <typename XT, int TPL, int EPL>
+__global__ __launch_bounds__(256, 2) void route_kernel(
     const XT *__restrict__ x, const float *__restrict__ Wgp,
     const float *__restrict__ bias, int bias_stride, int32_t *__restrict__ expert_idx,
-    float *__restrict__ gate, int32_t *__restrict__ seg_cnt, int T, int d, int dP, int E, int k,
-    int renorm)
+    float *__restrict__ gate, int32_t *__restrict__ seg_cnt, int T, int d, int dP, int E, int EP,
+    int TB, int k, int renorm)
 {
-    constexpr int KC = Stage<XT>::kc;            // 128 (bf16) or 64 (fp32)
-    constexpr int VE = 16 / sizeof(XT);          // elements per 16-byte vector
-    constexpr int LDX = KC + 4;                  // LDS row pitch in floats
-    constexpr int NVEC = kTok * 16;              // 16-byte vectors per stage
-    constexpr int VPT = 16 / NW;                 // vectors per thread per stage
-    static_assert(NVEC == VPT * NW * kWave, "staging map");
-    constexpr int PD = NW >= 8 ? 4 : (NW == 4 ? 2 : 1);   // stages of global loads kept in flight
-    __shared__ __attribute__((aligned(16))) float xs[2][kTok][LDX];
-    static_assert(sizeof(float) * 2 * kTok * LDX >= sizeof(float) * (kTok + 1) * (kMaxExperts + 1), "zs alias");
-    float (*zs)[kMaxExperts + 1] = reinterpret_cast<float (*)[kMaxExperts + 1]>(&xs[0][0][0]);
+    // register stages of global loads in flight: a stage of a large register block takes long
+    // enough for two to cover the load latency
+    constexpr int PD = TPL * EPL >= 4 ? 2 : 3;
+    constexpr int UNR = PD == 2 ? 2 : 6;             // stages per unrolled trip: lcm(PD, 2)
+    constexpr int VE = 16 / sizeof(XT);              // elements per 16-byte vector
+    constexpr int XRV = kKC / VE;                    // 16-byte vectors per token row per stage
+    constexpr int WRV = kKC / 4;                     // ... per gate-matrix row per stage
+    constexpr int XV = 64 * XRV / 256;               // per thread, at most (TB <= 64, 256 threads)
+    constexpr int WV = 64 * WRV / 256;               // per thread, at most (EP <= 64)
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float *xs = smem;                                // [2][TB][kLDX]
+    float *ws = smem + 2 * TB * kLDX;                // [2][EP][kLDX]
+    float (*zs)[kMaxExperts + 1] = reinterpret_cast<float (*)[kMaxExperts + 1]>(smem);
 
-    const int lane = lane_id();
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int e0 = wave * EPT;
-    const int t0 = blockIdx.x * kTok;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int NG = EP / EPL, TG = TB / TPL;
+    // threads beyond NG * TG (few experts) only help to stage the tiles
+    const bool active = tid < NG * TG;
+    const int eg = tid % NG, tg = min(tid / NG, TG - 1);
+    const int t0 = blockIdx.x * TB;
 
-    // staging map: vector v = row (v / 16), 16-byte column (v % 16)
-    u32x4 pre[PD][VPT];
-    const XT *src[VPT];
-    int col[VPT];
-    float *dst[2][VPT];
+    // staging maps: x vector v = row (v / XRV), column (v % XRV) * VE; same for the matrix
+    const int nxv = TB * XRV, nwv = EP * WRV;
+    const XT *xsrc[XV];
+    const float *wsrc[WV];
+    int xdst[XV], wdst[WV], xcol[XV];
 #pragma unroll
-    for (int q = 0; q < VPT; ++q) {
-        const int v = threadIdx.x + q * NW * kWave;
-        const int r = v >> 4;
-        col[q] = (v & 15) * VE;
-        src[q] = x + static_cast<size_t>(min(t0 + r, T - 1)) * d + col[q];
-        dst[0][q] = &xs[0][r][col[q]];
-        dst[1][q] = &xs[1][r][col[q]];
+    for (int q = 0; q < XV; ++q) {
+        const int v = min(tid + q * nthr, nxv - 1);
+        const int r = v / XRV;
+        xcol[q] = (v % XRV) * VE;
+        xsrc[q] = x + static_cast<size_t>(min(t0 + r, T - 1)) * d + xcol[q];
+        xdst[q] = r * kLDX + xcol[q];
     }
+#pragma unroll
+    for (int q = 0; q < WV; ++q) {
+        const int v = min(tid + q * nthr, nwv - 1);
+        const int r = v / WRV, c = (v % WRV) * 4;
+        wsrc[q] = Wgp + static_cast<size_t>(r) * dP + c;
+        wdst[q] = r * kLDX + c;
+    }
+    u32x4 xpre[PD][XV], wpre[PD][WV];
 #define MOE_LOAD_STAGE(slot, k0)                                                      \
-    _Pragma("unroll") for (int q = 0; q < VPT; ++q)                                   \
     {                                                                                 \
-        const u32x4 zero = {0u, 0u, 0u, 0u};                                          \
-        pre[slot][q] = zero;                                                          \
-        if ((k0) + col[q] < d)                                                        \
-            pre[slot][q] = *reinterpret_cast<const u32x4 *>(src[q] + (k0));           \
+        _Pragma("unroll") for (int q = 0; q < XV; ++q)                                \
+        {                                                                             \
+            xpre[slot][q] = (u32x4){0u, 0u, 0u, 0u};                                  \
+            if (tid + q * nthr < nxv && (k0) + xcol[q] < d)                           \
+                xpre[slot][q] = *reinterpret_cast<const u32x4 *>(xsrc[q] + (k0));     \
+        }                                                                             \
+        _Pragma("unroll") for (int q = 0; q < WV; ++q)                                \
+            if (tid + q * nthr < nwv)                                                 \
+                wpre[slot][q] = *reinterpret_cast<const u32x4 *>(wsrc[q] + (k0));     \
     }
 #define MOE_STORE_STAGE(slot, buf)                                                    \
-    _Pragma("unroll") for (int q = 0; q < VPT; ++q)                                   \
-        store_row_vec(dst[buf][q], pre[slot][q], XT());
+    {                                                                                 \
+        _Pragma("unroll") for (int q = 0; q < XV; ++q)                                \
+            if (tid + q * nthr < nxv)                                                 \
+                store_row_vec(xs + (buf) * TB * kLDX + xdst[q], xpre[slot][q], XT()); \
+        _Pragma("unroll") for (int q = 0; q < WV; ++q)                                \
+            if (tid + q * nthr < nwv)                                                 \
+                *reinterpret_cast<u32x4 *>(ws + (buf) * EP * kLDX + wdst[q]) = wpre[slot][q]; \
+    }
 
-    float acc[EPT];
+    float acc[TPL][EPL];
 #pragma unroll
-    for (int q = 0; q < EPT; ++q) acc[q] = 0.0f;
+    for (int a = 0; a < TPL; ++a)
+#pragma unroll
+        for (int b = 0; b < EPL; ++b) acc[a][b] = 0.0f;
 
-    const int nstage = dP / KC;
+    const int nstage = dP / kKC;
 #pragma unroll
     for (int u = 0; u < PD; ++u)
-        if (u < nstage) { MOE_LOAD_STAGE(u, u * KC) }
-    for (int s0 = 0; s0 < nstage; s0 += PD) {
+        if (u < nstage) MOE_LOAD_STAGE(u, u * kKC)
+    for (int s0 = 0; s0 < nstage; s0 += UNR) {
+        // unrolled so that the register slot (u % PD) and the LDS buffer (u & 1) of a stage
+        // are compile-time
 #pragma unroll
-        for (int u = 0; u < PD; ++u) {
+        for (int u = 0; u < UNR; ++u) {
             const int s = s0 + u;
             if (s < nstage) {
-                // PD is even or 1, so the LDS buffer of stage s is the compile-time u & 1
-                // (for PD == 1 it alternates with s)
-                const int buf = PD == 1 ? (s & 1) : (u & 1);
-                if (buf) { MOE_STORE_STAGE(u, 1) } else { MOE_STORE_STAGE(u, 0) }
+                const int buf = u & 1;
+                MOE_STORE_STAGE(u % PD, buf)
                 __syncthreads();
-                if (s + PD < nstage) { MOE_LOAD_STAGE(u, (s + PD) * KC) }
-                const float *wbase = Wgp + static_cast<size_t>(e0) * dP + s * KC;
-                const float *xrow = &xs[buf][lane][0];
-#pragma unroll 2
-                for (int ib = 0; ib < KC / 8; ++ib) {
-                    float w[EPT][8];
+                if (s + PD < nstage) MOE_LOAD_STAGE(u % PD, (s + PD) * kKC)
+                const float *xrow = xs + buf * TB * kLDX + tg * kLDX;
+                const float *wrow = ws + buf * EP * kLDX + eg * kLDX;
+#pragma unroll 4
+                for (int i4 = 0; i4 < kKC / 4; ++i4) {
+                    f32x4 xv[TPL], wv[EPL];
 #pragma unroll
-                    for (int q = 0; q < EPT; ++q)
+                    for (int a = 0; a < TPL; ++a)
+                        xv[a] = *reinterpret_cast<const f32x4 *>(xrow + a * TG * kLDX + i4 * 4);
 #pragma unroll
-                        for (int i = 0; i < 8; ++i)
-                            w[q][i] = wbase[static_cast<size_t>(q) * dP + ib * 8 + i];
-                    const f32x4 xa = *reinterpret_cast<const f32x4 *>(xrow + ib * 8);
-                    const f32x4 xb = *reinterpret_cast<const f32x4 *>(xrow + ib * 8 + 4);
-                    const float xv[8] = {xa[0], xa[1], xa[2], xa[3], xb[0], xb[1], xb[2], xb[3]};
+                    for (int b = 0; b < EPL; ++b)
+                        wv[b] = *reinterpret_cast<const f32x4 *>(wrow + b * NG * kLDX + i4 * 4);
 #pragma unroll
-                    for (int i = 0; i < 8; ++i)
+                    for (int c = 0; c < 4; ++c)
 #pragma unroll
-                        for (int q = 0; q < EPT; ++q)
-                            acc[q] = __builtin_fmaf(xv[i], w[q][i], acc[q]);
+                        for (int a = 0; a < TPL; ++a)
+#pragma unroll
+                            for (int b = 0; b < EPL; ++b)
+                                acc[a][b] = __builtin_fmaf(xv[a][c], wv[b][c], acc[a][b]);
                 }
             }
         }
     }
 #undef MOE_LOAD_STAGE
 #undef MOE_STORE_STAGE
-    __syncthreads();           // every wavefront is done with the token tile: reuse it for logits
+    __syncthreads();           // every wavefront is done with the tiles: reuse them for logits
 
-    const int t = t0 + lane;
 #pragma unroll
-    for (int q = 0; q < EPT; ++q) {
-        const int e = e0 + q;
-        if (e < E) {
-            float z = acc[q];
-            if (bias != nullptr && t < T)
-                z = z + bias[static_cast<size_t>(t) * bias_stride + e];
-            zs[lane][e] = z;
+    for (int a = 0; a < TPL; ++a) {
+        const int tl = a * TG + tg;
+        const int t = t0 + tl;
+#pragma unroll
+        for (int b = 0; b < EPL; ++b) {
+            const int e = b * NG + eg;
+            if (active && e < E) {
+                float z = acc[a][b];
+                if (bias != nullptr && t < T)
+                    z = z + bias[static_cast<size_t>(t) * bias_stride + e];
+                zs[tl][e] = z;
+            }
         }
     }
     __syncthreads();
-    if (wave != 0) return;
-    // The first wavefront finishes the block's 64 tokens: top-k, softmax weights and, for the
-    // layer call, the expert histogram of these tokens (one segment of the dispatch plan).
-    // The histogram sits behind the logits in the reused token-tile memory.
-    int32_t *cnt = reinterpret_cast<int32_t *>(&zs[kTok][0]);
+    if (tid >= kWave) return;
+    const int lane = tid;
+    const int t = t0 + lane;
+    // The histogram sits behind the logits in the reused tile memory.
+    int32_t *cnt = reinterpret_cast<int32_t *>(&zs[kWave][0]);
     if (seg_cnt != nullptr) cnt[lane] = 0;
     __builtin_amdgcn_wave_barrier();
-    if (t < T) {
+    if (lane < TB && t < T) {
     // softmax denominator over all E experts
     float zmax = zs[lane][0];
     for (int e = 1; e < E; ++e) zmax = fmaxf(zmax, zs[lane][e]);
@@ -226,6 +257,30 @@ int pow2_ceil(int v)
 
 int padded_dim(int d) { return (d + kGatePad - 1) / kGatePad * kGatePad; }
 
+// Register block of chains per lane and tokens per block for a layer shape: the largest
+// block that still leaves about eight wavefronts per compute unit, a block of 256 lanes
+// covering at most 64 tokens (the tail and the plan's segments are one wavefront wide).
+struct RouteShape {
+    int tpl, epl, tb;
+};
+
+RouteShape route_shape(const moe_shape &s)
+{
+    static const int cand[5][2] = {{4, 4}, {2, 4}, {2, 2}, {1, 2}, {1, 1}};
+    const int EP = pow2_ceil(s.E);
+    const long chains = static_cast<long>(s.T) * EP;
+    for (int c = 0; c < 5; ++c) {
+        const int tpl = cand[c][0], epl = cand[c][1];
+        if (epl > EP) continue;
+        const int ng = EP / epl;
+        const int tb = std::min(64, 256 * tpl / ng);
+        if (tb < tpl) continue;
+        const bool last = c == 4;
+        if (last || chains / (tpl * epl) >= 131072) return {tpl, epl, tb};
+    }
+    return {1, 1, std::min(64, 256 / EP)};
+}
+
 template <typename XT>
 moe_status launch_route_t(const moe_shape &s, const XT *x, const float *Wgp,
                           const float *bias, int bias_stride, int32_t *expert_idx,
@@ -233,29 +288,30 @@ moe_status launch_route_t(const moe_shape &s, const XT *x, const float *Wgp,
 {
     const int EP = pow2_ceil(s.E);
     const int dP = padded_dim(s.d_model);
-    const int blocks = ceil_div(s.T, kTok);
-    // Largest expert slice per lane (at most 4: the weights of a slice live in scalar
-    // registers) that still leaves about four wavefronts per SIMD in flight; a block
-    // holds at most 16 wavefronts.
-    int ept = 4;
-    while (ept > 1 && (ept > EP || static_cast<long>(blocks) * (EP / ept) < 4096)) ept >>= 1;
-    while (EP / ept > 16) ept <<= 1;
-    const int nw = EP / ept;
-    const dim3 grid(blocks), block(nw * kWave);
-#define MOE_ROUTE_CASE(EPT_, NW_)                                                            \
-    if (ept == EPT_ && nw == NW_) {                                                          \
-        hipLaunchKernelGGL((route_kernel<XT, EPT_, NW_>), grid, block, 0, st, x, Wgp, bias,  \
-                           bias_stride, expert_idx, gate, seg_cnt, s.T, s.d_model, dP, s.E,  \
-                           s.k, s.renorm_topk);                                              \
-        launched = true;                                                                     \
+    const RouteShape rs = route_shape(s);
+    const int blocks = ceil_div(s.T, rs.tb);
+    const size_t tiles = sizeof(float) * 2 * (rs.tb + EP) * kLDX;
+    const size_t logits = sizeof(float) * (kWave + 2) * (kMaxExperts + 1);
+    const size_t lds = std::max(tiles, logits);
+#define MOE_ROUTE_CASE(TPL_, EPL_)                                                            \
+    if (rs.tpl == TPL_ && rs.epl == EPL_) {                                                   \
+        auto kern = route_kernel<XT, TPL_, EPL_>;                                             \
+        static bool configured = false;                                                       \
+        if (!configured) {                                                                    \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                   \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024); \
+            configured = true;                                                                \
+        }                                                                                     \
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, x, Wgp, bias, bias_stride, \
+                           expert_idx, gate, seg_cnt, s.T, s.d_model, dP, s.E, EP, rs.tb,     \
+                           s.k, s.renorm_topk);                                               \
+        launched = true;                                                                      \
     }
     bool launched = false;
-    MOE_ROUTE_CASE(4, 16) MOE_ROUTE_CASE(4, 8) MOE_ROUTE_CASE(4, 4) MOE_ROUTE_CASE(4, 2) MOE_ROUTE_CASE(4, 1)
-    MOE_ROUTE_CASE(2, 16) MOE_ROUTE_CASE(2, 8) MOE_ROUTE_CASE(2, 4) MOE_ROUTE_CASE(2, 2) MOE_ROUTE_CASE(2, 1)
-    MOE_ROUTE_CASE(1, 16) MOE_ROUTE_CASE(1, 8) MOE_ROUTE_CASE(1, 4) MOE_ROUTE_CASE(1, 2) MOE_ROUTE_CASE(1, 1)
+    MOE_ROUTE_CASE(4, 4) MOE_ROUTE_CASE(2, 4) MOE_ROUTE_CASE(2, 2) MOE_ROUTE_CASE(1, 2) MOE_ROUTE_CASE(1, 1)
 #undef MOE_ROUTE_CASE
     if (!launched) {
-        set_error("route: internal error, expert slice %d x %d wavefronts", ept, nw);
+        set_error("route: internal error, register block %d x %d", rs.tpl, rs.epl);
         return MOE_EINVAL;
     }
     MOE_TRY_HIP(hipGetLastError());
@@ -263,6 +319,8 @@ moe_status launch_route_t(const moe_shape &s, const XT *x, const float *Wgp,
 }
 
 }  // namespace
+
+int route_segment_tokens(const moe_shape &s) { return route_shape(s).tb; }
 
 size_t packed_gate_bytes(const moe_shape &s)
 {
