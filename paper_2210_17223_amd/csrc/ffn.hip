@@ -447,6 +447,8 @@ void launch_mfma(const GemmPlan &gp, const uint16_t *A, const uint16_t *W, const
 {
     if (gp.bm == 256)
         launch_mfma_cfg<F16, TOut, ACT, 2, 4, 4, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, stage, st);
+    else if (gp.bm == 64)
+        launch_mfma_cfg<F16, TOut, ACT, 1, 8, 2, 1>(A, W, bias, C, items, nitems, gp.max_items, N, K, stage, st);
     else if (gp.bn == 256)
         launch_mfma_cfg<F16, TOut, ACT, 2, 4, 2, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, stage, st);
     else
@@ -488,6 +490,12 @@ GemmPlan choose_gemm_plan(const moe_shape &s, int which, int n_chunks)
         const int64_t big_tiles = (chunk_rows / 256 + s.E / 2) * ((N + 255) / 256);
         if (big_tiles >= 768) {
             gp.bm = 256; gp.bn = 256; gp.concurrent = 32;
+        } else if (K >= 2048 && N >= 256 && chunk_rows / s.E < 96 &&
+                   (chunk_rows / 128 + s.E / 2) * ((N + 255) / 256) < 256) {
+            // few rows per expert and fewer 128-row tiles than compute units: the GEMM
+            // streams the weights once; shorter tiles put more units on the stream and
+            // spend less of their loads on (mostly padded) rows
+            gp.bm = 64; gp.bn = 256; gp.concurrent = 32;
         } else if (K >= 2048 && N >= 256) {
             gp.bm = 128; gp.bn = 256; gp.concurrent = 32;
         } else {
