@@ -29,7 +29,7 @@ INFINITY_CACHE_BYTES = 256 << 20
 # --pmc WRITE_SIZE runs of this script (readings and scale factors: profiles/).  The
 # counters cannot be read from inside the process, so the figure is a stored measurement,
 # reported only for the workload and launch configuration it was taken on.
-GEMM1_TRAFFIC_BYTES = {("gpt2s_moe", 1): (69011 * 2.0 + 49246 * 1.0) * 1024}
+GEMM1_TRAFFIC_BYTES = {("gpt2s_moe", 1): (68752.4 * 2.0 + 50056.2 * 1.0) * 1024}
 
 
 def main() -> int:
