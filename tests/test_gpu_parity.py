@@ -170,3 +170,50 @@ def test_everything_to_one_expert_and_empty_experts():
         y = L.b["y"].cpu().numpy().reshape(li.T, li.d)
         assert rel_rms_err(y, o.y) <= TOL["bf16"]
         assert not y[300:].any()
+
+
+# Shapes that select each register block of the gate kernel (tokens x experts per lane,
+# chosen from T x E), few experts (lanes that only stage tiles), E not a power of two,
+# a model dimension that is no multiple of the 64-column stage, both dtypes and strides of
+# the bias.  The layer call also takes its plan histogram from the gate kernel, in
+# segments of the gate block's tokens.
+GATE_SHAPES = [
+    # name,            base,        T,     d,   E,  k, cf
+    ("block_1x2",      "gpt2s_moe", 8192,  128, 32, 2, 1.0),
+    ("block_2x2",      "skewed",    16384, 128, 32, 2, 1.25),
+    ("block_2x4",      "gpt2s_moe", 16384, 64,  64, 2, 1.0),
+    ("block_4x4",      "gpt2s_moe", 32768, 64,  64, 1, 1.25),
+    ("block_1x2_e3",   "gpt2s_moe", 65536, 72,  3,  2, 0.5),
+    ("block_1x2_f32",  "tiny_fp32", 8192,  100, 32, 2, 1.0),
+    ("e64_few_tokens", "gpt2s_moe", 100,   200, 64, 2, 2.0),
+    ("e2",             "gpt2s_moe", 3000,  136, 2,  1, 0.75),
+]
+
+
+@pytest.mark.parametrize("name,base,T,d,E,k,cf", GATE_SHAPES, ids=[g[0] for g in GATE_SHAPES])
+def test_gate_register_blocks_and_segments(name, base, T, d, E, k, cf):
+    cfg = wl.scaled(base, T=T, d=d, h=64, E=E, k=k, cf=cf)
+    li = wl.make_layer(cfg, seed=11, threads=8)
+    if name == "block_4x4":                     # per-token bias on the largest shape
+        prng = np.random.Generator(np.random.PCG64(5))
+        li.gate_bias = (0.05 * prng.standard_normal((T, E))).astype(np.float32)
+        li.bias_token_stride = E
+    sample = np.unique(np.concatenate([np.arange(48), np.arange(T - 48, T),
+                                       np.arange(0, T, max(1, T // 64))])).astype(np.int32)
+    o = oracle.moe_layer(li.x, li.Wg, li.W1, li.W2, k=li.k, capacity=li.C, bias=li.gate_bias,
+                         bias_stride=li.bias_token_stride, tokens=sample)
+    s = shape_of(li)
+    L = DeviceLayer(li, s, n_chunks=2)
+    b = L.b
+    # the gate alone
+    moe.moe_route(s, L.x, b["Wgp"], L.bias, L.bias_stride, b["expert_idx"], b["gate"])
+    torch.cuda.synchronize()
+    assert np.array_equal(b["expert_idx"].cpu().numpy().reshape(T, k), o.expert_idx)
+    np.testing.assert_allclose(b["gate"].cpu().numpy().reshape(T, k), o.gate, rtol=1e-6)
+    # the layer: plan from the gate kernel's per-block histogram
+    for n_chunks in (1, 2):
+        b["expert_idx"].zero_()
+        L.layer(n_chunks)
+        assert_ints_equal(L.ints(), o)
+        y = b["y"].cpu().numpy().reshape(T, d)[sample]
+        assert rel_rms_err(y, o.y) <= TOL[li.dtype if li.dtype == "bf16" else "f32"]
