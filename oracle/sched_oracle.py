@@ -27,7 +27,10 @@ def path_index(sel: np.ndarray, i: int, t: int, l: int, E: int) -> int:
     paper's inference runs use k = 1.)"""
     j = 0
     for m in range(i - l + 1, i + 1):
-        j = j * E + int(sel[m][t][0])
+        e = int(sel[m][t][0])
+        if not 0 <= e < E:
+            return -1          # (reading: a token carrying a non-expert id, e.g. padding, is skipped)
+        j = j * E + e
     return j
 
 
@@ -42,6 +45,8 @@ def profile_counts(sel: np.ndarray, l: int, E: int) -> List[np.ndarray]:
         C = np.zeros((E ** l, E), dtype=np.int64)
         for t in range(T):
             j = path_index(sel, i, t, l, E)
+            if j < 0 or any(not 0 <= int(sel[i + 1][t][c]) < E for c in range(k)):
+                continue
             for c in range(k):
                 C[j][int(sel[i + 1][t][c])] += 1
         out.append(C)
@@ -73,6 +78,8 @@ def estimate(C: np.ndarray, sel_hist: np.ndarray, k: int, E: int) -> Tuple[List[
     listed = [False] * E
     for t in range(T):
         j = path_index(sel_hist, l - 1, t, l, E)
+        if j < 0:
+            continue
         experts, probs = row_topk(C[j], k)
         for e, q in zip(experts, probs):
             S[e] += q

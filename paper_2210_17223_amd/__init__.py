@@ -1,6 +1,7 @@
 """MI355X-native one-GPU MoE-layer forward (libmoe) and its thin Python binding.
 
-The HIP kernels live in csrc/ behind the C-ABI declared in include/moe.h; this
+The HIP kernels live in csrc/ behind the C-ABI declared in include/moe.h and
+include/moe_sched.h; this
 package only marshals arguments.  PyTorch is used for device memory and streams.
 """
 from .binding import (ACT, DTYPE, MoeError, Shape, alloc_buffers, lib, lib_path,
@@ -10,7 +11,14 @@ from .binding import (ACT, DTYPE, MoeError, Shape, alloc_buffers, lib, lib_path,
                       moe_profile_enable, moe_profile_read, moe_route, moe_workspace_bytes,
                       STAGES)
 
-__all__ = ["ACT", "DTYPE", "MoeError", "Shape", "alloc_buffers", "lib", "lib_path",
+from .sched_binding import (PathShape, moe_devices_for_expert, moe_path_count, moe_path_finalize,
+                            moe_path_profile, moe_popularity_estimate, moe_schedule_experts,
+                            moe_schedule_layer, moe_top_lists_identical)
+
+__all__ = ["PathShape", "moe_devices_for_expert", "moe_path_count", "moe_path_finalize",
+           "moe_path_profile", "moe_popularity_estimate", "moe_schedule_experts",
+           "moe_schedule_layer", "moe_top_lists_identical",
+           "ACT", "DTYPE", "MoeError", "Shape", "alloc_buffers", "lib", "lib_path",
            "moe_capacity", "moe_combine", "moe_dispatch", "moe_expert_ffn",
            "moe_last_error", "moe_layer_chunked", "moe_max_rows", "moe_pack_gate",
            "moe_pack_weights", "moe_packed_gate_bytes", "moe_packed_weight_bytes",
