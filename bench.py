@@ -38,7 +38,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="gpt2s_moe",
-                    help="one of workloads.CONFIGS (default: the configuration the metric is quoted on)")
+                    help="one of workloads.CONFIGS (default: the configuration the metric is quoted on), "
+                         "or 'popularity': the inference scheduler's estimate + two-phase decision")
     ap.add_argument("--chunks", type=int, default=1, help="n_chunks of moe_layer_chunked")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true",
@@ -76,6 +77,8 @@ def main() -> int:
         return 3
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.workload == "popularity":
+        return bench_popularity(args, moe, np, torch, dev)
     cfg = wl.CONFIGS[args.workload]
     n_layers = cfg["layers"]
     host = wl.make_stack(cfg, seed=0, threads=16) if n_layers > 1 else [wl.make_layer(cfg, seed=0, threads=16)]
@@ -284,6 +287,103 @@ def main() -> int:
                                "sample": f"{passes} pass(es) over {n_layers} layer(s): gate+plan over all "
                                          f"{l0.T} tokens, expert FFN+combine for the first {sample} "
                                          f"tokens, {elapsed:.2f} s wall"}
+    print(json.dumps(out))
+    return 0
+
+
+def bench_popularity(args, moe, np, torch, dev) -> int:
+    """The inference scheduler of Sec. 5.2 on the paper's inference shape (Sec. 7.1: 12 MoE
+    layers, 16 experts, k = 1, sample-path length 3, at most 4 experts packed per device,
+    one device per expert).  A step = one batch through all nine layers that have a
+    three-layer history: estimate on the GPU, the estimate's 16 sums to the host, both
+    scheduling phases on the host.  Also reports the estimation accuracy the paper's way
+    (share of layers whose top-2k lists are identical)."""
+    from workloads import paths
+    L, E, k, l, N, max_pack = 12, 16, 1, 3, 16, 4
+    N_t, T_prof = 8192, 1 << 20
+    s = moe.PathShape(L, E, k, l)
+    P, tables = moe.moe_path_count(s), L - l
+    out = {"metric": "popularity_schedule_tokens_per_s", "unit": "tokens/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+           "config": {"workload": f"popularity: L={L} E={E} k={k} l={l} N={N} max_pack={max_pack}, "
+                                  f"{T_prof} profiled tokens, batches of {N_t}, seeded traces"}}
+    acc = {}
+    for kind in ("latent", "markov"):
+        trace = paths.trace_generator(kind)(0, L, T_prof + 64 * N_t, E, k)
+        prof = torch.from_numpy(np.ascontiguousarray(trace[:, :T_prof])).to(dev)
+        counts = torch.zeros(tables * P * E, dtype=torch.int32, device=dev)
+        top_e = torch.empty(tables * P * k, dtype=torch.int32, device=dev)
+        top_q = torch.empty(tables * P * k, dtype=torch.int64, device=dev)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        moe.moe_path_profile(s, prof, T_prof, counts)
+        moe.moe_path_finalize(s, counts, top_e, top_q)
+        torch.cuda.synchronize()
+        build_ms = (time.perf_counter() - t0) * 1e3
+        S_dev = torch.empty(E, dtype=torch.int64, device=dev)
+        batches = [torch.from_numpy(np.ascontiguousarray(trace[:, T_prof + b * N_t:T_prof + (b + 1) * N_t])).to(dev)
+                   for b in range(64)]
+        hits = total = resched = 0
+
+        def one_batch(bt, score):
+            nonlocal hits, total, resched
+            for a in range(tables):
+                moe.moe_popularity_estimate(s, bt[a:a + l], N_t, top_e[a * P * k:(a + 1) * P * k],
+                                            top_q[a * P * k:(a + 1) * P * k], S_dev)
+                S = S_dev.cpu().numpy().view(np.uint64)
+                cnt = torch.bincount(bt[a + l].reshape(-1), minlength=E).to(torch.int32).cpu().numpy()
+                again = moe.moe_schedule_layer(N, E, k, N_t, S, cnt, max_pack)[4]
+                if score:
+                    hits += 0 if again else 1
+                    resched += 1 if again else 0
+                    total += 1
+
+        for b in range(args.warmup):
+            one_batch(batches[b % 64], False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for b in range(args.steps):
+            one_batch(batches[b % 64], b < 64)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        acc[kind] = {"top2k_lists_identical": hits / total, "phase_two_reschedules": resched / total,
+                     "table_build_ms": build_ms, "ms_per_batch": ms}
+        if kind == "latent":
+            # the estimate kernel alone, timed with events on its stream
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            ev[0].record()
+            for _ in range(200):
+                moe.moe_popularity_estimate(s, batches[0][0:l], N_t, top_e[:P * k], top_q[:P * k], S_dev)
+            ev[1].record()
+            torch.cuda.synchronize()
+            est_us = ev[0].elapsed_time(ev[1]) * 1e3 / 200
+            bytes_per_launch = N_t * (l * k * 4 + k * 12) + E * 8
+            out.update({"value": N_t / (ms * 1e-3), "ms_per_step": ms})
+            out["roofline"] = {"bound": "hbm", "kernel": "popularity_estimate_kernel (+ its 64-lane clear)",
+                               "achieved": bytes_per_launch / (est_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBPS,
+                               "unit": "GB/s", "frac": bytes_per_launch / (est_us * 1e-6) / 1e9 / PEAK_HBM_GBPS,
+                               "traffic": None, "avg_launch_us": est_us,
+                               "algorithmic_bytes": bytes_per_launch,
+                               "note": "two launches over 8192 tokens: bound by launch latency, not by bytes"}
+            if not args.no_cpu_baseline:
+                from oracle import sched_oracle as so
+                sample = 4096
+                C = so.profile_counts(trace[:, :sample], l, E)        # tables from a bounded sample
+                hist = trace[:, T_prof:T_prof + sample]
+                c0 = time.perf_counter()
+                n = 0
+                while time.perf_counter() - c0 < 10.0:
+                    for a in range(tables):
+                        so.two_phase(C[a], hist[a:a + l], hist[a + l], E, k, N, max_pack)
+                    n += 1
+                el = time.perf_counter() - c0
+                out["cpu_baseline"] = {"value": sample * n / el, "unit": "tokens/s", "cores": 1,
+                                       "kind": "oracle",
+                                       "sample": f"{n} pass(es) of estimate + two-phase decision for {sample} "
+                                                 f"tokens over {tables} layers (tables from {sample} profiled "
+                                                 f"tokens), {el:.2f} s wall"}
+    out["estimation"] = acc
     print(json.dumps(out))
     return 0
 

@@ -100,7 +100,8 @@ double moe_devices_for_expert(uint64_t S_e, int32_t N_t, int32_t N);
  * host.  Phase-1 scheduling from integer weights: expert e should get w[e] / W devices
  * (w = N * S, W = N_t * 2^32 for the estimate; w = N * count, W = N_t * k for the actual
  * popularity).  What the paper leaves open is fixed as follows:
- *   - an expert with w >= W is replicated on round-half-up(w / W) devices of its own;
+ *   - an expert with w >= W is replicated on round-half-up(w / W) devices of its own
+ *     (at most N);
  *   - the others are packed first-fit-decreasing (weight descending, then expert index)
  *     into devices of capacity W holding at most max_pack experts (Sec. 7.1: 4);
  *   - experts with has[e] == 0 (no estimate) go round-robin, in index order, onto the

@@ -98,7 +98,8 @@ def schedule(w: Sequence[int], W: int, has: Sequence[bool], N: int, max_pack: in
     and W = N_t * k).
 
     Readings of what the paper leaves open:
-    * an expert with n_e >= 1 is replicated on round-half-up(n_e) devices of its own;
+    * an expert with n_e >= 1 is replicated on round-half-up(n_e) devices of its own (at
+      most N);
     * experts with n_e < 1 are items of size n_e for first-fit-decreasing into devices of
       capacity 1 holding at most max_pack experts (Sec. 7.1: 4); order: size descending,
       then expert index;
@@ -116,7 +117,7 @@ def schedule(w: Sequence[int], W: int, has: Sequence[bool], N: int, max_pack: in
         if not has[e]:
             continue
         if w[e] >= W:
-            r = (2 * w[e] + W) // (2 * W)
+            r = min((2 * w[e] + W) // (2 * W), N)
             replicas[e] = r
             for _ in range(r):
                 groups.append([e])

@@ -95,8 +95,9 @@ __global__ void zero_u64_kernel(unsigned long long *p, int n)
     if (i < n) p[i] = 0ull;
 }
 
-// One thread per token; a block sums its tokens' contributions in LDS and adds them to
-// S with one 64-bit atomic per expert.  Integer sums: the result does not depend on order.
+// A block walks its share of the tokens, sums their contributions in LDS and adds them to
+// S with one 64-bit atomic per expert (few blocks: the atomics of all blocks hit the same E
+// addresses).  Integer sums: the result does not depend on the order.
 __global__ __launch_bounds__(256) void popularity_estimate_kernel(
     const int32_t *__restrict__ hist, const int32_t *__restrict__ top_expert,
     const unsigned long long *__restrict__ top_prob, unsigned long long *__restrict__ S,
@@ -105,14 +106,12 @@ __global__ __launch_bounds__(256) void popularity_estimate_kernel(
     __shared__ unsigned long long acc[kMaxExperts];
     if (threadIdx.x < kMaxExperts) acc[threadIdx.x] = 0ull;
     __syncthreads();
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < N_t) {
+    for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < N_t; t += gridDim.x * blockDim.x) {
         const int j = path_of(hist, static_cast<size_t>(N_t) * k, t, k, l, E);
-        if (j >= 0) {
-            for (int c = 0; c < k; ++c) {
-                const int e = top_expert[static_cast<size_t>(j) * k + c];
-                if (e >= 0) atomicAdd(&acc[e], top_prob[static_cast<size_t>(j) * k + c]);
-            }
+        if (j < 0) continue;
+        for (int c = 0; c < k; ++c) {
+            const int e = top_expert[static_cast<size_t>(j) * k + c];
+            if (e >= 0) atomicAdd(&acc[e], top_prob[static_cast<size_t>(j) * k + c]);
         }
     }
     __syncthreads();
@@ -142,7 +141,7 @@ Schedule schedule_experts(int N, int E, const uint64_t *w, uint64_t W, const uin
             // round half up of w / W, without forming 2w + W (which could overflow)
             const uint64_t q = w[e] / W, rem = w[e] % W;
             const uint64_t r = q + (rem >= W - rem ? 1 : 0);
-            out.replicas[e] = static_cast<int32_t>(std::min<uint64_t>(r, 1u << 30));
+            out.replicas[e] = static_cast<int32_t>(std::min<uint64_t>(r, N));   // never more than all devices
             for (int32_t i = 0; i < out.replicas[e]; ++i) groups.push_back({e});
         } else {
             small.push_back(e);
@@ -305,7 +304,8 @@ moe_status moe_popularity_estimate(const moe_path_shape *s, const int32_t *sel_h
     unsigned long long *Sd = reinterpret_cast<unsigned long long *>(S);
     hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(kMaxExperts), 0, st, Sd, s->E);
     if (N_t > 0)
-        hipLaunchKernelGGL(popularity_estimate_kernel, dim3((N_t + 255) / 256), dim3(256), 0, st,
+        hipLaunchKernelGGL(popularity_estimate_kernel,
+                           dim3(std::min(256, (N_t + 1023) / 1024)), dim3(256), 0, st,
                            sel_hist, top_expert,
                            reinterpret_cast<const unsigned long long *>(top_prob), Sd, N_t, s->E,
                            s->k, s->l);

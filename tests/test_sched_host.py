@@ -59,7 +59,7 @@ def test_random_schedules_match_the_oracle():
         elif style == 1:     # a few heavy experts
             w = rng.integers(0, W // 4 + 2, size=E)
             heavy = rng.random(E) < 0.15
-            w = np.where(heavy, rng.integers(W, 6 * W + 1, size=E), w)
+            w = np.where(heavy, rng.integers(W, (60 if rng.random() < 0.2 else 6) * W + 1, size=E), w)
         else:                # many ties
             w = rng.choice([0, W // 3, W // 2, W, 3 * W // 2], size=E)
         has = (rng.random(E) < 0.8) & (w > 0) if style != 2 else rng.random(E) < 0.7
