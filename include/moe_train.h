@@ -1,0 +1,62 @@
+/*
+ * libmoe -- backward pass of the one-GPU MoE layer (the training half of the paper:
+ * Sec. 2.1's layer is trained, and Sec. 2.2 / Sec. 4 schedule its backward pass).
+ *
+ * The gradients are the chain rule of the forward definition in moe.h for a loss L whose
+ * gradient with respect to the layer output y is given as dy:
+ *
+ *   dye[slot]  = g[t,j] * dy[t]                 for every kept assignment (t, j)
+ *   dgate[t,j] = <ye[slot], dy[t]>              (0 for dropped assignments)
+ *   dP         = (dye . W2[e]^T) * act'(P)      P = xe . W1[e], recomputed here
+ *   dW2[e]     = act(P)^T . dye                 rows of expert e
+ *   dW1[e]     = xe^T . dP
+ *   dxe        = dP . W1[e]^T
+ *   dz[t,:]    = p * (dgfull - <p, dgfull>)     p = softmax of the token's logits,
+ *                                               dgfull[e] = dgate[t,j] where e = e(t,j)
+ *   dx[t]      = sum_j kept dxe[slot(t,j)] + dz[t,:] . Wg^T
+ *   dWg        = x^T . dz
+ *
+ * Routing (which experts, which slots, what is dropped) is piecewise constant and carries
+ * no gradient.  bf16 layers only; no FFN biases; renorm_topk must be 0.  The contractions
+ * run on bf16 MFMA with fp32 accumulation: dye, dP and the recomputed act(P) are rounded to
+ * bf16 as GEMM operands, every returned gradient is fp32.
+ *
+ * Conventions as in moe.h: device pointers, enqueue only, caller-owned buffers, status
+ * codes, moe_last_error.
+ */
+#ifndef MOE_TRAIN_H
+#define MOE_TRAIN_H
+
+#include "moe.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Bytes of workspace moe_layer_backward needs for this shape (0 if unsupported). */
+size_t moe_backward_workspace_bytes(const moe_shape *s);
+
+/*
+ * All gradients of one layer.
+ *   forward inputs   x [T,d]; Wg [d,E]; gate_bias, bias_token_stride as given to moe_route;
+ *                    W1 [E,d,h], W2 [E,h,d] in their canonical layouts; W1p the packed W1 of
+ *                    moe_pack_weights
+ *   forward outputs  expert_idx, gate, offsets, slot_of, src_of, xe, ye exactly as the
+ *                    forward call left them
+ *   dy               [T,d] fp32
+ *   dx [T,d], dWg [d,E], dW1 [E,d,h], dW2 [E,h,d], dgate [T*k]: fp32, overwritten (weight
+ *                    gradients of an expert without rows are zero)
+ */
+moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wg,
+                              const float *gate_bias, int32_t bias_token_stride,
+                              const void *W1, const void *W2, const void *W1p,
+                              const int32_t *expert_idx, const float *gate,
+                              const int32_t *offsets, const int32_t *slot_of,
+                              const int32_t *src_of, const void *xe, const float *ye,
+                              const float *dy, float *dx, float *dWg, float *dW1, float *dW2,
+                              float *dgate, void *workspace, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_TRAIN_H */

@@ -1,7 +1,7 @@
 """MI355X-native one-GPU MoE-layer forward (libmoe) and its thin Python binding.
 
 The HIP kernels live in csrc/ behind the C-ABI declared in include/moe.h and
-include/moe_sched.h; this
+include/moe_sched.h, include/moe_train.h; this
 package only marshals arguments.  PyTorch is used for device memory and streams.
 """
 from .binding import (ACT, DTYPE, MoeError, Shape, alloc_buffers, lib, lib_path,
@@ -15,7 +15,9 @@ from .sched_binding import (PathShape, moe_devices_for_expert, moe_path_count, m
                             moe_path_profile, moe_popularity_estimate, moe_schedule_experts,
                             moe_schedule_layer, moe_top_lists_identical)
 
-__all__ = ["PathShape", "moe_devices_for_expert", "moe_path_count", "moe_path_finalize",
+from .train_binding import moe_backward_workspace_bytes, moe_layer_backward
+
+__all__ = ["moe_backward_workspace_bytes", "moe_layer_backward", "PathShape", "moe_devices_for_expert", "moe_path_count", "moe_path_finalize",
            "moe_path_profile", "moe_popularity_estimate", "moe_schedule_experts",
            "moe_schedule_layer", "moe_top_lists_identical",
            "ACT", "DTYPE", "MoeError", "Shape", "alloc_buffers", "lib", "lib_path",

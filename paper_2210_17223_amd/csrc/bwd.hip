@@ -1,0 +1,646 @@
+// Backward pass of the MoE layer (chain rule of the forward of paper Sec. 2.1; the paper
+// trains this layer and schedules its backward pass in Sec. 2.2 and Sec. 4).
+//
+//   combine_bwd      dye[slot] = g dy[t] (bf16), dgate = <ye[slot], dy[t]>
+//   gemm (rows)      P = xe W1 (recomputed; fp16) and Hb = act(P) (bf16)
+//   gemm (rows)      dP = (dye W2^T) * act'(P)                        (bf16)
+//   gemm (rows)      dxe = dP W1^T                                    (fp32)
+//   transposes       Hb, dye, xe, dP -> [columns][rows], each expert's rows padded to 64
+//   gemm (wgrad)     dW2[e] = Hb^T dye, dW1[e] = xe^T dP              (fp32)
+//   gate_bwd         logits, softmax, dz, dx = sum of the token's dxe rows + dz Wg^T
+//   dwg              dWg = x^T dz (partial sums over token ranges, then a fixed-order sum)
+//
+// The contractions use 128 x 128 output tiles of 32x32x16 bf16 MFMAs fed through a
+// double-buffered LDS tile, like the forward's expert GEMM; a row-grouped GEMM walks the
+// forward's kind of work list, a weight-gradient GEMM contracts over one expert's
+// (transposed, zero-padded) rows.
+#include "common.h"
+#include "moe_train.h"
+
+#include <algorithm>
+
+namespace moe {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+constexpr int kBM = 128, kBN = 128, kBK = 64, kLD = kBK + 8;
+constexpr size_t kGemmLds = 2 * (kBM + kBN) * kLD * sizeof(uint16_t);
+
+template <int ACT>
+__device__ __forceinline__ float act_value(float v)
+{
+    if constexpr (ACT == MOE_ACT_GELU_ERF)
+        return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f));
+    else if constexpr (ACT == MOE_ACT_GELU_TANH)
+        return 0.5f * v * (1.0f + tanhf(0.7978845608028654f * (v + 0.044715f * v * v * v)));
+    else if constexpr (ACT == MOE_ACT_RELU)
+        return fmaxf(v, 0.0f);
+    else
+        return v;
+}
+
+template <int ACT>
+__device__ __forceinline__ float act_derivative(float v)
+{
+    if constexpr (ACT == MOE_ACT_GELU_ERF) {
+        const float Phi = 0.5f * (1.0f + erff(v * 0.70710678118654752f));
+        const float pdf = 0.3989422804014327f * __expf(-0.5f * v * v);
+        return Phi + v * pdf;
+    } else if constexpr (ACT == MOE_ACT_GELU_TANH) {
+        const float c = 0.7978845608028654f, a = 0.044715f;
+        const float th = tanhf(c * (v + a * v * v * v));
+        return 0.5f * (1.0f + th) + 0.5f * v * (1.0f - th * th) * c * (1.0f + 3.0f * a * v * v);
+    } else if constexpr (ACT == MOE_ACT_RELU) {
+        return v > 0.0f ? 1.0f : 0.0f;
+    } else {
+        return 1.0f;
+    }
+}
+
+__device__ __forceinline__ void store_bf16x4(uint16_t *p, const float (&v)[4])
+{
+    u32x2 o;
+    o[0] = static_cast<uint32_t>(f32_to_bf16(v[0])) | (static_cast<uint32_t>(f32_to_bf16(v[1])) << 16);
+    o[1] = static_cast<uint32_t>(f32_to_bf16(v[2])) | (static_cast<uint32_t>(f32_to_bf16(v[3])) << 16);
+    *reinterpret_cast<u32x2 *>(p) = o;
+}
+
+// ---------------------------------------------------------------- combine backward
+// One wavefront per token.
+__global__ __launch_bounds__(256) void combine_bwd_kernel(
+    const float *__restrict__ dy, const float *__restrict__ ye, const int32_t *__restrict__ slot_of,
+    const float *__restrict__ gate, uint16_t *__restrict__ dye, float *__restrict__ dgate, int T,
+    int d, int k, int max_rows)
+{
+    const int lane = lane_id();
+    const int t = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    if (t >= T) return;
+    const float *dyrow = dy + static_cast<size_t>(t) * d;
+    for (int j = 0; j < k; ++j) {
+        const int slot = slot_of[static_cast<size_t>(t) * k + j];
+        if (slot < 0 || slot >= max_rows) {
+            if (lane == 0) dgate[static_cast<size_t>(t) * k + j] = 0.0f;
+            continue;
+        }
+        const float g = gate[static_cast<size_t>(t) * k + j];
+        const float *yerow = ye + static_cast<size_t>(slot) * d;
+        uint16_t *out = dye + static_cast<size_t>(slot) * d;
+        float dot = 0.0f;
+        for (int c = lane * 4; c < d; c += kWave * 4) {
+            const float4 a = *reinterpret_cast<const float4 *>(dyrow + c);
+            const float4 b = *reinterpret_cast<const float4 *>(yerow + c);
+            dot = __builtin_fmaf(a.x, b.x, dot);
+            dot = __builtin_fmaf(a.y, b.y, dot);
+            dot = __builtin_fmaf(a.z, b.z, dot);
+            dot = __builtin_fmaf(a.w, b.w, dot);
+            const float v[4] = {g * a.x, g * a.y, g * a.z, g * a.w};
+            store_bf16x4(out + c, v);
+        }
+#pragma unroll
+        for (int m = kWave / 2; m > 0; m >>= 1) dot += __shfl_xor(dot, m);
+        if (lane == 0) dgate[static_cast<size_t>(t) * k + j] = dot;
+    }
+}
+
+// ---------------------------------------------------------------- GEMM
+// MODE 0 (rows): C[r, n] = sum_k A[r, k] W[e][n, k] for the rows of one work item.
+// MODE 1 (weight gradient): C[e][m, n] = sum_k A[m, koff[e] + k] W[n, koff[e] + k],
+//   A and W being [M or N][lda] transposed activations, k over expert e's padded rows.
+// EPI 0: fp32 store.  EPI 1: P = acc as fp16 into Pbuf and act(acc) as bf16 into C.
+// EPI 2: acc * act'(Pbuf) as bf16 into C.
+template <int MODE, int EPI, int ACT, bool KTAIL>
+__global__ __launch_bounds__(256, 2) void bwd_gemm_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, void *__restrict__ Cout,
+    _Float16 *__restrict__ Pbuf, const WorkItem *__restrict__ items,
+    const int32_t *__restrict__ nitems, const int32_t *__restrict__ koff, int E, int M, int N,
+    int K, int tiles_m, int tiles_n)
+{
+    constexpr int WM = 2, TM = 2, TN = 2, NT = 256;   // 2 x 2 wavefronts of 64 x 64
+    constexpr int AV = kBM * 8 / NT, WV = kBN * 8 / NT;
+    int expert, row0, row1, n0, KT;
+    size_t a_pitch, a_base, w_base;
+    {
+        const int total = MODE == 0 ? *nitems : E * tiles_m * tiles_n;
+        const int per_xcd = (total + 7) / 8;
+        const int slot = blockIdx.x / 8;
+        const int idx = (blockIdx.x % 8) * per_xcd + slot;
+        if (slot >= per_xcd || idx >= total) return;
+        if constexpr (MODE == 0) {
+            const WorkItem item = items[idx];
+            expert = item.expert; row0 = item.row0; row1 = item.row1; n0 = item.n0;
+            KT = (K + kBK - 1) / kBK;
+            a_pitch = K;
+            a_base = 0;
+            w_base = static_cast<size_t>(expert) * N * K;
+        } else {
+            expert = idx / (tiles_m * tiles_n);
+            const int rem = idx % (tiles_m * tiles_n);
+            row0 = (rem / tiles_n) * kBM;
+            row1 = min(M, row0 + kBM);
+            n0 = (rem % tiles_n) * kBN;
+            KT = (koff[expert + 1] - koff[expert]) / kBK;
+            a_pitch = K;                       // K carries the row pitch of the transposed buffers
+            a_base = koff[expert];
+            w_base = koff[expert];
+        }
+    }
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    constexpr int A_BUF = kBM * kLD, W_BUF = kBN * kLD;
+    uint16_t *As = smem;
+    uint16_t *Ws = smem + 2 * A_BUF;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM;
+    const int fr = lane & 31, fk = (lane >> 5) * 8;
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    if (KT > 0) {
+        const uint16_t *a_src[AV];
+        const uint16_t *w_src[WV];
+        int a_off[AV], w_off[WV];
+        const int ld_col = (tid & 7) * 8;
+#pragma unroll
+        for (int q = 0; q < AV; ++q) {
+            const int r = (tid + NT * q) >> 3;
+            a_off[q] = r * kLD + ld_col;
+            a_src[q] = A + a_base + static_cast<size_t>(min(row0 + r, row1 - 1)) * a_pitch + ld_col;
+        }
+#pragma unroll
+        for (int q = 0; q < WV; ++q) {
+            const int r = (tid + NT * q) >> 3;
+            w_off[q] = r * kLD + ld_col;
+            w_src[q] = W + w_base + static_cast<size_t>(min(n0 + r, N - 1)) * a_pitch + ld_col;
+        }
+        u32x4 a_reg[AV], w_reg[WV];
+        u32x4 wf[2][TN], af[2][TM];
+        const int wfrag = (wn * TN * 32 + fr) * kLD + fk;
+        const int afrag = (wm * TM * 32 + fr) * kLD + fk;
+#define BWD_LOADG(kt_)                                                                          \
+    {                                                                                           \
+        const int k0_ = (kt_) * kBK;                                                            \
+        const bool in_ = !KTAIL || k0_ + ld_col < K;                                           \
+        _Pragma("unroll") for (int q = 0; q < AV; ++q)                                          \
+        {                                                                                       \
+            if (in_) a_reg[q] = *reinterpret_cast<const u32x4 *>(a_src[q] + k0_);               \
+            else a_reg[q] = (u32x4){0u, 0u, 0u, 0u};                                            \
+        }                                                                                       \
+        _Pragma("unroll") for (int q = 0; q < WV; ++q)                                          \
+        {                                                                                       \
+            if (in_) w_reg[q] = *reinterpret_cast<const u32x4 *>(w_src[q] + k0_);               \
+            else w_reg[q] = (u32x4){0u, 0u, 0u, 0u};                                            \
+        }                                                                                       \
+    }
+#define BWD_STOREL(buf)                                                                         \
+    {                                                                                           \
+        _Pragma("unroll") for (int q = 0; q < AV; ++q)                                          \
+            *reinterpret_cast<u32x4 *>(As + (buf) * A_BUF + a_off[q]) = a_reg[q];               \
+        _Pragma("unroll") for (int q = 0; q < WV; ++q)                                          \
+            *reinterpret_cast<u32x4 *>(Ws + (buf) * W_BUF + w_off[q]) = w_reg[q];               \
+    }
+#define BWD_READF(slot_, buf, ks)                                                               \
+    {                                                                                           \
+        _Pragma("unroll") for (int i = 0; i < TN; ++i) wf[slot_][i] =                           \
+            *reinterpret_cast<const u32x4 *>(Ws + (buf) * W_BUF + wfrag + i * 32 * kLD + (ks) * 16); \
+        _Pragma("unroll") for (int j = 0; j < TM; ++j) af[slot_][j] =                           \
+            *reinterpret_cast<const u32x4 *>(As + (buf) * A_BUF + afrag + j * 32 * kLD + (ks) * 16); \
+    }
+#define BWD_MMA(slot_)                                                                          \
+    {                                                                                           \
+        _Pragma("unroll") for (int j = 0; j < TM; ++j)                                          \
+            _Pragma("unroll") for (int i = 0; i < TN; ++i)                                      \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                            \
+                    __builtin_bit_cast(bf16x8, wf[slot_][i]),                                   \
+                    __builtin_bit_cast(bf16x8, af[slot_][j]), acc[i][j], 0, 0, 0);              \
+    }
+        BWD_LOADG(0)
+        BWD_STOREL(0)
+        if (KT > 1) BWD_LOADG(1)
+        __syncthreads();
+        BWD_READF(0, 0, 0)
+        for (int kt = 0; kt < KT; ++kt) {
+            const int buf = kt & 1;
+            const bool next1 = kt + 1 < KT, next2 = kt + 2 < KT;
+            if (next1) BWD_STOREL(buf ^ 1)
+            if (next2) BWD_LOADG(kt + 2)
+            BWD_READF(1, buf, 1)
+            BWD_MMA(0)
+            BWD_READF(0, buf, 2)
+            BWD_MMA(1)
+            BWD_READF(1, buf, 3)
+            BWD_MMA(0)
+            __syncthreads();
+            if (next1) BWD_READF(0, buf ^ 1, 0)
+            BWD_MMA(1)
+        }
+#undef BWD_LOADG
+#undef BWD_STOREL
+#undef BWD_READF
+#undef BWD_MMA
+    }
+
+    // acc[i][j][4*g + c]: column n0 + (wn*TN + i)*32 + 8*g + 4*(lane/32) + c,
+    //                     row row0 + (wm*TM + j)*32 + lane%32
+    const size_t c_base = MODE == 0 ? 0 : static_cast<size_t>(expert) * M * N;
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int r = row0 + (wm * TM + j) * 32 + fr;
+        if (r >= row1) continue;
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + (wn * TN + i) * 32 + 8 * g + 4 * (lane >> 5);
+                if (n >= N) continue;
+                const size_t at = c_base + static_cast<size_t>(r) * N + n;
+                float v[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[c] = acc[i][j][4 * g + c];
+                if constexpr (EPI == 0) {
+                    *reinterpret_cast<float4 *>(static_cast<float *>(Cout) + at) =
+                        make_float4(v[0], v[1], v[2], v[3]);
+                } else if constexpr (EPI == 1) {
+                    f16x4 p;
+                    float a[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        p[c] = static_cast<_Float16>(v[c]);
+                        a[c] = act_value<ACT>(v[c]);
+                    }
+                    *reinterpret_cast<f16x4 *>(Pbuf + at) = p;
+                    store_bf16x4(static_cast<uint16_t *>(Cout) + at, a);
+                } else {
+                    const f16x4 p = *reinterpret_cast<const f16x4 *>(Pbuf + at);
+                    float a[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) a[c] = v[c] * act_derivative<ACT>(static_cast<float>(p[c]));
+                    store_bf16x4(static_cast<uint16_t *>(Cout) + at, a);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- transposes
+// koff[e] = sum over earlier experts of their row counts rounded up to 64.
+__global__ void padded_offsets_kernel(const int32_t *__restrict__ offsets, int32_t *__restrict__ koff,
+                                      int E)
+{
+    const int e = threadIdx.x;
+    int incl = e < E ? (offsets[e + 1] - offsets[e] + 63) / 64 * 64 : 0;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int v = __shfl_up(incl, d);
+        if (e >= d) incl += v;
+    }
+    if (e < E) koff[e + 1] = incl;
+    if (e == 0) koff[0] = 0;
+}
+
+// out[m][koff[e] + i] = in[offsets[e] + i][m] for i < rows of expert e, 0 for the padding;
+// one block per 64 padded rows x 64 columns, through LDS.
+__global__ __launch_bounds__(256) void transpose_rows_kernel(
+    const uint16_t *__restrict__ in, uint16_t *__restrict__ out, const int32_t *__restrict__ offsets,
+    const int32_t *__restrict__ koff, int E, int M, int lda)
+{
+    __shared__ uint16_t tile[64][66];
+    const int kb = blockIdx.x * 64;
+    if (kb >= koff[E]) return;
+    int e = 0;
+    while (e + 1 < E && koff[e + 1] <= kb) ++e;
+    const int r_base = offsets[e] + (kb - koff[e]);
+    const int r_end = offsets[e + 1];
+    const int m0 = blockIdx.y * 64;
+    for (int v = threadIdx.x; v < 64 * 64; v += 256) {
+        const int rr = v / 64, mm = v % 64;
+        uint16_t val = 0;
+        if (r_base + rr < r_end && m0 + mm < M)
+            val = in[static_cast<size_t>(r_base + rr) * M + m0 + mm];
+        tile[rr][mm] = val;
+    }
+    __syncthreads();
+    for (int v = threadIdx.x; v < 64 * 64; v += 256) {
+        const int mm = v / 64, rr = v % 64;
+        if (m0 + mm < M) out[static_cast<size_t>(m0 + mm) * lda + kb + rr] = tile[rr][mm];
+    }
+}
+
+// ---------------------------------------------------------------- gate backward
+// One wavefront per token: logits (lane = expert), softmax, dz, then
+// dx[t, i] = sum of the token's kept dxe rows + sum_e dz[e] Wg[i, e] (lane = column).
+__global__ __launch_bounds__(256) void gate_bwd_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ Wg, const float *__restrict__ bias,
+    int bias_stride, const int32_t *__restrict__ expert_idx, const int32_t *__restrict__ slot_of,
+    const float *__restrict__ dgate, const float *__restrict__ dxe, float *__restrict__ dz,
+    float *__restrict__ dx, int T, int d, int E, int k, int max_rows)
+{
+    __shared__ float dzs[4][kMaxExperts];
+    const int lane = lane_id();
+    const int w = threadIdx.x / kWave;
+    const int t = blockIdx.x * 4 + w;
+    if (t >= T) return;
+    const uint16_t *xrow = x + static_cast<size_t>(t) * d;
+    const int e = lane;
+    float z = 0.0f;
+    if (e < E) {
+        for (int i = 0; i < d; ++i)
+            z = __builtin_fmaf(bf16_to_f32(xrow[i]), bf16_to_f32(Wg[static_cast<size_t>(i) * E + e]), z);
+        if (bias != nullptr) z += bias[static_cast<size_t>(t) * bias_stride + e];
+    }
+    float zmax = e < E ? z : -3.0e38f;
+#pragma unroll
+    for (int m = kWave / 2; m > 0; m >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, m));
+    float p = e < E ? expf(z - zmax) : 0.0f;
+    float denom = p;
+#pragma unroll
+    for (int m = kWave / 2; m > 0; m >>= 1) denom += __shfl_xor(denom, m);
+    p /= denom;
+    float dg = 0.0f;
+    for (int j = 0; j < k; ++j)
+        if (expert_idx[static_cast<size_t>(t) * k + j] == e) dg = dgate[static_cast<size_t>(t) * k + j];
+    float s = p * dg;
+#pragma unroll
+    for (int m = kWave / 2; m > 0; m >>= 1) s += __shfl_xor(s, m);
+    const float dze = p * (dg - s);
+    if (e < E) dz[static_cast<size_t>(t) * E + e] = dze;
+    dzs[w][lane] = e < E ? dze : 0.0f;
+    __builtin_amdgcn_wave_barrier();
+    for (int i = lane; i < d; i += kWave) {
+        float acc = 0.0f;
+        for (int j = 0; j < k; ++j) {
+            const int slot = slot_of[static_cast<size_t>(t) * k + j];
+            if (slot >= 0 && slot < max_rows) acc += dxe[static_cast<size_t>(slot) * d + i];
+        }
+        const uint16_t *wrow = Wg + static_cast<size_t>(i) * E;
+        for (int ee = 0; ee < E; ++ee) acc = __builtin_fmaf(dzs[w][ee], bf16_to_f32(wrow[ee]), acc);
+        dx[static_cast<size_t>(t) * d + i] = acc;
+    }
+}
+
+// partial[s][i][e] = sum over the tokens of range s of x[t, i] dz[t, e];
+// block = 64 columns i x 4 expert groups.
+__global__ __launch_bounds__(256) void dwg_partial_kernel(
+    const uint16_t *__restrict__ x, const float *__restrict__ dz, float *__restrict__ partial, int T,
+    int d, int E, int per_split)
+{
+    const int il = threadIdx.x % 64, eg = threadIdx.x / 64;
+    const int i = blockIdx.x * 64 + il;
+    const int EQ = (E + 3) / 4;
+    const int e0 = eg * EQ;
+    const int t0 = blockIdx.y * per_split, t1 = min(T, t0 + per_split);
+    float acc[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[q] = 0.0f;
+    if (i < d) {
+        for (int t = t0; t < t1; ++t) {
+            const float xv = bf16_to_f32(x[static_cast<size_t>(t) * d + i]);
+#pragma unroll
+            for (int q = 0; q < 16; ++q)
+                if (q < EQ && e0 + q < E) acc[q] = __builtin_fmaf(xv, dz[static_cast<size_t>(t) * E + e0 + q], acc[q]);
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            if (q < EQ && e0 + q < E)
+                partial[(static_cast<size_t>(blockIdx.y) * d + i) * E + e0 + q] = acc[q];
+    }
+}
+
+__global__ void dwg_reduce_kernel(const float *__restrict__ partial, float *__restrict__ dWg, int n,
+                                  int splits)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n) return;
+    float acc = 0.0f;
+    for (int s = 0; s < splits; ++s) acc += partial[static_cast<size_t>(s) * n + idx];
+    dWg[idx] = acc;
+}
+
+// ---------------------------------------------------------------- host side
+struct BwdWorkspace {
+    Workspace lists;          // work lists of the two row-grouped GEMM shapes
+    _Float16 *P;              // [R][h]
+    uint16_t *Hb, *dye, *dP;  // [R][h], [R][d], [R][h]
+    float *dxe;               // [R][d]
+    int32_t *koff;            // [E+1]
+    uint16_t *HT, *dPT, *dyeT, *xeT;   // [h][lda], [h][lda], [d][lda], [d][lda]
+    float *dz, *partial;      // [T][E], [splits][d][E]
+    int lda, splits, per_split;
+    size_t bytes;
+};
+
+GemmPlan plan128(int N, int64_t max_rows, int E)
+{
+    GemmPlan gp;
+    gp.bm = kBM;
+    gp.bn = kBN;
+    gp.concurrent = 64;
+    gp.tiles_n = (N + kBN - 1) / kBN;
+    gp.max_row_tiles = static_cast<int32_t>((max_rows + kBM - 1) / kBM + E);
+    gp.max_items = gp.max_row_tiles * gp.tiles_n;
+    return gp;
+}
+
+void layout_bwd(const moe_shape &s, void *base, BwdWorkspace *w)
+{
+    const int64_t R = moe_max_rows(&s);
+    char *p = static_cast<char *>(base);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char *at = p + off;
+        off += align_up(bytes, 256);
+        return at;
+    };
+    w->lists = Workspace{};
+    w->lists.gp[0] = plan128(s.d_ff, R, s.E);
+    w->lists.gp[1] = plan128(s.d_model, R, s.E);
+    for (int g = 0; g < 2; ++g) {
+        w->lists.items[g] = reinterpret_cast<WorkItem *>(take(sizeof(WorkItem) * w->lists.gp[g].max_items));
+        w->lists.nitems[g] = reinterpret_cast<int32_t *>(take(sizeof(int32_t)));
+    }
+    const size_t Rh = static_cast<size_t>(R) * s.d_ff, Rd = static_cast<size_t>(R) * s.d_model;
+    w->P = reinterpret_cast<_Float16 *>(take(Rh * 2));
+    w->Hb = reinterpret_cast<uint16_t *>(take(Rh * 2));
+    w->dye = reinterpret_cast<uint16_t *>(take(Rd * 2));
+    w->dP = reinterpret_cast<uint16_t *>(take(Rh * 2));
+    w->dxe = reinterpret_cast<float *>(take(Rd * 4));
+    w->koff = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * (s.E + 1)));
+    w->lda = static_cast<int>((R + 63) / 64 * 64 + 64 * s.E);
+    w->HT = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(s.d_ff) * w->lda * 2));
+    w->dPT = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(s.d_ff) * w->lda * 2));
+    w->dyeT = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(s.d_model) * w->lda * 2));
+    w->xeT = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(s.d_model) * w->lda * 2));
+    w->dz = reinterpret_cast<float *>(take(static_cast<size_t>(s.T) * s.E * 4));
+    w->splits = std::max(1, std::min(64, (s.T + 63) / 64));
+    w->per_split = (s.T + w->splits - 1) / w->splits;
+    w->partial = reinterpret_cast<float *>(take(static_cast<size_t>(w->splits) * s.d_model * s.E * 4));
+    w->bytes = off;
+}
+
+bool supported(const moe_shape *s)
+{
+    if (s == nullptr || s->dtype != MOE_BF16 || s->renorm_topk != 0) return false;
+    if (s->T < 1 || s->d_model < 8 || s->d_ff < 8 || s->E < 1 || s->E > kMaxExperts || s->k < 1 ||
+        s->k > kMaxTopK || s->k > s->E || s->capacity < 1)
+        return false;
+    return s->d_model % 8 == 0 && s->d_ff % 8 == 0;
+}
+
+template <int MODE, int EPI, int ACT, bool KTAIL>
+void launch_gemm_k(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, const WorkItem *items,
+                   const int32_t *nitems, const int32_t *koff, int E, int M, int N, int K,
+                   int grid_items, hipStream_t st)
+{
+    auto kern = bwd_gemm_kernel<MODE, EPI, ACT, KTAIL>;
+    static bool configured = false;
+    if (!configured) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  static_cast<int>(kGemmLds));
+        configured = true;
+    }
+    const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
+    const int grid = static_cast<int>(align_up(static_cast<size_t>(grid_items), 8));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), kGemmLds, st, A, W, C, P, items, nitems, koff, E,
+                       M, N, K, tiles_m, tiles_n);
+}
+
+template <int MODE, int EPI, int ACT>
+void launch_gemm(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, const WorkItem *items,
+                 const int32_t *nitems, const int32_t *koff, int E, int M, int N, int K,
+                 int grid_items, hipStream_t st)
+{
+    if (MODE == 1 || K % kBK == 0)
+        launch_gemm_k<MODE, EPI, ACT, false>(A, W, C, P, items, nitems, koff, E, M, N, K, grid_items, st);
+    else
+        launch_gemm_k<MODE, EPI, ACT, true>(A, W, C, P, items, nitems, koff, E, M, N, K, grid_items, st);
+}
+
+template <int ACT>
+moe_status backward_t(const moe_shape &s, const uint16_t *x, const uint16_t *Wg, const float *bias,
+                      int bias_stride, const uint16_t *W1, const uint16_t *W2, const uint16_t *W1p,
+                      const int32_t *expert_idx, const float *gate, const int32_t *offsets,
+                      const int32_t *slot_of, const int32_t *src_of, const uint16_t *xe,
+                      const float *ye, const float *dy, float *dx, float *dWg, float *dW1,
+                      float *dW2, float *dgate, const BwdWorkspace &w, hipStream_t st)
+{
+    const int T = s.T, d = s.d_model, h = s.d_ff, E = s.E, k = s.k;
+    const int R = static_cast<int>(moe_max_rows(&s));
+    // work lists of the row-grouped GEMMs (one chunk) and the padded row offsets
+    moe_status rc = launch_items(s, 1, offsets, src_of, w.lists, st);
+    if (rc != MOE_OK) return rc;
+    hipLaunchKernelGGL(padded_offsets_kernel, dim3(1), dim3(kWave), 0, st, offsets, w.koff, E);
+    hipLaunchKernelGGL(combine_bwd_kernel, dim3(ceil_div(T, 4)), dim3(256), 0, st, dy, ye, slot_of,
+                       gate, w.dye, dgate, T, d, k, R);
+    const GemmPlan &g0 = w.lists.gp[0], &g1 = w.lists.gp[1];
+    // P = xe W1 (fp16), Hb = act(P) (bf16)
+    launch_gemm<0, 1, ACT>(xe, W1p, w.Hb, w.P, w.lists.items[0], w.lists.nitems[0], nullptr, E, 0, h,
+                           d, g0.max_items, st);
+    // dP = (dye W2^T) * act'(P): W2 [E][h][d] is already "rows n = h, contraction d contiguous"
+    launch_gemm<0, 2, ACT>(w.dye, W2, w.dP, w.P, w.lists.items[0], w.lists.nitems[0], nullptr, E, 0,
+                           h, d, g0.max_items, st);
+    // dxe = dP W1^T: W1 [E][d][h] is "rows n = d, contraction h contiguous"
+    launch_gemm<0, 0, ACT>(w.dP, W1, w.dxe, nullptr, w.lists.items[1], w.lists.nitems[1], nullptr, E,
+                           0, d, h, g1.max_items, st);
+    // transposed, per-expert zero-padded copies for the weight gradients
+    const dim3 tb(256);
+    const int kblocks = w.lda / 64;
+    hipLaunchKernelGGL(transpose_rows_kernel, dim3(kblocks, ceil_div(h, 64)), tb, 0, st, w.Hb, w.HT,
+                       offsets, w.koff, E, h, w.lda);
+    hipLaunchKernelGGL(transpose_rows_kernel, dim3(kblocks, ceil_div(h, 64)), tb, 0, st, w.dP, w.dPT,
+                       offsets, w.koff, E, h, w.lda);
+    hipLaunchKernelGGL(transpose_rows_kernel, dim3(kblocks, ceil_div(d, 64)), tb, 0, st, w.dye, w.dyeT,
+                       offsets, w.koff, E, d, w.lda);
+    hipLaunchKernelGGL(transpose_rows_kernel, dim3(kblocks, ceil_div(d, 64)), tb, 0, st, xe, w.xeT,
+                       offsets, w.koff, E, d, w.lda);
+    // dW2[e] [h][d] = Hb^T dye ; dW1[e] [d][h] = xe^T dP
+    launch_gemm<1, 0, ACT>(w.HT, w.dyeT, dW2, nullptr, nullptr, nullptr, w.koff, E, h, d, w.lda,
+                           E * ceil_div(h, kBM) * ceil_div(d, kBN), st);
+    launch_gemm<1, 0, ACT>(w.xeT, w.dPT, dW1, nullptr, nullptr, nullptr, w.koff, E, d, h, w.lda,
+                           E * ceil_div(d, kBM) * ceil_div(h, kBN), st);
+    // gate: dz, dx, dWg
+    hipLaunchKernelGGL(gate_bwd_kernel, dim3(ceil_div(T, 4)), dim3(256), 0, st, x, Wg, bias,
+                       bias_stride, expert_idx, slot_of, dgate, w.dxe, w.dz, dx, T, d, E, k, R);
+    hipLaunchKernelGGL(dwg_partial_kernel, dim3(ceil_div(d, 64), w.splits), dim3(256), 0, st, x, w.dz,
+                       w.partial, T, d, E, w.per_split);
+    hipLaunchKernelGGL(dwg_reduce_kernel, dim3(ceil_div(d * E, 256)), dim3(256), 0, st, w.partial, dWg,
+                       d * E, w.splits);
+    MOE_TRY_HIP(hipGetLastError());
+    return MOE_OK;
+}
+
+}  // namespace
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+size_t moe_backward_workspace_bytes(const moe_shape *s)
+{
+    if (!supported(s)) return 0;
+    BwdWorkspace w;
+    layout_bwd(*s, reinterpret_cast<void *>(static_cast<uintptr_t>(256)), &w);   // sizes only
+    return w.bytes;
+}
+
+moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wg,
+                              const float *gate_bias, int32_t bias_token_stride,
+                              const void *W1, const void *W2, const void *W1p,
+                              const int32_t *expert_idx, const float *gate,
+                              const int32_t *offsets, const int32_t *slot_of,
+                              const int32_t *src_of, const void *xe, const float *ye,
+                              const float *dy, float *dx, float *dWg, float *dW1, float *dW2,
+                              float *dgate, void *workspace, void *stream)
+{
+    if (!supported(s)) {
+        set_error("moe_layer_backward: bf16 layers without top-k renormalisation only, E <= %d, "
+                  "k <= %d, d_model and d_ff multiples of 8", kMaxExperts, kMaxTopK);
+        return s == nullptr ? MOE_EINVAL : MOE_EUNSUPPORTED;
+    }
+    if (gate_bias != nullptr && bias_token_stride != 0 && bias_token_stride != s->E) {
+        set_error("bias_token_stride must be 0 or E");
+        return MOE_EINVAL;
+    }
+    const void *need[] = {x, Wg, W1, W2, W1p, expert_idx, gate, offsets, slot_of, src_of, xe, ye, dy,
+                          dx, dWg, dW1, dW2, dgate, workspace};
+    for (const void *p : need) {
+        if (p == nullptr || (reinterpret_cast<uintptr_t>(p) & 15u) != 0) {
+            set_error("moe_layer_backward: a required pointer is NULL or not 16-byte aligned");
+            return MOE_EINVAL;
+        }
+    }
+    BwdWorkspace w;
+    layout_bwd(*s, workspace, &w);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint16_t *xb = static_cast<const uint16_t *>(x);
+    const uint16_t *Wgb = static_cast<const uint16_t *>(Wg);
+    const uint16_t *W1b = static_cast<const uint16_t *>(W1), *W2b = static_cast<const uint16_t *>(W2);
+    const uint16_t *W1pb = static_cast<const uint16_t *>(W1p), *xeb = static_cast<const uint16_t *>(xe);
+#define MOE_BWD_CASE(ACT)                                                                         \
+    case ACT:                                                                                     \
+        return backward_t<ACT>(*s, xb, Wgb, gate_bias, bias_token_stride, W1b, W2b, W1pb,         \
+                               expert_idx, gate, offsets, slot_of, src_of, xeb, ye, dy, dx, dWg,  \
+                               dW1, dW2, dgate, w, st);
+    switch (s->act) {
+        MOE_BWD_CASE(MOE_ACT_GELU_ERF)
+        MOE_BWD_CASE(MOE_ACT_GELU_TANH)
+        MOE_BWD_CASE(MOE_ACT_RELU)
+        MOE_BWD_CASE(MOE_ACT_IDENTITY)
+    }
+#undef MOE_BWD_CASE
+    set_error("unknown activation %d", static_cast<int>(s->act));
+    return MOE_EINVAL;
+}
+
+}  // extern "C"

@@ -1,0 +1,62 @@
+"""Thin Python binding of include/moe_train.h (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+
+import torch
+
+from .binding import MoeError, Shape, _check, _ptr, _stream, lib, moe_max_rows
+
+_ready = False
+
+
+def _lib():
+    global _ready
+    L = lib()
+    if not _ready:
+        sp, vp, i32 = C.POINTER(Shape), C.c_void_p, C.c_int32
+        L.moe_backward_workspace_bytes.restype = C.c_size_t
+        L.moe_backward_workspace_bytes.argtypes = [sp]
+        L.moe_layer_backward.restype = C.c_int
+        L.moe_layer_backward.argtypes = [sp, vp, vp, vp, i32] + [vp] * 18
+        _ready = True
+    return L
+
+
+def moe_backward_workspace_bytes(s: Shape) -> int:
+    return int(_lib().moe_backward_workspace_bytes(C.byref(s)))
+
+
+def _need(t: torch.Tensor, dtype, numel: int, name: str) -> None:
+    if t.dtype != dtype or t.numel() < numel:
+        raise MoeError(f"{name}: need {numel} elements of {dtype}, got {t.numel()} of {t.dtype}")
+
+
+def moe_layer_backward(s: Shape, x, Wg, gate_bias, bias_token_stride, W1, W2, W1p, expert_idx, gate,
+                       offsets, slot_of, src_of, xe, ye, dy, dx, dWg, dW1, dW2, dgate, workspace,
+                       stream=None) -> None:
+    rows = moe_max_rows(s)
+    T, d, E, h, k = s.T, s.d_model, s.E, s.d_ff, s.k
+    _need(x, torch.bfloat16, T * d, "x")
+    _need(Wg, torch.bfloat16, d * E, "Wg")
+    _need(W1, torch.bfloat16, E * d * h, "W1")
+    _need(W2, torch.bfloat16, E * d * h, "W2")
+    _need(expert_idx, torch.int32, T * k, "expert_idx")
+    _need(gate, torch.float32, T * k, "gate")
+    _need(offsets, torch.int32, E + 1, "offsets")
+    _need(slot_of, torch.int32, T * k, "slot_of")
+    _need(src_of, torch.int32, rows, "src_of")
+    _need(xe, torch.bfloat16, rows * d, "xe")
+    _need(ye, torch.float32, rows * d, "ye")
+    _need(dy, torch.float32, T * d, "dy")
+    _need(dx, torch.float32, T * d, "dx")
+    _need(dWg, torch.float32, d * E, "dWg")
+    _need(dW1, torch.float32, E * d * h, "dW1")
+    _need(dW2, torch.float32, E * d * h, "dW2")
+    _need(dgate, torch.float32, T * k, "dgate")
+    _need(workspace, torch.uint8, moe_backward_workspace_bytes(s), "workspace")
+    _check(_lib().moe_layer_backward(C.byref(s), _ptr(x), _ptr(Wg), _ptr(gate_bias), bias_token_stride,
+                                     _ptr(W1), _ptr(W2), _ptr(W1p), _ptr(expert_idx), _ptr(gate),
+                                     _ptr(offsets), _ptr(slot_of), _ptr(src_of), _ptr(xe), _ptr(ye),
+                                     _ptr(dy), _ptr(dx), _ptr(dWg), _ptr(dW1), _ptr(dW2), _ptr(dgate),
+                                     _ptr(workspace), _stream(stream)))
