@@ -38,16 +38,16 @@ size_t moe_backward_workspace_bytes(const moe_shape *s);
 
 /*
  * All gradients of one layer.
- *   forward inputs   x [T,d]; Wg [d,E]; gate_bias, bias_token_stride as given to moe_route;
- *                    W1 [E,d,h], W2 [E,h,d] in their canonical layouts; W1p the packed W1 of
- *                    moe_pack_weights
+ *   forward inputs   x [T,d]; Wgp the packed gate matrix of moe_pack_gate; gate_bias,
+ *                    bias_token_stride as given to moe_route; W1 [E,d,h], W2 [E,h,d] in their
+ *                    canonical layouts; W1p the packed W1 of moe_pack_weights
  *   forward outputs  expert_idx, gate, offsets, slot_of, src_of, xe, ye exactly as the
  *                    forward call left them
  *   dy               [T,d] fp32
  *   dx [T,d], dWg [d,E], dW1 [E,d,h], dW2 [E,h,d], dgate [T*k]: fp32, overwritten (weight
  *                    gradients of an expert without rows are zero)
  */
-moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wg,
+moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp,
                               const float *gate_bias, int32_t bias_token_stride,
                               const void *W1, const void *W2, const void *W1p,
                               const int32_t *expert_idx, const float *gate,

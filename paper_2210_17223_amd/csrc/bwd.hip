@@ -7,7 +7,8 @@
 //   gemm (rows)      dxe = dP W1^T                                    (fp32)
 //   transposes       Hb, dye, xe, dP -> [columns][rows], each expert's rows padded to 64
 //   gemm (wgrad)     dW2[e] = Hb^T dye, dW1[e] = xe^T dP              (fp32)
-//   gate_bwd         logits, softmax, dz, dx = sum of the token's dxe rows + dz Wg^T
+//   gate_bwd         logits (from the packed gate matrix), softmax, dz,
+//                    dx = sum of the token's dxe rows + dz Wg^T
 //   dwg              dWg = x^T dz (partial sums over token ranges, then a fixed-order sum)
 //
 // The contractions use 128 x 128 output tiles of 32x32x16 bf16 MFMAs fed through a
@@ -31,11 +32,23 @@ typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 constexpr int kBM = 128, kBN = 128, kBK = 64, kLD = kBK + 8;
 constexpr size_t kGemmLds = 2 * (kBM + kBN) * kLD * sizeof(uint16_t);
 
+// Phi(v), the normal CDF, as 1 / (1 + 2^(v Q(min(v^2, 49)))) with the cubic Q of the forward's
+// GeLU (absolute error of v Phi(v) below 1.5e-5).
+__device__ __forceinline__ float normal_cdf_fast(float v)
+{
+    const float s = fminf(v * v, 49.0f);
+    float q = 2.1637799e-05f;
+    q = __builtin_fmaf(q, s, 7.7587553e-04f);
+    q = __builtin_fmaf(q, s, -1.0610976e-01f);
+    q = __builtin_fmaf(q, s, -2.3015507e+00f);
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * q));
+}
+
 template <int ACT>
 __device__ __forceinline__ float act_value(float v)
 {
     if constexpr (ACT == MOE_ACT_GELU_ERF)
-        return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f));
+        return v * normal_cdf_fast(v);
     else if constexpr (ACT == MOE_ACT_GELU_TANH)
         return 0.5f * v * (1.0f + tanhf(0.7978845608028654f * (v + 0.044715f * v * v * v)));
     else if constexpr (ACT == MOE_ACT_RELU)
@@ -48,9 +61,9 @@ template <int ACT>
 __device__ __forceinline__ float act_derivative(float v)
 {
     if constexpr (ACT == MOE_ACT_GELU_ERF) {
-        const float Phi = 0.5f * (1.0f + erff(v * 0.70710678118654752f));
-        const float pdf = 0.3989422804014327f * __expf(-0.5f * v * v);
-        return Phi + v * pdf;
+        // Phi(v) + v phi(v); phi(v) = exp(-v^2 / 2) / sqrt(2 pi) through exp2
+        const float pdf = 0.3989422804014327f * __builtin_amdgcn_exp2f(-0.72134752044448171f * v * v);
+        return normal_cdf_fast(v) + v * pdf;
     } else if constexpr (ACT == MOE_ACT_GELU_TANH) {
         const float c = 0.7978845608028654f, a = 0.044715f;
         const float th = tanhf(c * (v + a * v * v * v));
@@ -309,12 +322,13 @@ __global__ void padded_offsets_kernel(const int32_t *__restrict__ offsets, int32
 }
 
 // out[m][koff[e] + i] = in[offsets[e] + i][m] for i < rows of expert e, 0 for the padding;
-// one block per 64 padded rows x 64 columns, through LDS.
+// one block per 64 padded rows x 64 columns, through LDS, 16 bytes per lane on both sides
+// (M is a multiple of 8).
 __global__ __launch_bounds__(256) void transpose_rows_kernel(
     const uint16_t *__restrict__ in, uint16_t *__restrict__ out, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ koff, int E, int M, int lda)
 {
-    __shared__ uint16_t tile[64][66];
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64][72];   // [column][row]
     const int kb = blockIdx.x * 64;
     if (kb >= koff[E]) return;
     int e = 0;
@@ -322,97 +336,164 @@ __global__ __launch_bounds__(256) void transpose_rows_kernel(
     const int r_base = offsets[e] + (kb - koff[e]);
     const int r_end = offsets[e + 1];
     const int m0 = blockIdx.y * 64;
-    for (int v = threadIdx.x; v < 64 * 64; v += 256) {
-        const int rr = v / 64, mm = v % 64;
-        uint16_t val = 0;
-        if (r_base + rr < r_end && m0 + mm < M)
-            val = in[static_cast<size_t>(r_base + rr) * M + m0 + mm];
-        tile[rr][mm] = val;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int v = threadIdx.x + pass * 256;
+        const int rr = v / 8, c8 = (v % 8) * 8;
+        u32x4 q = {0u, 0u, 0u, 0u};
+        if (r_base + rr < r_end && m0 + c8 < M)
+            q = *reinterpret_cast<const u32x4 *>(in + static_cast<size_t>(r_base + rr) * M + m0 + c8);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            tile[c8 + 2 * i][rr] = static_cast<uint16_t>(q[i] & 0xFFFFu);
+            tile[c8 + 2 * i + 1][rr] = static_cast<uint16_t>(q[i] >> 16);
+        }
     }
     __syncthreads();
-    for (int v = threadIdx.x; v < 64 * 64; v += 256) {
-        const int mm = v / 64, rr = v % 64;
-        if (m0 + mm < M) out[static_cast<size_t>(m0 + mm) * lda + kb + rr] = tile[rr][mm];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int v = threadIdx.x + pass * 256;
+        const int mm = v / 8, r8 = (v % 8) * 8;
+        if (m0 + mm < M)
+            *reinterpret_cast<u32x4 *>(out + static_cast<size_t>(m0 + mm) * lda + kb + r8) =
+                *reinterpret_cast<const u32x4 *>(&tile[mm][r8]);
     }
 }
 
 // ---------------------------------------------------------------- gate backward
-// One wavefront per token: logits (lane = expert), softmax, dz, then
-// dx[t, i] = sum of the token's kept dxe rows + sum_e dz[e] Wg[i, e] (lane = column).
+// One wavefront per token.  Logits: lane = four consecutive columns of the model dimension,
+// EP partial sums per lane (Wgp is the forward's packed gate matrix, fp32 [EP][dP],
+// expert-major, zero padded), then a butterfly sum per expert; the order of the additions
+// differs from the forward's chain, which only the top-k decision needed.  Softmax, dz with
+// lane = expert, and finally, lane = column again,
+// dx[t, i] = sum of the token's kept dxe rows + sum_e dz[e] Wg[i, e].
+template <int EP>
 __global__ __launch_bounds__(256) void gate_bwd_kernel(
-    const uint16_t *__restrict__ x, const uint16_t *__restrict__ Wg, const float *__restrict__ bias,
+    const uint16_t *__restrict__ x, const float *__restrict__ Wgp, const float *__restrict__ bias,
     int bias_stride, const int32_t *__restrict__ expert_idx, const int32_t *__restrict__ slot_of,
     const float *__restrict__ dgate, const float *__restrict__ dxe, float *__restrict__ dz,
-    float *__restrict__ dx, int T, int d, int E, int k, int max_rows)
+    float *__restrict__ dx, int T, int d, int dP, int E, int k, int max_rows)
 {
-    __shared__ float dzs[4][kMaxExperts];
+    __shared__ float dzs[4][kWave];
     const int lane = lane_id();
     const int w = threadIdx.x / kWave;
     const int t = blockIdx.x * 4 + w;
     if (t >= T) return;
     const uint16_t *xrow = x + static_cast<size_t>(t) * d;
-    const int e = lane;
-    float z = 0.0f;
-    if (e < E) {
-        for (int i = 0; i < d; ++i)
-            z = __builtin_fmaf(bf16_to_f32(xrow[i]), bf16_to_f32(Wg[static_cast<size_t>(i) * E + e]), z);
-        if (bias != nullptr) z += bias[static_cast<size_t>(t) * bias_stride + e];
+    float acc[EP];
+#pragma unroll
+    for (int e = 0; e < EP; ++e) acc[e] = 0.0f;
+    for (int i = lane * 4; i < d; i += kWave * 4) {
+        const u32x2 xq = *reinterpret_cast<const u32x2 *>(xrow + i);
+        const float x0 = __uint_as_float(xq[0] << 16), x1 = __uint_as_float(xq[0] & 0xFFFF0000u);
+        const float x2 = __uint_as_float(xq[1] << 16), x3 = __uint_as_float(xq[1] & 0xFFFF0000u);
+#pragma unroll
+        for (int e = 0; e < EP; ++e) {
+            const float4 wv = *reinterpret_cast<const float4 *>(Wgp + static_cast<size_t>(e) * dP + i);
+            acc[e] = __builtin_fmaf(x0, wv.x, acc[e]);
+            acc[e] = __builtin_fmaf(x1, wv.y, acc[e]);
+            acc[e] = __builtin_fmaf(x2, wv.z, acc[e]);
+            acc[e] = __builtin_fmaf(x3, wv.w, acc[e]);
+        }
     }
-    float zmax = e < E ? z : -3.0e38f;
+    float z = 0.0f;
+#pragma unroll
+    for (int e = 0; e < EP; ++e) {
+        float v = acc[e];
+#pragma unroll
+        for (int m = kWave / 2; m > 0; m >>= 1) v += __shfl_xor(v, m);
+        if (lane == e) z = v;
+    }
+    const int e = lane;
+    const bool live = e < E;
+    if (bias != nullptr && live) z += bias[static_cast<size_t>(t) * bias_stride + e];
+    float zmax = live ? z : -3.0e38f;
 #pragma unroll
     for (int m = kWave / 2; m > 0; m >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, m));
-    float p = e < E ? expf(z - zmax) : 0.0f;
+    float p = live ? expf(z - zmax) : 0.0f;
     float denom = p;
 #pragma unroll
     for (int m = kWave / 2; m > 0; m >>= 1) denom += __shfl_xor(denom, m);
     p /= denom;
     float dg = 0.0f;
-    for (int j = 0; j < k; ++j)
-        if (expert_idx[static_cast<size_t>(t) * k + j] == e) dg = dgate[static_cast<size_t>(t) * k + j];
+    if (live)
+        for (int j = 0; j < k; ++j)
+            if (expert_idx[static_cast<size_t>(t) * k + j] == e) dg = dgate[static_cast<size_t>(t) * k + j];
     float s = p * dg;
 #pragma unroll
     for (int m = kWave / 2; m > 0; m >>= 1) s += __shfl_xor(s, m);
     const float dze = p * (dg - s);
-    if (e < E) dz[static_cast<size_t>(t) * E + e] = dze;
-    dzs[w][lane] = e < E ? dze : 0.0f;
+    if (live) dz[static_cast<size_t>(t) * E + e] = dze;
+    dzs[w][lane] = live ? dze : 0.0f;
     __builtin_amdgcn_wave_barrier();
-    for (int i = lane; i < d; i += kWave) {
-        float acc = 0.0f;
+    float dzr[EP];
+#pragma unroll
+    for (int ee = 0; ee < EP; ++ee) dzr[ee] = dzs[w][ee];
+    for (int i = lane * 4; i < d; i += kWave * 4) {
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int j = 0; j < k; ++j) {
             const int slot = slot_of[static_cast<size_t>(t) * k + j];
-            if (slot >= 0 && slot < max_rows) acc += dxe[static_cast<size_t>(slot) * d + i];
+            if (slot >= 0 && slot < max_rows) {
+                const float4 r = *reinterpret_cast<const float4 *>(dxe + static_cast<size_t>(slot) * d + i);
+                o.x += r.x; o.y += r.y; o.z += r.z; o.w += r.w;
+            }
         }
-        const uint16_t *wrow = Wg + static_cast<size_t>(i) * E;
-        for (int ee = 0; ee < E; ++ee) acc = __builtin_fmaf(dzs[w][ee], bf16_to_f32(wrow[ee]), acc);
-        dx[static_cast<size_t>(t) * d + i] = acc;
+#pragma unroll
+        for (int ee = 0; ee < EP; ++ee) {
+            const float4 wv = *reinterpret_cast<const float4 *>(Wgp + static_cast<size_t>(ee) * dP + i);
+            o.x = __builtin_fmaf(dzr[ee], wv.x, o.x);
+            o.y = __builtin_fmaf(dzr[ee], wv.y, o.y);
+            o.z = __builtin_fmaf(dzr[ee], wv.z, o.z);
+            o.w = __builtin_fmaf(dzr[ee], wv.w, o.w);
+        }
+        *reinterpret_cast<float4 *>(dx + static_cast<size_t>(t) * d + i) = o;
     }
 }
 
-// partial[s][i][e] = sum over the tokens of range s of x[t, i] dz[t, e];
-// block = 64 columns i x 4 expert groups.
+// partial[s][i][e] = sum over the tokens of range s of x[t, i] dz[t, e].  Block = 64 columns
+// i x 4 expert groups of EQ = EP / 4 experts (EP < 4: one expert per group, surplus groups
+// idle); tokens go through LDS 64 at a time.
+template <int EP>
 __global__ __launch_bounds__(256) void dwg_partial_kernel(
     const uint16_t *__restrict__ x, const float *__restrict__ dz, float *__restrict__ partial, int T,
     int d, int E, int per_split)
 {
+    constexpr int EQ = EP >= 4 ? EP / 4 : 1;
+    __shared__ float xs[64][65];
+    __shared__ float zs[64][EP + 1];
     const int il = threadIdx.x % 64, eg = threadIdx.x / 64;
-    const int i = blockIdx.x * 64 + il;
-    const int EQ = (E + 3) / 4;
+    const int i0 = blockIdx.x * 64;
     const int e0 = eg * EQ;
     const int t0 = blockIdx.y * per_split, t1 = min(T, t0 + per_split);
-    float acc[16];
+    float acc[EQ];
 #pragma unroll
-    for (int q = 0; q < 16; ++q) acc[q] = 0.0f;
-    if (i < d) {
-        for (int t = t0; t < t1; ++t) {
-            const float xv = bf16_to_f32(x[static_cast<size_t>(t) * d + i]);
-#pragma unroll
-            for (int q = 0; q < 16; ++q)
-                if (q < EQ && e0 + q < E) acc[q] = __builtin_fmaf(xv, dz[static_cast<size_t>(t) * E + e0 + q], acc[q]);
+    for (int q = 0; q < EQ; ++q) acc[q] = 0.0f;
+    for (int tb = t0; tb < t1; tb += 64) {
+        __syncthreads();
+        for (int v = threadIdx.x; v < 64 * 64; v += 256) {
+            const int tt = v / 64, ii = v % 64;
+            xs[tt][ii] = (tb + tt < t1 && i0 + ii < d)
+                             ? bf16_to_f32(x[static_cast<size_t>(tb + tt) * d + i0 + ii]) : 0.0f;
         }
+        for (int v = threadIdx.x; v < 64 * EP; v += 256) {
+            const int tt = v / EP, ee = v % EP;
+            zs[tt][ee] = (tb + tt < t1 && ee < E) ? dz[static_cast<size_t>(tb + tt) * E + ee] : 0.0f;
+        }
+        __syncthreads();
+        if (e0 < EP) {
+#pragma unroll 8
+            for (int tt = 0; tt < 64; ++tt) {
+                const float xv = xs[tt][il];
 #pragma unroll
-        for (int q = 0; q < 16; ++q)
-            if (q < EQ && e0 + q < E)
-                partial[(static_cast<size_t>(blockIdx.y) * d + i) * E + e0 + q] = acc[q];
+                for (int q = 0; q < EQ; ++q) acc[q] = __builtin_fmaf(xv, zs[tt][e0 + q], acc[q]);
+            }
+        }
+    }
+    if (i0 + il < d && e0 < EP) {
+#pragma unroll
+        for (int q = 0; q < EQ; ++q)
+            if (e0 + q < E)
+                partial[(static_cast<size_t>(blockIdx.y) * d + i0 + il) * E + e0 + q] = acc[q];
     }
 }
 
@@ -422,6 +503,7 @@ __global__ void dwg_reduce_kernel(const float *__restrict__ partial, float *__re
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= n) return;
     float acc = 0.0f;
+#pragma unroll 8
     for (int s = 0; s < splits; ++s) acc += partial[static_cast<size_t>(s) * n + idx];
     dWg[idx] = acc;
 }
@@ -481,7 +563,7 @@ void layout_bwd(const moe_shape &s, void *base, BwdWorkspace *w)
     w->dyeT = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(s.d_model) * w->lda * 2));
     w->xeT = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(s.d_model) * w->lda * 2));
     w->dz = reinterpret_cast<float *>(take(static_cast<size_t>(s.T) * s.E * 4));
-    w->splits = std::max(1, std::min(64, (s.T + 63) / 64));
+    w->splits = std::max(1, std::min(32, (s.T + 127) / 128));
     w->per_split = (s.T + w->splits - 1) / w->splits;
     w->partial = reinterpret_cast<float *>(take(static_cast<size_t>(w->splits) * s.d_model * s.E * 4));
     w->bytes = off;
@@ -527,7 +609,7 @@ void launch_gemm(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, con
 }
 
 template <int ACT>
-moe_status backward_t(const moe_shape &s, const uint16_t *x, const uint16_t *Wg, const float *bias,
+moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, const float *bias,
                       int bias_stride, const uint16_t *W1, const uint16_t *W2, const uint16_t *W1p,
                       const int32_t *expert_idx, const float *gate, const int32_t *offsets,
                       const int32_t *slot_of, const int32_t *src_of, const uint16_t *xe,
@@ -569,10 +651,20 @@ moe_status backward_t(const moe_shape &s, const uint16_t *x, const uint16_t *Wg,
     launch_gemm<1, 0, ACT>(w.xeT, w.dPT, dW1, nullptr, nullptr, nullptr, w.koff, E, d, h, w.lda,
                            E * ceil_div(d, kBM) * ceil_div(h, kBN), st);
     // gate: dz, dx, dWg
-    hipLaunchKernelGGL(gate_bwd_kernel, dim3(ceil_div(T, 4)), dim3(256), 0, st, x, Wg, bias,
-                       bias_stride, expert_idx, slot_of, dgate, w.dxe, w.dz, dx, T, d, E, k, R);
-    hipLaunchKernelGGL(dwg_partial_kernel, dim3(ceil_div(d, 64), w.splits), dim3(256), 0, st, x, w.dz,
-                       w.partial, T, d, E, w.per_split);
+    int EP = 1;
+    while (EP < E) EP <<= 1;
+    const int dPad = (d + 127) / 128 * 128;            // the packed gate matrix's row length
+#define MOE_GATE_BWD_CASE(EP_)                                                                    \
+    if (EP == EP_) {                                                                              \
+        hipLaunchKernelGGL(gate_bwd_kernel<EP_>, dim3(ceil_div(T, 4)), dim3(256), 0, st, x, Wgp,  \
+                           bias, bias_stride, expert_idx, slot_of, dgate, w.dxe, w.dz, dx, T, d,  \
+                           dPad, E, k, R);                                                        \
+        hipLaunchKernelGGL(dwg_partial_kernel<EP_>, dim3(ceil_div(d, 64), w.splits), dim3(256), 0, \
+                           st, x, w.dz, w.partial, T, d, E, w.per_split);                         \
+    }
+    MOE_GATE_BWD_CASE(1) MOE_GATE_BWD_CASE(2) MOE_GATE_BWD_CASE(4) MOE_GATE_BWD_CASE(8)
+    MOE_GATE_BWD_CASE(16) MOE_GATE_BWD_CASE(32) MOE_GATE_BWD_CASE(64)
+#undef MOE_GATE_BWD_CASE
     hipLaunchKernelGGL(dwg_reduce_kernel, dim3(ceil_div(d * E, 256)), dim3(256), 0, st, w.partial, dWg,
                        d * E, w.splits);
     MOE_TRY_HIP(hipGetLastError());
@@ -594,7 +686,7 @@ size_t moe_backward_workspace_bytes(const moe_shape *s)
     return w.bytes;
 }
 
-moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wg,
+moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp,
                               const float *gate_bias, int32_t bias_token_stride,
                               const void *W1, const void *W2, const void *W1p,
                               const int32_t *expert_idx, const float *gate,
@@ -612,7 +704,7 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wg,
         set_error("bias_token_stride must be 0 or E");
         return MOE_EINVAL;
     }
-    const void *need[] = {x, Wg, W1, W2, W1p, expert_idx, gate, offsets, slot_of, src_of, xe, ye, dy,
+    const void *need[] = {x, Wgp, W1, W2, W1p, expert_idx, gate, offsets, slot_of, src_of, xe, ye, dy,
                           dx, dWg, dW1, dW2, dgate, workspace};
     for (const void *p : need) {
         if (p == nullptr || (reinterpret_cast<uintptr_t>(p) & 15u) != 0) {
@@ -624,12 +716,12 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wg,
     layout_bwd(*s, workspace, &w);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint16_t *xb = static_cast<const uint16_t *>(x);
-    const uint16_t *Wgb = static_cast<const uint16_t *>(Wg);
+    const float *Wgf = static_cast<const float *>(Wgp);
     const uint16_t *W1b = static_cast<const uint16_t *>(W1), *W2b = static_cast<const uint16_t *>(W2);
     const uint16_t *W1pb = static_cast<const uint16_t *>(W1p), *xeb = static_cast<const uint16_t *>(xe);
 #define MOE_BWD_CASE(ACT)                                                                         \
     case ACT:                                                                                     \
-        return backward_t<ACT>(*s, xb, Wgb, gate_bias, bias_token_stride, W1b, W2b, W1pb,         \
+        return backward_t<ACT>(*s, xb, Wgf, gate_bias, bias_token_stride, W1b, W2b, W1pb,         \
                                expert_idx, gate, offsets, slot_of, src_of, xeb, ye, dy, dx, dWg,  \
                                dW1, dW2, dgate, w, st);
     switch (s->act) {

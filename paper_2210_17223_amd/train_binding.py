@@ -32,13 +32,12 @@ def _need(t: torch.Tensor, dtype, numel: int, name: str) -> None:
         raise MoeError(f"{name}: need {numel} elements of {dtype}, got {t.numel()} of {t.dtype}")
 
 
-def moe_layer_backward(s: Shape, x, Wg, gate_bias, bias_token_stride, W1, W2, W1p, expert_idx, gate,
+def moe_layer_backward(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1, W2, W1p, expert_idx, gate,
                        offsets, slot_of, src_of, xe, ye, dy, dx, dWg, dW1, dW2, dgate, workspace,
                        stream=None) -> None:
     rows = moe_max_rows(s)
     T, d, E, h, k = s.T, s.d_model, s.E, s.d_ff, s.k
     _need(x, torch.bfloat16, T * d, "x")
-    _need(Wg, torch.bfloat16, d * E, "Wg")
     _need(W1, torch.bfloat16, E * d * h, "W1")
     _need(W2, torch.bfloat16, E * d * h, "W2")
     _need(expert_idx, torch.int32, T * k, "expert_idx")
@@ -55,7 +54,7 @@ def moe_layer_backward(s: Shape, x, Wg, gate_bias, bias_token_stride, W1, W2, W1
     _need(dW2, torch.float32, E * d * h, "dW2")
     _need(dgate, torch.float32, T * k, "dgate")
     _need(workspace, torch.uint8, moe_backward_workspace_bytes(s), "workspace")
-    _check(_lib().moe_layer_backward(C.byref(s), _ptr(x), _ptr(Wg), _ptr(gate_bias), bias_token_stride,
+    _check(_lib().moe_layer_backward(C.byref(s), _ptr(x), _ptr(Wgp), _ptr(gate_bias), bias_token_stride,
                                      _ptr(W1), _ptr(W2), _ptr(W1p), _ptr(expert_idx), _ptr(gate),
                                      _ptr(offsets), _ptr(slot_of), _ptr(src_of), _ptr(xe), _ptr(ye),
                                      _ptr(dy), _ptr(dx), _ptr(dWg), _ptr(dW1), _ptr(dW2), _ptr(dgate),

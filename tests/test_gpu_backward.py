@@ -38,7 +38,7 @@ def run_backward(li, act="gelu"):
     g = dict(dx=f32(li.T * li.d), dWg=f32(li.d * li.E), dW1=f32(li.E * li.d * li.h),
              dW2=f32(li.E * li.d * li.h), dgate=f32(li.T * li.k))
     ws = torch.empty(moe.moe_backward_workspace_bytes(s), dtype=torch.uint8, device=DEV)
-    moe.moe_layer_backward(s, L.x, L.Wg, L.bias, L.bias_stride, W1, W2, b["W1p"], b["expert_idx"],
+    moe.moe_layer_backward(s, L.x, b["Wgp"], L.bias, L.bias_stride, W1, W2, b["W1p"], b["expert_idx"],
                            b["gate"], b["offsets"], b["slot_of"], b["src_of"], b["xe"], b["ye"],
                            torch.from_numpy(dy).to(DEV), g["dx"], g["dWg"], g["dW1"], g["dW2"],
                            g["dgate"], ws)
