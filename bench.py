@@ -48,6 +48,9 @@ def main() -> int:
                     help="after the timed region, time the same steps rotating through this many "
                          "copies of every buffer, so that no step finds its data in the 256 MB "
                          "Infinity Cache (skipped when one copy alone exceeds the cache; 0 = off)")
+    ap.add_argument("--backward", action="store_true",
+                    help="a step is forward + backward of the layer (moe_layer_backward); the roofline "
+                         "object is then for the second layer's weight-gradient GEMM")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten plain device copies of 256 MiB and exit: under rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE the copy kernel's reading fixes the counter's unit")
@@ -106,6 +109,13 @@ def main() -> int:
                 W1, W2 = up(li.W1), up(li.W2)
                 moe.moe_pack_weights(s, W1, W2, self.b["W1p"], self.b["W2p"])
                 torch.cuda.synchronize()
+                if args.backward:
+                    self.W1, self.W2 = W1, W2
+                    f32 = lambda n: torch.empty(n, dtype=torch.float32, device=dev)
+                    self.dy = torch.randn(l0.T * l0.d, dtype=torch.float32, device=dev)
+                    self.g = [f32(l0.T * l0.d), f32(l0.d * l0.E), f32(l0.E * l0.d * l0.h),
+                              f32(l0.E * l0.d * l0.h), f32(l0.T * l0.k)]
+                    self.bws = torch.empty(moe.moe_backward_workspace_bytes(s), dtype=torch.uint8, device=dev)
             else:       # a second copy of the same layer at other addresses
                 self.x = None if like.x is None else like.x.clone()
                 self.bias = None if like.bias is None else like.bias.clone()
@@ -123,6 +133,10 @@ def main() -> int:
                                   b["W2p"], None, b["expert_idx"], b["gate"], b["counts"], b["offsets"],
                                   b["slot_of"], b["src_of"], b["xe"], b["ye"], b["y"], b["y_act"],
                                   b["workspace"])
+            if args.backward:
+                moe.moe_layer_backward(s, x, b["Wgp"], self.bias, self.stride, self.W1, self.W2, b["W1p"],
+                                       b["expert_idx"], b["gate"], b["offsets"], b["slot_of"], b["src_of"],
+                                       b["xe"], b["ye"], self.dy, *self.g, self.bws)
 
     sets = [[DevLayer(li) for li in host]]
     for li in host:       # the host copies of the weights are needed again only by the oracle
@@ -146,7 +160,10 @@ def main() -> int:
     launches = args.steps * args.chunks * n_layers
     for _ in range(args.warmup):
         step(sets[0])
-    G1 = moe.STAGES.index("gemm1")
+    if args.backward and (n_layers != 1 or args.chunks != 1 or not bf16):
+        print("bench.py: --backward takes a one-layer bf16 workload and --chunks 1", file=sys.stderr)
+        return 2
+    G1 = moe.STAGES.index("bwd_wgrad2" if args.backward else "gemm1")
     torch.cuda.synchronize()
     moe.moe_profile_enable(1 << G1, launches)
     ms_per_step = timed(args.steps, lambda i: 0)
@@ -170,10 +187,15 @@ def main() -> int:
     ffn_mfma_s = 4.0 * A * l0.d * l0.h / (PEAK_BF16_TFLOPS * 1e12)
     ffn_hbm_s = (2 * live * l0.d * l0.h * 2 + A * l0.d * (2 + 4)) / (PEAK_HBM_GBPS * 1e9)
     hbm_bound = ffn_hbm_s > ffn_mfma_s
-    roof = {"kernel": "grouped_gemm_mfma_kernel<bf16 in, fp16 out, GeLU> (first expert GEMM)",
+    if args.backward:
+        # dW2[e] = act(P)^T dye: reads both transposed operands once, writes fp32 dW2
+        g1_bytes = A * l0.h * 2 + A * l0.d * 2 + l0.E * l0.d * l0.h * 4
+        g1_gbps = g1_bytes / (g1_avg_ms * 1e-3) / 1e9
+    roof = {"kernel": ("bwd_gemm_kernel<weight gradient> (dW2 = act(P)^T dye)" if args.backward else
+                       "grouped_gemm_mfma_kernel<bf16 in, fp16 out, GeLU> (first expert GEMM)"),
             "avg_launch_us": g1_avg_ms * 1e3, "launches": int(g1_ms.size),
             "algorithmic_flops": g1_flops, "algorithmic_bytes": g1_bytes,
-            "traffic": GEMM1_TRAFFIC_BYTES.get((args.workload, args.chunks)),
+            "traffic": None if args.backward else GEMM1_TRAFFIC_BYTES.get((args.workload, args.chunks)),
             "mfma_tflops": g1_tflops, "hbm_gbps": g1_gbps}
     if hbm_bound:
         roof.update({"bound": "hbm", "achieved": g1_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
@@ -186,7 +208,8 @@ def main() -> int:
                 "achieved": None, "peak": None, "unit": None, "frac": None, "traffic": None,
                 "avg_launch_us": g1_avg_ms * 1e3}
     out = {
-        "metric": "moe_layer_tokens_per_s", "value": tokens_per_s * n_layers, "unit": "tokens/s",
+        "metric": "moe_layer_fwd_bwd_tokens_per_s" if args.backward else "moe_layer_tokens_per_s",
+        "value": tokens_per_s * n_layers, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
@@ -201,7 +224,7 @@ def main() -> int:
 
     # ---- the same steps with cold caches -------------------------------------------------
     set_bytes = sum(L.bytes() for L in sets[0])
-    if args.cold_sets > 1 and n_layers == 1 and set_bytes <= 4 * INFINITY_CACHE_BYTES:
+    if args.cold_sets > 1 and n_layers == 1 and set_bytes <= 4 * INFINITY_CACHE_BYTES and not args.backward:
         while len(sets) < args.cold_sets:
             sets.append([DevLayer(like=L) for L in sets[0]])
         n = len(sets)
@@ -244,6 +267,9 @@ def main() -> int:
         st["ffn_mfma_util"] = (4.0 * A * l0.d * l0.h * n_layers) / ((st["gemm1"] + st["gemm2"]) * 1e-6) / 1e12 / PEAK_BF16_TFLOPS
         ffn_bytes = (2 * live * l0.d * l0.h * 2 + A * l0.d * 2 + 2 * A * l0.h * 2 + A * l0.d * 4) * n_layers
         st["ffn_GBps"] = ffn_bytes / ((st["gemm1"] + st["gemm2"]) * 1e-6) / 1e9
+        if args.backward:
+            bw = ("bwd_recompute", "bwd_dP", "bwd_dxe", "bwd_wgrad2", "bwd_wgrad1")
+            st["bwd_gemm_mfma_util"] = (5 * 2.0 * A * l0.d * l0.h) / (sum(st[n] for n in bw) * 1e-6) / 1e12 / PEAK_BF16_TFLOPS
         out["stages_us"] = st
         out["stages_us_median"] = med
         out["stages_us_min"] = mn
@@ -258,7 +284,20 @@ def main() -> int:
                                     "t_pack_us": st["scatter"], "t_unpack_us": st["combine"],
                                     "hidden_fraction": 1.0 - (t_pipe - t_ffn) / (st["scatter"] + st["combine"])}
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.backward:
+        # The backward oracle (fp64 numpy matmuls, forward included) once over the whole layer.
+        from oracle import bwd_oracle
+        li = host[0]
+        dy_host = np.random.Generator(np.random.PCG64(7)).standard_normal((l0.T, l0.d))
+        c0 = time.perf_counter()
+        bwd_oracle.moe_layer_backward(li.x, li.Wg, li.W1, li.W2, dy_host, k=li.k, capacity=li.C,
+                                      bias=li.gate_bias, bias_stride=li.bias_token_stride)
+        elapsed = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": l0.T / elapsed, "unit": "tokens/s", "cores": os.cpu_count(),
+                               "kind": "oracle",
+                               "sample": f"one forward + backward pass of the fp64 oracle over all {l0.T} "
+                                         f"tokens (numpy's BLAS threads), {elapsed:.2f} s wall"}
+    elif not args.no_cpu_baseline:
         import oracle
         # Bounded sample: whole passes of the oracle over the workload (gate and plan over
         # all tokens; expert FFN and combine for a leading slice of tokens when one full

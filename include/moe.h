@@ -174,7 +174,9 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
 
 /* Measurement aid, off by default (not part of the layer).  Stage numbers:
  * 0 gate, 1 dispatch plan, 2 row-tile table, 3 pack (scatter), 4 first expert GEMM
- * (+ activation), 5 second expert GEMM, 6 combine.
+ * (+ activation), 5 second expert GEMM, 6 combine; backward pass (moe_train.h): 7 recomputed
+ * pre-activation GEMM, 8 hidden-gradient GEMM, 9 input-gradient GEMM, 10 and 11 the weight
+ * gradient GEMMs of the second and first layer, 12 all its other kernels together.
  * moe_profile_enable: for every stage whose bit is set in stage_mask, the next
  * max_samples launches of that stage are bracketed by a pair of timing events
  * recorded on the stream the stage runs on.  (0, 0) switches it off and frees the

@@ -220,7 +220,8 @@ def moe_layer_chunked(s: Shape, n_chunks: int, x, Wgp, gate_bias, bias_token_str
         _ptr(workspace), _stream(stream)))
 
 
-STAGES = ("route", "plan", "tiles", "scatter", "gemm1", "gemm2", "combine")
+STAGES = ("route", "plan", "tiles", "scatter", "gemm1", "gemm2", "combine",
+          "bwd_recompute", "bwd_dP", "bwd_dxe", "bwd_wgrad2", "bwd_wgrad1", "bwd_other")
 
 
 def moe_profile_enable(stage_mask: int, max_samples: int) -> None:

@@ -20,6 +20,8 @@
 
 #include <algorithm>
 
+#include <hip/hip_ext.h>
+
 namespace moe {
 namespace {
 
@@ -581,7 +583,7 @@ bool supported(const moe_shape *s)
 template <int MODE, int EPI, int ACT, bool KTAIL>
 void launch_gemm_k(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, const WorkItem *items,
                    const int32_t *nitems, const int32_t *koff, int E, int M, int N, int K,
-                   int grid_items, hipStream_t st)
+                   int grid_items, int stage, hipStream_t st)
 {
     auto kern = bwd_gemm_kernel<MODE, EPI, ACT, KTAIL>;
     static bool configured = false;
@@ -593,19 +595,23 @@ void launch_gemm_k(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, c
     }
     const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
     const int grid = static_cast<int>(align_up(static_cast<size_t>(grid_items), 8));
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), kGemmLds, st, A, W, C, P, items, nitems, koff, E,
-                       M, N, K, tiles_m, tiles_n);
+    hipEvent_t t0, t1;
+    prof_kernel_events(stage, &t0, &t1);
+    hipExtLaunchKernelGGL(kern, dim3(grid), dim3(256), kGemmLds, st, t0, t1, 0, A, W, C, P, items,
+                          nitems, koff, E, M, N, K, tiles_m, tiles_n);
 }
 
 template <int MODE, int EPI, int ACT>
 void launch_gemm(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, const WorkItem *items,
                  const int32_t *nitems, const int32_t *koff, int E, int M, int N, int K,
-                 int grid_items, hipStream_t st)
+                 int grid_items, int stage, hipStream_t st)
 {
     if (MODE == 1 || K % kBK == 0)
-        launch_gemm_k<MODE, EPI, ACT, false>(A, W, C, P, items, nitems, koff, E, M, N, K, grid_items, st);
+        launch_gemm_k<MODE, EPI, ACT, false>(A, W, C, P, items, nitems, koff, E, M, N, K, grid_items,
+                                             stage, st);
     else
-        launch_gemm_k<MODE, EPI, ACT, true>(A, W, C, P, items, nitems, koff, E, M, N, K, grid_items, st);
+        launch_gemm_k<MODE, EPI, ACT, true>(A, W, C, P, items, nitems, koff, E, M, N, K, grid_items,
+                                            stage, st);
 }
 
 template <int ACT>
@@ -627,13 +633,13 @@ moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, c
     const GemmPlan &g0 = w.lists.gp[0], &g1 = w.lists.gp[1];
     // P = xe W1 (fp16), Hb = act(P) (bf16)
     launch_gemm<0, 1, ACT>(xe, W1p, w.Hb, w.P, w.lists.items[0], w.lists.nitems[0], nullptr, E, 0, h,
-                           d, g0.max_items, st);
+                           d, g0.max_items, kStageBwdRecompute, st);
     // dP = (dye W2^T) * act'(P): W2 [E][h][d] is already "rows n = h, contraction d contiguous"
     launch_gemm<0, 2, ACT>(w.dye, W2, w.dP, w.P, w.lists.items[0], w.lists.nitems[0], nullptr, E, 0,
-                           h, d, g0.max_items, st);
+                           h, d, g0.max_items, kStageBwdDP, st);
     // dxe = dP W1^T: W1 [E][d][h] is "rows n = d, contraction h contiguous"
     launch_gemm<0, 0, ACT>(w.dP, W1, w.dxe, nullptr, w.lists.items[1], w.lists.nitems[1], nullptr, E,
-                           0, d, h, g1.max_items, st);
+                           0, d, h, g1.max_items, kStageBwdDxe, st);
     // transposed, per-expert zero-padded copies for the weight gradients
     const dim3 tb(256);
     const int kblocks = w.lda / 64;
@@ -647,9 +653,9 @@ moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, c
                        offsets, w.koff, E, d, w.lda);
     // dW2[e] [h][d] = Hb^T dye ; dW1[e] [d][h] = xe^T dP
     launch_gemm<1, 0, ACT>(w.HT, w.dyeT, dW2, nullptr, nullptr, nullptr, w.koff, E, h, d, w.lda,
-                           E * ceil_div(h, kBM) * ceil_div(d, kBN), st);
+                           E * ceil_div(h, kBM) * ceil_div(d, kBN), kStageBwdWgrad2, st);
     launch_gemm<1, 0, ACT>(w.xeT, w.dPT, dW1, nullptr, nullptr, nullptr, w.koff, E, d, h, w.lda,
-                           E * ceil_div(d, kBM) * ceil_div(h, kBN), st);
+                           E * ceil_div(d, kBM) * ceil_div(h, kBN), kStageBwdWgrad1, st);
     // gate: dz, dx, dWg
     int EP = 1;
     while (EP < E) EP <<= 1;

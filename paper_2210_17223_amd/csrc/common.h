@@ -63,7 +63,10 @@ bool layout_workspace(const moe_shape &s, int n_chunks, void *base, Workspace *w
 // Optional per-stage timing (moe_profile_enable): when a stage is enabled, its
 // launches are bracketed by a pair of timing events on the stream they run on.
 enum Stage { kStageRoute = 0, kStagePlan, kStageTiles, kStageScatter, kStageGemm1, kStageGemm2,
-             kStageCombine, kNumStages };
+             kStageCombine,
+             // backward pass: the five GEMMs (each one kernel), and everything else
+             kStageBwdRecompute, kStageBwdDP, kStageBwdDxe, kStageBwdWgrad2, kStageBwdWgrad1,
+             kStageBwdOther, kNumStages };
 // Tokens per block of the gate kernel for this shape = tokens per segment of the plan.
 int route_segment_tokens(const moe_shape &s);
 void prof_begin(int stage, hipStream_t st);

@@ -8,6 +8,7 @@ import pytest
 import torch
 
 import oracle
+import paper_2210_17223_amd as moe
 import workloads as wl
 from gpu_util import DeviceLayer, assert_ints_equal, download, rel_rms_err, shape_of, upload
 
@@ -134,3 +135,36 @@ def test_inference_stack():
         drift = np.linalg.norm(y - o.y) / np.linalg.norm(o.y)
         assert drift <= TOL_BF16, f"layer {l}: relative Frobenius drift {drift}"
         x_dev = L.b["y_act"].view(T, d)
+
+
+def test_backward_at_the_bench_configuration():
+    """Forward + backward of configuration 2 at full size against the backward oracle
+    (every gradient, every expert)."""
+    from oracle import bwd_oracle as bo
+    cfg = wl.CONFIGS["gpt2s_moe"]
+    li = wl.make_layer(cfg, seed=0, threads=16)
+    T, d, E, h, k = li.T, li.d, li.E, li.h, li.k
+    s = shape_of(li)
+    L = DeviceLayer(li, s)
+    L.layer(1)
+    b = L.b
+    dy = np.random.Generator(np.random.PCG64(31)).standard_normal((T, d)).astype(np.float32)
+    W1, W2 = upload(li.W1, "bf16"), upload(li.W2, "bf16")
+    f32 = lambda n: torch.full((n,), 3.0, dtype=torch.float32, device="cuda:0")
+    g = dict(dx=f32(T * d), dWg=f32(d * E), dW1=f32(E * d * h), dW2=f32(E * d * h), dgate=f32(T * k))
+    ws = torch.empty(moe.moe_backward_workspace_bytes(s), dtype=torch.uint8, device="cuda:0")
+    moe.moe_layer_backward(s, L.x, b["Wgp"], None, 0, W1, W2, b["W1p"], b["expert_idx"], b["gate"],
+                           b["offsets"], b["slot_of"], b["src_of"], b["xe"], b["ye"],
+                           torch.from_numpy(dy).to("cuda:0"), g["dx"], g["dWg"], g["dW1"], g["dW2"],
+                           g["dgate"], ws)
+    torch.cuda.synchronize()
+    o = bo.moe_layer_backward(li.x, li.Wg, li.W1, li.W2, dy, k=k, capacity=li.C)
+    assert np.array_equal(b["slot_of"].cpu().numpy(), o.fwd.slot_of)
+    tol = 3e-2          # two chained bf16 operand roundings (see the backward parity tests)
+    assert rel_rms_err(g["dgate"].cpu().numpy().reshape(T, k), o.dgate) <= 5e-3
+    assert rel_rms_err(g["dx"].cpu().numpy().reshape(T, d), o.dx) <= tol
+    assert rel_rms_err(g["dWg"].cpu().numpy().reshape(d, E), o.dWg) <= tol
+    dW1, dW2 = g["dW1"].cpu().numpy().reshape(E, d, h), g["dW2"].cpu().numpy().reshape(E, h, d)
+    for e in range(E):
+        assert rel_rms_err(dW1[e], o.dW1[e]) <= tol, e
+        assert rel_rms_err(dW2[e], o.dW2[e]) <= tol, e
