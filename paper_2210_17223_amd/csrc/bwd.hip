@@ -31,8 +31,9 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
-constexpr int kBM = 128, kBN = 128, kBK = 64, kLD = kBK + 8;
-constexpr size_t kGemmLds = 2 * (kBM + kBN) * kLD * sizeof(uint16_t);
+constexpr int kBM = 128, kBK = 64, kLD = kBK + 8;
+// output tile 128 x (64 WN): WN = 2 (four wavefronts) or 4 (eight)
+constexpr size_t gemm_lds(int wn) { return 2 * (kBM + 64 * wn) * kLD * sizeof(uint16_t); }
 
 // Phi(v), the normal CDF, as 1 / (1 + 2^(v Q(min(v^2, 49)))) with the cubic Q of the forward's
 // GeLU (absolute error of v Phi(v) below 1.5e-5).
@@ -128,14 +129,15 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(
 //   A and W being [M or N][lda] transposed activations, k over expert e's padded rows.
 // EPI 0: fp32 store.  EPI 1: P = acc as fp16 into Pbuf and act(acc) as bf16 into C.
 // EPI 2: acc * act'(Pbuf) as bf16 into C.
-template <int MODE, int EPI, int ACT, bool KTAIL>
-__global__ __launch_bounds__(256, 2) void bwd_gemm_kernel(
+template <int MODE, int EPI, int ACT, bool KTAIL, int WN>
+__global__ __launch_bounds__(128 * WN, 2) void bwd_gemm_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, void *__restrict__ Cout,
     _Float16 *__restrict__ Pbuf, const WorkItem *__restrict__ items,
     const int32_t *__restrict__ nitems, const int32_t *__restrict__ koff, int E, int M, int N,
     int K, int tiles_m, int tiles_n)
 {
-    constexpr int WM = 2, TM = 2, TN = 2, NT = 256;   // 2 x 2 wavefronts of 64 x 64
+    constexpr int WM = 2, TM = 2, TN = 2, NT = 128 * WN;   // 2 x WN wavefronts of 64 x 64
+    constexpr int kBN = 64 * WN;
     constexpr int AV = kBM * 8 / NT, WV = kBN * 8 / NT;
     int expert, row0, row1, n0, KT;
     size_t a_pitch, a_base, w_base;
@@ -198,31 +200,31 @@ __global__ __launch_bounds__(256, 2) void bwd_gemm_kernel(
             w_off[q] = r * kLD + ld_col;
             w_src[q] = W + w_base + static_cast<size_t>(min(n0 + r, N - 1)) * a_pitch + ld_col;
         }
-        u32x4 a_reg[AV], w_reg[WV];
+        u32x4 a_reg[AV], w_reg[WV], a_reg2[AV], w_reg2[WV];   // two register stages of prefetch
         u32x4 wf[2][TN], af[2][TM];
         const int wfrag = (wn * TN * 32 + fr) * kLD + fk;
         const int afrag = (wm * TM * 32 + fr) * kLD + fk;
-#define BWD_LOADG(kt_)                                                                          \
+#define BWD_LOADG(kt_, AR, WR)                                                                  \
     {                                                                                           \
         const int k0_ = (kt_) * kBK;                                                            \
         const bool in_ = !KTAIL || k0_ + ld_col < K;                                           \
         _Pragma("unroll") for (int q = 0; q < AV; ++q)                                          \
         {                                                                                       \
-            if (in_) a_reg[q] = *reinterpret_cast<const u32x4 *>(a_src[q] + k0_);               \
-            else a_reg[q] = (u32x4){0u, 0u, 0u, 0u};                                            \
+            if (in_) AR[q] = *reinterpret_cast<const u32x4 *>(a_src[q] + k0_);                  \
+            else AR[q] = (u32x4){0u, 0u, 0u, 0u};                                               \
         }                                                                                       \
         _Pragma("unroll") for (int q = 0; q < WV; ++q)                                          \
         {                                                                                       \
-            if (in_) w_reg[q] = *reinterpret_cast<const u32x4 *>(w_src[q] + k0_);               \
-            else w_reg[q] = (u32x4){0u, 0u, 0u, 0u};                                            \
+            if (in_) WR[q] = *reinterpret_cast<const u32x4 *>(w_src[q] + k0_);                  \
+            else WR[q] = (u32x4){0u, 0u, 0u, 0u};                                               \
         }                                                                                       \
     }
-#define BWD_STOREL(buf)                                                                         \
+#define BWD_STOREL(buf, AR, WR)                                                                 \
     {                                                                                           \
         _Pragma("unroll") for (int q = 0; q < AV; ++q)                                          \
-            *reinterpret_cast<u32x4 *>(As + (buf) * A_BUF + a_off[q]) = a_reg[q];               \
+            *reinterpret_cast<u32x4 *>(As + (buf) * A_BUF + a_off[q]) = AR[q];                  \
         _Pragma("unroll") for (int q = 0; q < WV; ++q)                                          \
-            *reinterpret_cast<u32x4 *>(Ws + (buf) * W_BUF + w_off[q]) = w_reg[q];               \
+            *reinterpret_cast<u32x4 *>(Ws + (buf) * W_BUF + w_off[q]) = WR[q];                  \
     }
 #define BWD_READF(slot_, buf, ks)                                                               \
     {                                                                                           \
@@ -239,26 +241,39 @@ __global__ __launch_bounds__(256, 2) void bwd_gemm_kernel(
                     __builtin_bit_cast(bf16x8, wf[slot_][i]),                                   \
                     __builtin_bit_cast(bf16x8, af[slot_][j]), acc[i][j], 0, 0, 0);              \
     }
-        BWD_LOADG(0)
-        BWD_STOREL(0)
-        if (KT > 1) BWD_LOADG(1)
+// stage kt in LDS buffer `buf`: AR/WR (stage kt+1) go to the other buffer and are refilled
+// with stage kt+3
+#define BWD_STAGE(buf, AR, WR)                                                                  \
+    {                                                                                           \
+        const bool next1 = kt + 1 < KT, next3 = kt + 3 < KT;                                    \
+        if (next1) BWD_STOREL(buf ^ 1, AR, WR)                                                  \
+        if (next3) BWD_LOADG(kt + 3, AR, WR)                                                    \
+        BWD_READF(1, buf, 1)                                                                    \
+        BWD_MMA(0)                                                                              \
+        BWD_READF(0, buf, 2)                                                                    \
+        BWD_MMA(1)                                                                              \
+        BWD_READF(1, buf, 3)                                                                    \
+        BWD_MMA(0)                                                                              \
+        __syncthreads();                                                                        \
+        __builtin_amdgcn_sched_barrier(0);                                                      \
+        if (next1) BWD_READF(0, buf ^ 1, 0)                                                     \
+        BWD_MMA(1)                                                                              \
+    }
+        BWD_LOADG(0, a_reg, w_reg)
+        BWD_STOREL(0, a_reg, w_reg)
+        if (KT > 1) BWD_LOADG(1, a_reg, w_reg)
+        if (KT > 2) BWD_LOADG(2, a_reg2, w_reg2)
         __syncthreads();
         BWD_READF(0, 0, 0)
-        for (int kt = 0; kt < KT; ++kt) {
-            const int buf = kt & 1;
-            const bool next1 = kt + 1 < KT, next2 = kt + 2 < KT;
-            if (next1) BWD_STOREL(buf ^ 1)
-            if (next2) BWD_LOADG(kt + 2)
-            BWD_READF(1, buf, 1)
-            BWD_MMA(0)
-            BWD_READF(0, buf, 2)
-            BWD_MMA(1)
-            BWD_READF(1, buf, 3)
-            BWD_MMA(0)
-            __syncthreads();
-            if (next1) BWD_READF(0, buf ^ 1, 0)
-            BWD_MMA(1)
+        int kt = 0;
+        for (; kt + 1 < KT; kt += 2) {
+            BWD_STAGE(0, a_reg, w_reg)
+            ++kt;
+            BWD_STAGE(1, a_reg2, w_reg2)
+            --kt;
         }
+        if (kt < KT) BWD_STAGE(0, a_reg, w_reg)
+#undef BWD_STAGE
 #undef BWD_LOADG
 #undef BWD_STOREL
 #undef BWD_READF
@@ -523,13 +538,15 @@ struct BwdWorkspace {
     size_t bytes;
 };
 
-GemmPlan plan128(int N, int64_t max_rows, int E)
+// 128-row tiles; 256 columns wide when the contraction is long enough to pay for the larger
+// tile's prologue (as in the forward), else 128
+GemmPlan plan128(int N, int K, int64_t max_rows, int E)
 {
     GemmPlan gp;
     gp.bm = kBM;
-    gp.bn = kBN;
-    gp.concurrent = 64;
-    gp.tiles_n = (N + kBN - 1) / kBN;
+    gp.bn = (K >= 2048 && N >= 256) ? 256 : 128;
+    gp.concurrent = gp.bn == 256 ? 32 : 64;
+    gp.tiles_n = (N + gp.bn - 1) / gp.bn;
     gp.max_row_tiles = static_cast<int32_t>((max_rows + kBM - 1) / kBM + E);
     gp.max_items = gp.max_row_tiles * gp.tiles_n;
     return gp;
@@ -546,8 +563,8 @@ void layout_bwd(const moe_shape &s, void *base, BwdWorkspace *w)
         return at;
     };
     w->lists = Workspace{};
-    w->lists.gp[0] = plan128(s.d_ff, R, s.E);
-    w->lists.gp[1] = plan128(s.d_model, R, s.E);
+    w->lists.gp[0] = plan128(s.d_ff, s.d_model, R, s.E);
+    w->lists.gp[1] = plan128(s.d_model, s.d_ff, R, s.E);
     for (int g = 0; g < 2; ++g) {
         w->lists.items[g] = reinterpret_cast<WorkItem *>(take(sizeof(WorkItem) * w->lists.gp[g].max_items));
         w->lists.nitems[g] = reinterpret_cast<int32_t *>(take(sizeof(int32_t)));
@@ -580,12 +597,14 @@ bool supported(const moe_shape *s)
     return s->d_model % 8 == 0 && s->d_ff % 8 == 0;
 }
 
-template <int MODE, int EPI, int ACT, bool KTAIL>
+template <int MODE, int EPI, int ACT, bool KTAIL, int WN>
 void launch_gemm_k(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, const WorkItem *items,
                    const int32_t *nitems, const int32_t *koff, int E, int M, int N, int K,
                    int grid_items, int stage, hipStream_t st)
 {
-    auto kern = bwd_gemm_kernel<MODE, EPI, ACT, KTAIL>;
+    auto kern = bwd_gemm_kernel<MODE, EPI, ACT, KTAIL, WN>;
+    constexpr size_t kGemmLds = gemm_lds(WN);
+    constexpr int kBN = 64 * WN;
     static bool configured = false;
     if (!configured) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -597,21 +616,25 @@ void launch_gemm_k(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, c
     const int grid = static_cast<int>(align_up(static_cast<size_t>(grid_items), 8));
     hipEvent_t t0, t1;
     prof_kernel_events(stage, &t0, &t1);
-    hipExtLaunchKernelGGL(kern, dim3(grid), dim3(256), kGemmLds, st, t0, t1, 0, A, W, C, P, items,
+    hipExtLaunchKernelGGL(kern, dim3(grid), dim3(128 * WN), kGemmLds, st, t0, t1, 0, A, W, C, P, items,
                           nitems, koff, E, M, N, K, tiles_m, tiles_n);
 }
 
 template <int MODE, int EPI, int ACT>
 void launch_gemm(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, const WorkItem *items,
-                 const int32_t *nitems, const int32_t *koff, int E, int M, int N, int K,
+                 const int32_t *nitems, const int32_t *koff, int E, int M, int N, int K, int bn,
                  int grid_items, int stage, hipStream_t st)
 {
-    if (MODE == 1 || K % kBK == 0)
-        launch_gemm_k<MODE, EPI, ACT, false>(A, W, C, P, items, nitems, koff, E, M, N, K, grid_items,
-                                             stage, st);
-    else
-        launch_gemm_k<MODE, EPI, ACT, true>(A, W, C, P, items, nitems, koff, E, M, N, K, grid_items,
-                                            stage, st);
+#define MOE_BWD_GEMM(KTAIL_, WN_)                                                                 \
+    launch_gemm_k<MODE, EPI, ACT, KTAIL_, WN_>(A, W, C, P, items, nitems, koff, E, M, N, K,       \
+                                               grid_items, stage, st)
+    const bool tail = MODE == 0 && K % kBK != 0;
+    if (bn == 256) {
+        if (tail) MOE_BWD_GEMM(true, 4); else MOE_BWD_GEMM(false, 4);
+    } else {
+        if (tail) MOE_BWD_GEMM(true, 2); else MOE_BWD_GEMM(false, 2);
+    }
+#undef MOE_BWD_GEMM
 }
 
 template <int ACT>
@@ -633,13 +656,13 @@ moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, c
     const GemmPlan &g0 = w.lists.gp[0], &g1 = w.lists.gp[1];
     // P = xe W1 (fp16), Hb = act(P) (bf16)
     launch_gemm<0, 1, ACT>(xe, W1p, w.Hb, w.P, w.lists.items[0], w.lists.nitems[0], nullptr, E, 0, h,
-                           d, g0.max_items, kStageBwdRecompute, st);
+                           d, g0.bn, g0.max_items, kStageBwdRecompute, st);
     // dP = (dye W2^T) * act'(P): W2 [E][h][d] is already "rows n = h, contraction d contiguous"
     launch_gemm<0, 2, ACT>(w.dye, W2, w.dP, w.P, w.lists.items[0], w.lists.nitems[0], nullptr, E, 0,
-                           h, d, g0.max_items, kStageBwdDP, st);
+                           h, d, g0.bn, g0.max_items, kStageBwdDP, st);
     // dxe = dP W1^T: W1 [E][d][h] is "rows n = d, contraction h contiguous"
     launch_gemm<0, 0, ACT>(w.dP, W1, w.dxe, nullptr, w.lists.items[1], w.lists.nitems[1], nullptr, E,
-                           0, d, h, g1.max_items, kStageBwdDxe, st);
+                           0, d, h, g1.bn, g1.max_items, kStageBwdDxe, st);
     // transposed, per-expert zero-padded copies for the weight gradients
     const dim3 tb(256);
     const int kblocks = w.lda / 64;
@@ -652,10 +675,10 @@ moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, c
     hipLaunchKernelGGL(transpose_rows_kernel, dim3(kblocks, ceil_div(d, 64)), tb, 0, st, xe, w.xeT,
                        offsets, w.koff, E, d, w.lda);
     // dW2[e] [h][d] = Hb^T dye ; dW1[e] [d][h] = xe^T dP
-    launch_gemm<1, 0, ACT>(w.HT, w.dyeT, dW2, nullptr, nullptr, nullptr, w.koff, E, h, d, w.lda,
-                           E * ceil_div(h, kBM) * ceil_div(d, kBN), kStageBwdWgrad2, st);
-    launch_gemm<1, 0, ACT>(w.xeT, w.dPT, dW1, nullptr, nullptr, nullptr, w.koff, E, d, h, w.lda,
-                           E * ceil_div(d, kBM) * ceil_div(h, kBN), kStageBwdWgrad1, st);
+    launch_gemm<1, 0, ACT>(w.HT, w.dyeT, dW2, nullptr, nullptr, nullptr, w.koff, E, h, d, w.lda, 128,
+                           E * ceil_div(h, kBM) * ceil_div(d, 128), kStageBwdWgrad2, st);
+    launch_gemm<1, 0, ACT>(w.xeT, w.dPT, dW1, nullptr, nullptr, nullptr, w.koff, E, d, h, w.lda, 128,
+                           E * ceil_div(d, kBM) * ceil_div(h, 128), kStageBwdWgrad1, st);
     // gate: dz, dx, dWg
     int EP = 1;
     while (EP < E) EP <<= 1;
