@@ -90,8 +90,20 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(
     const int g = threadIdx.x / EPs;
     const int per = ceil_div(nseg, G);
     const int s0 = min(g * per, nseg), s1 = min(s0 + per, nseg);
+    // The common case (at most eight segments per group) keeps the group's counts in
+    // registers: one batch of loads instead of two dependent passes over global memory.
+    constexpr int kKeep = 8;
+    int32_t c[kKeep];
     int32_t local = 0;
-    for (int s = s0; s < s1; ++s) local += seg_cnt[static_cast<size_t>(s) * kMaxExperts + e];
+    if (per <= kKeep) {
+#pragma unroll
+        for (int q = 0; q < kKeep; ++q)
+            c[q] = s0 + q < s1 ? seg_cnt[static_cast<size_t>(s0 + q) * kMaxExperts + e] : 0;
+#pragma unroll
+        for (int q = 0; q < kKeep; ++q) local += c[q];
+    } else {
+        for (int s = s0; s < s1; ++s) local += seg_cnt[static_cast<size_t>(s) * kMaxExperts + e];
+    }
     if (g < G) gsum[g * EPs + e] = local;
     if (threadIdx.x < kMaxExperts) kept[threadIdx.x] = 0;
     __syncthreads();
@@ -102,11 +114,19 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(
         total += v;
     }
     int32_t running = before;
-    for (int s = s0; s < s1; ++s) {
-        const size_t at = static_cast<size_t>(s) * kMaxExperts + e;
-        const int32_t c = seg_cnt[at];
-        seg_cnt[at] = running;
-        running += c;
+    if (per <= kKeep) {
+#pragma unroll
+        for (int q = 0; q < kKeep; ++q) {
+            if (s0 + q < s1) seg_cnt[static_cast<size_t>(s0 + q) * kMaxExperts + e] = running;
+            running += c[q];
+        }
+    } else {
+        for (int s = s0; s < s1; ++s) {
+            const size_t at = static_cast<size_t>(s) * kMaxExperts + e;
+            const int32_t cc = seg_cnt[at];
+            seg_cnt[at] = running;
+            running += cc;
+        }
     }
     if (g == 0 && e < E) {
         counts[e] = total;
