@@ -51,6 +51,10 @@ def main() -> int:
     ap.add_argument("--backward", action="store_true",
                     help="a step is forward + backward of the layer (moe_layer_backward); the roofline "
                          "object is then for the second layer's weight-gradient GEMM")
+    ap.add_argument("--offload", type=int, default=0, metavar="R",
+                    help="expert weights stay in (pinned) host memory and stream through R device "
+                         "slots (moe_expert_ffn_offloaded); the step is gate, dispatch, that FFN and "
+                         "combine; a stack workload contributes its first layer")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten plain device copies of 256 MiB and exit: under rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE the copy kernel's reading fixes the counter's unit")
@@ -85,6 +89,8 @@ def main() -> int:
     cfg = wl.CONFIGS[args.workload]
     n_layers = cfg["layers"]
     host = wl.make_stack(cfg, seed=0, threads=16) if n_layers > 1 else [wl.make_layer(cfg, seed=0, threads=16)]
+    if args.offload:
+        host, n_layers = host[:1], 1
     l0 = host[0]
     bf16 = l0.dtype == "bf16"
     s = moe.Shape.make(l0.T, l0.d, l0.E, l0.h, l0.k, l0.C, dtype="bf16" if bf16 else "f32", act="gelu")
@@ -109,6 +115,11 @@ def main() -> int:
                 W1, W2 = up(li.W1), up(li.W2)
                 moe.moe_pack_weights(s, W1, W2, self.b["W1p"], self.b["W2p"])
                 torch.cuda.synchronize()
+                if args.offload:
+                    self.W1h, self.W2h = self.b["W1p"].cpu().pin_memory(), self.b["W2p"].cpu().pin_memory()
+                    self.staging = torch.empty(moe.moe_offload_staging_bytes(s, args.offload),
+                                               dtype=torch.uint8, device=dev)
+                    self.ows = torch.empty(moe.moe_offload_workspace_bytes(s), dtype=torch.uint8, device=dev)
                 if args.backward:
                     self.W1, self.W2 = W1, W2
                     f32 = lambda n: torch.empty(n, dtype=torch.float32, device=dev)
@@ -129,6 +140,14 @@ def main() -> int:
 
         def run(self, x):
             b = self.b
+            if args.offload:
+                moe.moe_route(s, x, b["Wgp"], self.bias, self.stride, b["expert_idx"], b["gate"])
+                moe.moe_dispatch(s, x, b["expert_idx"], b["counts"], b["offsets"], b["slot_of"],
+                                 b["src_of"], b["xe"], b["workspace"])
+                moe.moe_expert_ffn_offloaded(s, b["xe"], b["offsets"], self.W1h, self.W2h, None, None,
+                                             b["ye"], self.staging, args.offload, self.ows)
+                moe.moe_combine(s, b["ye"], b["slot_of"], b["gate"], b["y"], b["y_act"])
+                return
             moe.moe_layer_chunked(s, args.chunks, x, b["Wgp"], self.bias, self.stride, b["W1p"], None,
                                   b["W2p"], None, b["expert_idx"], b["gate"], b["counts"], b["offsets"],
                                   b["slot_of"], b["src_of"], b["xe"], b["ye"], b["y"], b["y_act"],
@@ -160,6 +179,9 @@ def main() -> int:
     launches = args.steps * args.chunks * n_layers
     for _ in range(args.warmup):
         step(sets[0])
+    if args.offload and (args.backward or args.chunks != 1 or not bf16):
+        print("bench.py: --offload takes a bf16 workload, --chunks 1, no --backward", file=sys.stderr)
+        return 2
     if args.backward and (n_layers != 1 or args.chunks != 1 or not bf16):
         print("bench.py: --backward takes a one-layer bf16 workload and --chunks 1", file=sys.stderr)
         return 2
@@ -203,12 +225,22 @@ def main() -> int:
     else:
         roof.update({"bound": "mfma", "achieved": g1_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": g1_tflops / PEAK_BF16_TFLOPS})
+    if args.offload:
+        # the step is bound by the host link: every expert's packed weights cross it once
+        link_bytes = 2.0 * l0.E * l0.d * l0.h * 2
+        roof = {"bound": "hbm", "kernel": "host-to-device copies of the expert weights (copy engine)",
+                "note": "bound by the host link, not by HBM: 'peak' is PCIe 5.0 x16, 64 GB/s per direction",
+                "achieved": link_bytes / (ms_per_step * 1e-3) / 1e9, "peak": 64.0, "unit": "GB/s",
+                "frac": link_bytes / (ms_per_step * 1e-3) / 1e9 / 64.0, "traffic": None,
+                "algorithmic_bytes": link_bytes, "resident_slots": args.offload,
+                "first_gemm_avg_launch_us": g1_avg_ms * 1e3}
     if not bf16:
         roof = {"bound": "alu", "note": "fp32 correctness configuration: launch-bound, no roofline claimed",
                 "achieved": None, "peak": None, "unit": None, "frac": None, "traffic": None,
                 "avg_launch_us": g1_avg_ms * 1e3}
     out = {
-        "metric": "moe_layer_fwd_bwd_tokens_per_s" if args.backward else "moe_layer_tokens_per_s",
+        "metric": ("moe_layer_fwd_bwd_tokens_per_s" if args.backward else
+                   "moe_layer_offloaded_tokens_per_s" if args.offload else "moe_layer_tokens_per_s"),
         "value": tokens_per_s * n_layers, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -224,7 +256,8 @@ def main() -> int:
 
     # ---- the same steps with cold caches -------------------------------------------------
     set_bytes = sum(L.bytes() for L in sets[0])
-    if args.cold_sets > 1 and n_layers == 1 and set_bytes <= 4 * INFINITY_CACHE_BYTES and not args.backward:
+    if (args.cold_sets > 1 and n_layers == 1 and set_bytes <= 4 * INFINITY_CACHE_BYTES
+            and not args.backward and not args.offload):
         while len(sets) < args.cold_sets:
             sets.append([DevLayer(like=L) for L in sets[0]])
         n = len(sets)

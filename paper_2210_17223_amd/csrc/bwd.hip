@@ -605,12 +605,11 @@ void launch_gemm_k(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, c
     auto kern = bwd_gemm_kernel<MODE, EPI, ACT, KTAIL, WN>;
     constexpr size_t kGemmLds = gemm_lds(WN);
     constexpr int kBN = 64 * WN;
-    static bool configured = false;
-    if (!configured) {
+    static PerDeviceOnce once;   // raising the dynamic LDS limit: once per kernel and device
+    if (once.first()) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                   hipFuncAttributeMaxDynamicSharedMemorySize,
                                   static_cast<int>(kGemmLds));
-        configured = true;
     }
     const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
     const int grid = static_cast<int>(align_up(static_cast<size_t>(grid_items), 8));

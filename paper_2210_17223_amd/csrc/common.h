@@ -25,6 +25,21 @@ moe_status hip_fail(hipError_t e, const char *what);
         if (e_ != hipSuccess) return ::moe::hip_fail(e_, #expr);      \
     } while (0)
 
+// True the first time it is called for the current device with this flag set (a kernel's
+// dynamic-LDS limit is raised once per kernel and per device).
+struct PerDeviceOnce {
+    uint64_t done = 0;                       // bit per device ordinal (up to 64 devices)
+    bool first()
+    {
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        const uint64_t bit = 1ull << (dev & 63);
+        if (done & bit) return false;
+        done |= bit;
+        return true;
+    }
+};
+
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
@@ -89,6 +104,9 @@ moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *c
                        const Workspace &w, bool counted, int n_chunks, hipStream_t st);
 moe_status launch_items(const moe_shape &s, int n_chunks, const int32_t *offsets,
                         const int32_t *src_of, const Workspace &w, hipStream_t st);
+// w.items[g] / w.nitems[g] sized for E lists: list e = the output tiles of expert e alone
+moe_status launch_items_per_expert(const moe_shape &s, const int32_t *offsets, const Workspace &w,
+                                   hipStream_t st);
 moe_status launch_scatter(const moe_shape &s, const void *x, const int32_t *slot_of,
                           void *xe, int t0, int t1, hipStream_t st);
 moe_status launch_combine(const moe_shape &s, const float *ye, const int32_t *slot_of,

@@ -287,7 +287,39 @@ __global__ __launch_bounds__(256) void plan_items_kernel(
     build_items(gp, items, nitems, lo_s, hi_s, mt_s, cum_s, blockIdx.z, gridDim.z);
 }
 
+// One work list per expert (list e holds expert e's output tiles only), for executing the
+// experts one after the other: block (e, g) builds list e of GEMM g.
+__global__ __launch_bounds__(256) void plan_items_expert_kernel(
+    const int32_t *__restrict__ offsets, WorkItem *__restrict__ items0,
+    int32_t *__restrict__ nitems0, GemmPlan gp0, WorkItem *__restrict__ items1,
+    int32_t *__restrict__ nitems1, GemmPlan gp1, int E)
+{
+    __shared__ int32_t lo_s[kMaxExperts], hi_s[kMaxExperts], mt_s[kMaxExperts];
+    __shared__ int32_t cum_s[kMaxExperts + 1];
+    const int only = blockIdx.x;
+    const GemmPlan gp = blockIdx.y == 0 ? gp0 : gp1;
+    WorkItem *items = (blockIdx.y == 0 ? items0 : items1) + static_cast<size_t>(only) * gp.max_items;
+    int32_t *nitems = (blockIdx.y == 0 ? nitems0 : nitems1) + only;
+    if (threadIdx.x < kWave) {
+        const int e = threadIdx.x;
+        const bool mine = e == only && e < E;
+        lo_s[e] = mine ? offsets[e] : 0;
+        hi_s[e] = mine ? offsets[e + 1] : 0;
+    }
+    __syncthreads();
+    build_items(gp, items, nitems, lo_s, hi_s, mt_s, cum_s, 0, 1);
+}
+
 }  // namespace
+
+moe_status launch_items_per_expert(const moe_shape &s, const int32_t *offsets, const Workspace &w,
+                                   hipStream_t st)
+{
+    hipLaunchKernelGGL(plan_items_expert_kernel, dim3(s.E, 2), dim3(256), 0, st, offsets, w.items[0],
+                       w.nitems[0], w.gp[0], w.items[1], w.nitems[1], w.gp[1], s.E);
+    MOE_TRY_HIP(hipGetLastError());
+    return MOE_OK;
+}
 
 moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *counts,
                        int32_t *offsets, int32_t *slot_of, int32_t *src_of,

@@ -296,11 +296,10 @@ moe_status launch_route_t(const moe_shape &s, const XT *x, const float *Wgp,
 #define MOE_ROUTE_CASE(TPL_, EPL_)                                                            \
     if (rs.tpl == TPL_ && rs.epl == EPL_) {                                                   \
         auto kern = route_kernel<XT, TPL_, EPL_>;                                             \
-        static bool configured = false;                                                       \
-        if (!configured) {                                                                    \
+        static PerDeviceOnce once;                                                            \
+        if (once.first()) {                                                                   \
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                   \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024); \
-            configured = true;                                                                \
         }                                                                                     \
         hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, x, Wgp, bias, bias_stride, \
                            expert_idx, gate, seg_cnt, s.T, s.d_model, dP, s.E, EP, rs.tb,     \
