@@ -294,6 +294,9 @@ def main() -> int:
         disp_bytes = (kept_tokens + A) * l0.d * esz * n_layers      # read routed tokens, write slots
         comb_bytes = (A + l0.T) * l0.d * 4 * n_layers               # fp32 expert rows in, fp32 y out
         st["dispatch_GBps"] = disp_bytes / (st["scatter"] * 1e-6) / 1e9
+        # gate: T*d*E sequential-order fp32 FMAs against the unpacked vector rate
+        # (256 CUs x 64 lanes x 2.4 GHz = 39.3 TFMA/s; packed-fp32 instructions are off)
+        st["route_alu_frac"] = (l0.T * l0.d * l0.E * n_layers) / (st["route"] * 1e-6) / 39.3e12
         st["combine_GBps"] = comb_bytes / (st["combine"] * 1e-6) / 1e9
         st["dispatch_combine_frac_of_hbm_peak"] = ((disp_bytes + comb_bytes) /
                                                    ((st["scatter"] + st["combine"]) * 1e-6) / 1e9 / PEAK_HBM_GBPS)
