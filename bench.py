@@ -51,6 +51,9 @@ def main() -> int:
     ap.add_argument("--backward", action="store_true",
                     help="a step is forward + backward of the layer (moe_layer_backward); the roofline "
                          "object is then for the second layer's weight-gradient GEMM")
+    ap.add_argument("--recompute", action="store_true",
+                    help="with --backward: the forward is the plain layer call and the backward pass "
+                         "computes the first GEMM again (default: moe_layer_forward_keep keeps it)")
     ap.add_argument("--offload", type=int, default=0, metavar="R",
                     help="expert weights stay in (pinned) host memory and stream through R device "
                          "slots (moe_expert_ffn_offloaded); the step is gate, dispatch, that FFN and "
@@ -127,6 +130,8 @@ def main() -> int:
                     self.g = [f32(l0.T * l0.d), f32(l0.d * l0.E), f32(l0.E * l0.d * l0.h),
                               f32(l0.E * l0.d * l0.h), f32(l0.T * l0.k)]
                     self.bws = torch.empty(moe.moe_backward_workspace_bytes(s), dtype=torch.uint8, device=dev)
+                    self.pre = None if args.recompute else torch.empty(
+                        moe.moe_max_rows(s) * l0.h, dtype=torch.float16, device=dev)
             else:       # a second copy of the same layer at other addresses
                 self.x = None if like.x is None else like.x.clone()
                 self.bias = None if like.bias is None else like.bias.clone()
@@ -148,14 +153,20 @@ def main() -> int:
                                              b["ye"], self.staging, args.offload, self.ows)
                 moe.moe_combine(s, b["ye"], b["slot_of"], b["gate"], b["y"], b["y_act"])
                 return
-            moe.moe_layer_chunked(s, args.chunks, x, b["Wgp"], self.bias, self.stride, b["W1p"], None,
-                                  b["W2p"], None, b["expert_idx"], b["gate"], b["counts"], b["offsets"],
-                                  b["slot_of"], b["src_of"], b["xe"], b["ye"], b["y"], b["y_act"],
-                                  b["workspace"])
+            if args.backward and self.pre is not None:
+                moe.moe_layer_forward_keep(s, x, b["Wgp"], self.bias, self.stride, b["W1p"], None, b["W2p"],
+                                           None, b["expert_idx"], b["gate"], b["counts"], b["offsets"],
+                                           b["slot_of"], b["src_of"], b["xe"], b["ye"], self.pre, b["y"],
+                                           b["workspace"])
+            else:
+                moe.moe_layer_chunked(s, args.chunks, x, b["Wgp"], self.bias, self.stride, b["W1p"], None,
+                                      b["W2p"], None, b["expert_idx"], b["gate"], b["counts"], b["offsets"],
+                                      b["slot_of"], b["src_of"], b["xe"], b["ye"], b["y"], b["y_act"],
+                                      b["workspace"])
             if args.backward:
                 moe.moe_layer_backward(s, x, b["Wgp"], self.bias, self.stride, self.W1, self.W2, b["W1p"],
                                        b["expert_idx"], b["gate"], b["offsets"], b["slot_of"], b["src_of"],
-                                       b["xe"], b["ye"], self.dy, *self.g, self.bws)
+                                       b["xe"], b["ye"], self.pre, self.dy, *self.g, self.bws)
 
     sets = [[DevLayer(li) for li in host]]
     for li in host:       # the host copies of the weights are needed again only by the oracle
@@ -304,8 +315,9 @@ def main() -> int:
         ffn_bytes = (2 * live * l0.d * l0.h * 2 + A * l0.d * 2 + 2 * A * l0.h * 2 + A * l0.d * 4) * n_layers
         st["ffn_GBps"] = ffn_bytes / ((st["gemm1"] + st["gemm2"]) * 1e-6) / 1e9
         if args.backward:
-            bw = ("bwd_recompute", "bwd_dP", "bwd_dxe", "bwd_wgrad2", "bwd_wgrad1")
-            st["bwd_gemm_mfma_util"] = (5 * 2.0 * A * l0.d * l0.h) / (sum(st[n] for n in bw) * 1e-6) / 1e12 / PEAK_BF16_TFLOPS
+            bw = [n for n in ("bwd_recompute", "bwd_dP", "bwd_dxe", "bwd_wgrad2", "bwd_wgrad1")
+                  if st[n] is not None]          # no recomputation when the forward kept P
+            st["bwd_gemm_mfma_util"] = (len(bw) * 2.0 * A * l0.d * l0.h) / (sum(st[n] for n in bw) * 1e-6) / 1e12 / PEAK_BF16_TFLOPS
         out["stages_us"] = st
         out["stages_us_median"] = med
         out["stages_us_min"] = mn

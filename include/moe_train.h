@@ -7,7 +7,8 @@
  *
  *   dye[slot]  = g[t,j] * dy[t]                 for every kept assignment (t, j)
  *   dgate[t,j] = <ye[slot], dy[t]>              (0 for dropped assignments)
- *   dP         = (dye . W2[e]^T) * act'(P)      P = xe . W1[e], recomputed here
+ *   dP         = (dye . W2[e]^T) * act'(P)      P = xe . W1[e]: kept by the forward call
+ *                                               below, else recomputed here
  *   dW2[e]     = act(P)^T . dye                 rows of expert e
  *   dW1[e]     = xe^T . dP
  *   dxe        = dP . W1[e]^T
@@ -33,6 +34,22 @@
 extern "C" {
 #endif
 
+/*
+ * The forward pass of a training step: moe_layer_chunked with one chunk (same arguments,
+ * same outputs bit for bit, no y_act) that also keeps the first expert GEMM's result
+ * before the activation, which the backward pass would otherwise compute again.
+ *   pre  [moe_max_rows, d_ff] fp16, output: pre[slot,:] = xe[slot,:] W1[e] + b1[e], rounded
+ *        from the fp32 accumulator; rows at or beyond offsets[E] are left untouched
+ * bf16 layers only.
+ */
+moe_status moe_layer_forward_keep(const moe_shape *s, const void *x, const float *Wgp,
+                                  const float *gate_bias, int32_t bias_token_stride,
+                                  const void *W1p, const float *b1, const void *W2p,
+                                  const float *b2, int32_t *expert_idx, float *gate,
+                                  int32_t *counts, int32_t *offsets, int32_t *slot_of,
+                                  int32_t *src_of, void *xe, float *ye, void *pre, float *y,
+                                  void *workspace, void *stream);
+
 /* Bytes of workspace moe_layer_backward needs for this shape (0 if unsupported). */
 size_t moe_backward_workspace_bytes(const moe_shape *s);
 
@@ -43,6 +60,8 @@ size_t moe_backward_workspace_bytes(const moe_shape *s);
  *                    canonical layouts; W1p the packed W1 of moe_pack_weights
  *   forward outputs  expert_idx, gate, offsets, slot_of, src_of, xe, ye exactly as the
  *                    forward call left them
+ *   pre              NULL, or the buffer moe_layer_forward_keep filled in that forward call
+ *                    (the backward pass of a layer with FFN biases is not supported either way)
  *   dy               [T,d] fp32
  *   dx [T,d], dWg [d,E], dW1 [E,d,h], dW2 [E,h,d], dgate [T*k]: fp32, overwritten (weight
  *                    gradients of an expert without rows are zero)
@@ -53,8 +72,8 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
                               const int32_t *expert_idx, const float *gate,
                               const int32_t *offsets, const int32_t *slot_of,
                               const int32_t *src_of, const void *xe, const float *ye,
-                              const float *dy, float *dx, float *dWg, float *dW1, float *dW2,
-                              float *dgate, void *workspace, void *stream);
+                              const void *pre, const float *dy, float *dx, float *dWg, float *dW1,
+                              float *dW2, float *dgate, void *workspace, void *stream);
 
 #ifdef __cplusplus
 }

@@ -17,10 +17,11 @@ from .sched_binding import (PathShape, moe_devices_for_expert, moe_path_count, m
 
 from .offload_binding import (moe_expert_ffn_offloaded, moe_offload_staging_bytes,
                               moe_offload_workspace_bytes)
-from .train_binding import moe_backward_workspace_bytes, moe_layer_backward
+from .train_binding import (moe_backward_workspace_bytes, moe_layer_backward,
+                            moe_layer_forward_keep)
 
 __all__ = ["moe_expert_ffn_offloaded", "moe_offload_staging_bytes", "moe_offload_workspace_bytes",
-           "moe_backward_workspace_bytes", "moe_layer_backward", "PathShape", "moe_devices_for_expert", "moe_path_count", "moe_path_finalize",
+           "moe_backward_workspace_bytes", "moe_layer_backward", "moe_layer_forward_keep", "PathShape", "moe_devices_for_expert", "moe_path_count", "moe_path_finalize",
            "moe_path_profile", "moe_popularity_estimate", "moe_schedule_experts",
            "moe_schedule_layer", "moe_top_lists_identical",
            "ACT", "DTYPE", "MoeError", "Shape", "alloc_buffers", "lib", "lib_path",

@@ -6,6 +6,7 @@
 #include <mutex>
 
 #include "common.h"
+#include "moe_train.h"
 
 namespace moe {
 
@@ -413,13 +414,18 @@ moe_status moe_combine(const moe_shape *s, const float *ye, const int32_t *slot_
     return MOE_OK;
 }
 
-moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x,
-                             const float *Wgp, const float *gate_bias,
-                             int32_t bias_token_stride, const void *W1p, const float *b1,
-                             const void *W2p, const float *b2, int32_t *expert_idx, float *gate,
-                             int32_t *counts, int32_t *offsets, int32_t *slot_of,
-                             int32_t *src_of, void *xe, float *ye, float *y, void *y_act,
-                             void *workspace, void *stream)
+}  // extern "C"
+
+namespace {
+
+// The layer call; pre != NULL (one chunk only) keeps the first GEMM's pre-activations.
+moe_status layer_forward(const moe_shape *s, int32_t n_chunks, const void *x,
+                         const float *Wgp, const float *gate_bias,
+                         int32_t bias_token_stride, const void *W1p, const float *b1,
+                         const void *W2p, const float *b2, int32_t *expert_idx, float *gate,
+                         int32_t *counts, int32_t *offsets, int32_t *slot_of,
+                         int32_t *src_of, void *xe, float *ye, void *pre, float *y, void *y_act,
+                         void *workspace, void *stream)
 {
     MOE_TRY(check_common(s));
     if (n_chunks < 1 || n_chunks > kMaxChunks) {
@@ -460,7 +466,7 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
 
     if (n_chunks == 1) {
         MOE_TIMED(kStageScatter, st, launch_scatter(*s, x, slot_of, xe, 0, s->T, st));
-        MOE_TRY(launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, 0, st));
+        MOE_TRY(launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, 0, st, pre));
         MOE_TIMED(kStageCombine, st,
                   launch_combine(*s, ye, slot_of, gate, y, y_act, 0, s->T, st));
         return MOE_OK;
@@ -492,6 +498,42 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
     MOE_TRY_HIP(hipEventRecord(r->unpacked, r->unpack));
     MOE_TRY_HIP(hipStreamWaitEvent(st, r->unpacked, 0));
     return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x,
+                             const float *Wgp, const float *gate_bias,
+                             int32_t bias_token_stride, const void *W1p, const float *b1,
+                             const void *W2p, const float *b2, int32_t *expert_idx, float *gate,
+                             int32_t *counts, int32_t *offsets, int32_t *slot_of,
+                             int32_t *src_of, void *xe, float *ye, float *y, void *y_act,
+                             void *workspace, void *stream)
+{
+    return layer_forward(s, n_chunks, x, Wgp, gate_bias, bias_token_stride, W1p, b1, W2p, b2,
+                         expert_idx, gate, counts, offsets, slot_of, src_of, xe, ye, nullptr, y,
+                         y_act, workspace, stream);
+}
+
+moe_status moe_layer_forward_keep(const moe_shape *s, const void *x, const float *Wgp,
+                                  const float *gate_bias, int32_t bias_token_stride,
+                                  const void *W1p, const float *b1, const void *W2p,
+                                  const float *b2, int32_t *expert_idx, float *gate,
+                                  int32_t *counts, int32_t *offsets, int32_t *slot_of,
+                                  int32_t *src_of, void *xe, float *ye, void *pre, float *y,
+                                  void *workspace, void *stream)
+{
+    MOE_TRY(check_common(s));
+    if (s->dtype != MOE_BF16) {
+        set_error("moe_layer_forward_keep: bf16 layers only");
+        return MOE_EUNSUPPORTED;
+    }
+    MOE_REQUIRE_PTR(pre);
+    return layer_forward(s, 1, x, Wgp, gate_bias, bias_token_stride, W1p, b1, W2p, b2, expert_idx,
+                         gate, counts, offsets, slot_of, src_of, xe, ye, pre, y, nullptr,
+                         workspace, stream);
 }
 
 }  // extern "C"

@@ -2,7 +2,8 @@
 // trains this layer and schedules its backward pass in Sec. 2.2 and Sec. 4).
 //
 //   combine_bwd      dye[slot] = g dy[t] (bf16), dgate = <ye[slot], dy[t]>
-//   gemm (rows)      P = xe W1 (recomputed; fp16) and Hb = act(P) (bf16)
+//   gemm (rows)      P = xe W1 (fp16) and Hb = act(P) (bf16), recomputed unless the forward
+//                    kept P (then Hb is formed while it is transposed)
 //   gemm (rows)      dP = (dye W2^T) * act'(P)                        (bf16)
 //   gemm (rows)      dxe = dP W1^T                                    (fp32)
 //   transposes       Hb, dye, xe, dP -> [columns][rows], each expert's rows padded to 64
@@ -341,6 +342,8 @@ __global__ void padded_offsets_kernel(const int32_t *__restrict__ offsets, int32
 // out[m][koff[e] + i] = in[offsets[e] + i][m] for i < rows of expert e, 0 for the padding;
 // one block per 64 padded rows x 64 columns, through LDS, 16 bytes per lane on both sides
 // (M is a multiple of 8).
+// ACT >= 0: `in` holds fp16 pre-activations and the copy is act(in) rounded to bf16.
+template <int ACT>
 __global__ __launch_bounds__(256) void transpose_rows_kernel(
     const uint16_t *__restrict__ in, uint16_t *__restrict__ out, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ koff, int E, int M, int lda)
@@ -362,8 +365,13 @@ __global__ __launch_bounds__(256) void transpose_rows_kernel(
             q = *reinterpret_cast<const u32x4 *>(in + static_cast<size_t>(r_base + rr) * M + m0 + c8);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            tile[c8 + 2 * i][rr] = static_cast<uint16_t>(q[i] & 0xFFFFu);
-            tile[c8 + 2 * i + 1][rr] = static_cast<uint16_t>(q[i] >> 16);
+            uint16_t lo = static_cast<uint16_t>(q[i] & 0xFFFFu), hi = static_cast<uint16_t>(q[i] >> 16);
+            if constexpr (ACT >= 0) {
+                lo = f32_to_bf16(act_value<ACT>(static_cast<float>(__builtin_bit_cast(_Float16, lo))));
+                hi = f32_to_bf16(act_value<ACT>(static_cast<float>(__builtin_bit_cast(_Float16, hi))));
+            }
+            tile[c8 + 2 * i][rr] = lo;
+            tile[c8 + 2 * i + 1][rr] = hi;
         }
     }
     __syncthreads();
@@ -641,8 +649,8 @@ moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, c
                       int bias_stride, const uint16_t *W1, const uint16_t *W2, const uint16_t *W1p,
                       const int32_t *expert_idx, const float *gate, const int32_t *offsets,
                       const int32_t *slot_of, const int32_t *src_of, const uint16_t *xe,
-                      const float *ye, const float *dy, float *dx, float *dWg, float *dW1,
-                      float *dW2, float *dgate, const BwdWorkspace &w, hipStream_t st)
+                      const float *ye, const _Float16 *pre, const float *dy, float *dx, float *dWg,
+                      float *dW1, float *dW2, float *dgate, const BwdWorkspace &w, hipStream_t st)
 {
     const int T = s.T, d = s.d_model, h = s.d_ff, E = s.E, k = s.k;
     const int R = static_cast<int>(moe_max_rows(&s));
@@ -653,11 +661,13 @@ moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, c
     hipLaunchKernelGGL(combine_bwd_kernel, dim3(ceil_div(T, 4)), dim3(256), 0, st, dy, ye, slot_of,
                        gate, w.dye, dgate, T, d, k, R);
     const GemmPlan &g0 = w.lists.gp[0], &g1 = w.lists.gp[1];
-    // P = xe W1 (fp16), Hb = act(P) (bf16)
-    launch_gemm<0, 1, ACT>(xe, W1p, w.Hb, w.P, w.lists.items[0], w.lists.nitems[0], nullptr, E, 0, h,
-                           d, g0.bn, g0.max_items, kStageBwdRecompute, st);
+    // P = xe W1 (fp16), Hb = act(P) (bf16) -- unless the forward kept P
+    _Float16 *P = pre != nullptr ? const_cast<_Float16 *>(pre) : w.P;
+    if (pre == nullptr)
+        launch_gemm<0, 1, ACT>(xe, W1p, w.Hb, w.P, w.lists.items[0], w.lists.nitems[0], nullptr, E, 0,
+                               h, d, g0.bn, g0.max_items, kStageBwdRecompute, st);
     // dP = (dye W2^T) * act'(P): W2 [E][h][d] is already "rows n = h, contraction d contiguous"
-    launch_gemm<0, 2, ACT>(w.dye, W2, w.dP, w.P, w.lists.items[0], w.lists.nitems[0], nullptr, E, 0,
+    launch_gemm<0, 2, ACT>(w.dye, W2, w.dP, P, w.lists.items[0], w.lists.nitems[0], nullptr, E, 0,
                            h, d, g0.bn, g0.max_items, kStageBwdDP, st);
     // dxe = dP W1^T: W1 [E][d][h] is "rows n = d, contraction h contiguous"
     launch_gemm<0, 0, ACT>(w.dP, W1, w.dxe, nullptr, w.lists.items[1], w.lists.nitems[1], nullptr, E,
@@ -665,13 +675,17 @@ moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, c
     // transposed, per-expert zero-padded copies for the weight gradients
     const dim3 tb(256);
     const int kblocks = w.lda / 64;
-    hipLaunchKernelGGL(transpose_rows_kernel, dim3(kblocks, ceil_div(h, 64)), tb, 0, st, w.Hb, w.HT,
+    if (pre != nullptr)   // act(P) is formed on the way
+        hipLaunchKernelGGL(transpose_rows_kernel<ACT>, dim3(kblocks, ceil_div(h, 64)), tb, 0, st,
+                           reinterpret_cast<const uint16_t *>(pre), w.HT, offsets, w.koff, E, h, w.lda);
+    else
+        hipLaunchKernelGGL(transpose_rows_kernel<-1>, dim3(kblocks, ceil_div(h, 64)), tb, 0, st, w.Hb,
+                           w.HT, offsets, w.koff, E, h, w.lda);
+    hipLaunchKernelGGL(transpose_rows_kernel<-1>, dim3(kblocks, ceil_div(h, 64)), tb, 0, st, w.dP, w.dPT,
                        offsets, w.koff, E, h, w.lda);
-    hipLaunchKernelGGL(transpose_rows_kernel, dim3(kblocks, ceil_div(h, 64)), tb, 0, st, w.dP, w.dPT,
-                       offsets, w.koff, E, h, w.lda);
-    hipLaunchKernelGGL(transpose_rows_kernel, dim3(kblocks, ceil_div(d, 64)), tb, 0, st, w.dye, w.dyeT,
-                       offsets, w.koff, E, d, w.lda);
-    hipLaunchKernelGGL(transpose_rows_kernel, dim3(kblocks, ceil_div(d, 64)), tb, 0, st, xe, w.xeT,
+    hipLaunchKernelGGL(transpose_rows_kernel<-1>, dim3(kblocks, ceil_div(d, 64)), tb, 0, st, w.dye,
+                       w.dyeT, offsets, w.koff, E, d, w.lda);
+    hipLaunchKernelGGL(transpose_rows_kernel<-1>, dim3(kblocks, ceil_div(d, 64)), tb, 0, st, xe, w.xeT,
                        offsets, w.koff, E, d, w.lda);
     // dW2[e] [h][d] = Hb^T dye ; dW1[e] [d][h] = xe^T dP
     launch_gemm<1, 0, ACT>(w.HT, w.dyeT, dW2, nullptr, nullptr, nullptr, w.koff, E, h, d, w.lda, 128,
@@ -720,8 +734,8 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
                               const int32_t *expert_idx, const float *gate,
                               const int32_t *offsets, const int32_t *slot_of,
                               const int32_t *src_of, const void *xe, const float *ye,
-                              const float *dy, float *dx, float *dWg, float *dW1, float *dW2,
-                              float *dgate, void *workspace, void *stream)
+                              const void *pre, const float *dy, float *dx, float *dWg, float *dW1,
+                              float *dW2, float *dgate, void *workspace, void *stream)
 {
     if (!supported(s)) {
         set_error("moe_layer_backward: bf16 layers without top-k renormalisation only, E <= %d, "
@@ -740,9 +754,14 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
             return MOE_EINVAL;
         }
     }
+    if ((reinterpret_cast<uintptr_t>(pre) & 15u) != 0) {
+        set_error("moe_layer_backward: pre is not 16-byte aligned");
+        return MOE_EINVAL;
+    }
     BwdWorkspace w;
     layout_bwd(*s, workspace, &w);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const _Float16 *preh = static_cast<const _Float16 *>(pre);
     const uint16_t *xb = static_cast<const uint16_t *>(x);
     const float *Wgf = static_cast<const float *>(Wgp);
     const uint16_t *W1b = static_cast<const uint16_t *>(W1), *W2b = static_cast<const uint16_t *>(W2);
@@ -750,8 +769,8 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
 #define MOE_BWD_CASE(ACT)                                                                         \
     case ACT:                                                                                     \
         return backward_t<ACT>(*s, xb, Wgf, gate_bias, bias_token_stride, W1b, W2b, W1pb,         \
-                               expert_idx, gate, offsets, slot_of, src_of, xeb, ye, dy, dx, dWg,  \
-                               dW1, dW2, dgate, w, st);
+                               expert_idx, gate, offsets, slot_of, src_of, xeb, ye, preh, dy, dx, \
+                               dWg, dW1, dW2, dgate, w, st);
     switch (s->act) {
         MOE_BWD_CASE(MOE_ACT_GELU_ERF)
         MOE_BWD_CASE(MOE_ACT_GELU_TANH)

@@ -112,9 +112,10 @@ moe_status launch_scatter(const moe_shape &s, const void *x, const int32_t *slot
 moe_status launch_combine(const moe_shape &s, const float *ye, const int32_t *slot_of,
                           const float *gate, float *y, void *y_act, int t0, int t1,
                           hipStream_t st);
+// pre: NULL, or fp16 [rows, d_ff] receiving the pre-activations of the first GEMM (bf16 layers)
 moe_status launch_ffn(const moe_shape &s, const void *xe, const void *W1p,
                       const float *b1, const void *W2p, const float *b2, float *ye,
-                      const Workspace &w, int chunk, hipStream_t st);
+                      const Workspace &w, int chunk, hipStream_t st, void *pre = nullptr);
 moe_status launch_pack(const moe_shape &s, const void *W1, const void *W2, void *W1p,
                        void *W2p, hipStream_t st);
 

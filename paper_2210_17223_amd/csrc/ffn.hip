@@ -163,12 +163,14 @@ __device__ __forceinline__ void store4(_Float16 *p, const float (&v)[4])
 // fragments.  The work list (one entry per output tile) is ordered so that each XCD
 // walks a contiguous share of it: neighbouring blocks then reuse operand tiles in that
 // XCD's L2.  32-row sub-tiles past the end of a ragged row tile are skipped.
-template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN, bool KTAIL>
+// KEEP: the pre-activation values (accumulator + bias) also go to Pre [rows, N] as fp16, for
+// the backward pass.
+template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN, bool KTAIL, bool KEEP>
 // (two wavefronts per SIMD in every shape: two 4-wavefront blocks or one 8-wavefront block)
 __global__ __launch_bounds__(64 * WM * WN, 2) void grouped_gemm_mfma_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W,
-    const float *__restrict__ bias, TOut *__restrict__ C, const WorkItem *__restrict__ items,
-    const int32_t *__restrict__ nitems, int N, int K)
+    const float *__restrict__ bias, TOut *__restrict__ C, _Float16 *__restrict__ Pre,
+    const WorkItem *__restrict__ items, const int32_t *__restrict__ nitems, int N, int K)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64, LD = BK + 8;
     constexpr int NT = 64 * WM * WN;
@@ -342,13 +344,15 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void grouped_gemm_mfma_kernel(
             for (int g = 0; g < 4; ++g) {
                 const int n = n0 + (wn * TN + i) * 32 + 8 * g + 4 * (lane >> 5);
                 if (n >= N) continue;
-                float v[4];
+                float v[4], pre[4];
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     float s = acc[i][j][4 * g + c];
                     if (bexp != nullptr) s += bexp[n + c];
+                    pre[c] = s;
                     v[c] = activate<ACT, true>(s);
                 }
+                if constexpr (KEEP) store4(Pre + static_cast<size_t>(r) * N + n, pre);
                 store4(C + static_cast<size_t>(r) * N + n, v);
             }
         }
@@ -404,14 +408,14 @@ void launch_f32_pair(const moe_shape &s, const float *xe, const float *W1, const
     prof_end(kStageGemm2, st);
 }
 
-template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN, bool KTAIL>
+template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN, bool KTAIL, bool KEEP>
 void launch_mfma_cfg_k(const uint16_t *A, const uint16_t *W, const float *bias, TOut *C,
-                     const WorkItem *items, const int32_t *nitems, int max_items, int N, int K,
-                     int stage, hipStream_t st)
+                     _Float16 *pre, const WorkItem *items, const int32_t *nitems, int max_items,
+                     int N, int K, int stage, hipStream_t st)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t lds = 2 * (BM + BN) * (64 + 8) * sizeof(uint16_t);
-    auto kern = grouped_gemm_mfma_kernel<F16, TOut, ACT, WM, WN, TM, TN, KTAIL>;
+    auto kern = grouped_gemm_mfma_kernel<F16, TOut, ACT, WM, WN, TM, TN, KTAIL, KEEP>;
     static PerDeviceOnce once;   // raising the dynamic LDS limit: once per kernel and device
     if (once.first()) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -421,52 +425,62 @@ void launch_mfma_cfg_k(const uint16_t *A, const uint16_t *W, const float *bias, 
     hipEvent_t t0, t1;
     prof_kernel_events(stage, &t0, &t1);
     hipExtLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, st, t0, t1, 0, A, W, bias, C,
-                          items, nitems, N, K);
+                          pre, items, nitems, N, K);
 }
 
 // The contraction depth is a multiple of the 64-deep stage in every benchmark shape;
 // other depths take a variant that zero-fills the last stage.
-template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN>
+template <bool F16, typename TOut, int ACT, bool KEEP, int WM, int WN, int TM, int TN>
 void launch_mfma_cfg(const uint16_t *A, const uint16_t *W, const float *bias, TOut *C,
-                     const WorkItem *items, const int32_t *nitems, int max_items, int N, int K,
-                     int stage, hipStream_t st)
+                     _Float16 *pre, const WorkItem *items, const int32_t *nitems, int max_items,
+                     int N, int K, int stage, hipStream_t st)
 {
     if (K % 64 == 0)
-        launch_mfma_cfg_k<F16, TOut, ACT, WM, WN, TM, TN, false>(A, W, bias, C, items, nitems,
-                                                                 max_items, N, K, stage, st);
+        launch_mfma_cfg_k<F16, TOut, ACT, WM, WN, TM, TN, false, KEEP>(
+            A, W, bias, C, pre, items, nitems, max_items, N, K, stage, st);
     else
-        launch_mfma_cfg_k<F16, TOut, ACT, WM, WN, TM, TN, true>(A, W, bias, C, items, nitems,
-                                                                max_items, N, K, stage, st);
+        launch_mfma_cfg_k<F16, TOut, ACT, WM, WN, TM, TN, true, KEEP>(
+            A, W, bias, C, pre, items, nitems, max_items, N, K, stage, st);
 }
 
-template <bool F16, typename TOut, int ACT>
+template <bool F16, typename TOut, int ACT, bool KEEP>
 void launch_mfma(const GemmPlan &gp, const uint16_t *A, const uint16_t *W, const float *bias,
-                 TOut *C, const WorkItem *items, const int32_t *nitems, int N, int K,
+                 TOut *C, _Float16 *pre, const WorkItem *items, const int32_t *nitems, int N, int K,
                  int stage, hipStream_t st)
 {
+#define MOE_MFMA_SHAPE(WM_, WN_, TM_, TN_)                                                        \
+    launch_mfma_cfg<F16, TOut, ACT, KEEP, WM_, WN_, TM_, TN_>(A, W, bias, C, pre, items, nitems,    \
+                                                              gp.max_items, N, K, stage, st)
     if (gp.bm == 256)
-        launch_mfma_cfg<F16, TOut, ACT, 2, 4, 4, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, stage, st);
+        MOE_MFMA_SHAPE(2, 4, 4, 2);
     else if (gp.bm == 64)
-        launch_mfma_cfg<F16, TOut, ACT, 1, 8, 2, 1>(A, W, bias, C, items, nitems, gp.max_items, N, K, stage, st);
+        MOE_MFMA_SHAPE(1, 8, 2, 1);
     else if (gp.bn == 256)
-        launch_mfma_cfg<F16, TOut, ACT, 2, 4, 2, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, stage, st);
+        MOE_MFMA_SHAPE(2, 4, 2, 2);
     else
-        launch_mfma_cfg<F16, TOut, ACT, 2, 2, 2, 2>(A, W, bias, C, items, nitems, gp.max_items, N, K, stage, st);
+        MOE_MFMA_SHAPE(2, 2, 2, 2);
+#undef MOE_MFMA_SHAPE
 }
 
 template <int ACT>
 void launch_mfma_pair(const moe_shape &s, const uint16_t *xe, const uint16_t *W1p,
                       const float *b1, const uint16_t *W2p, const float *b2, float *ye,
-                      const Workspace &w, int chunk, hipStream_t st)
+                      _Float16 *pre, const Workspace &w, int chunk, hipStream_t st)
 {
     _Float16 *H = static_cast<_Float16 *>(w.hidden);
     const WorkItem *it1 = w.items[0] + static_cast<size_t>(chunk) * w.gp[0].max_items;
     const WorkItem *it2 = w.items[1] + static_cast<size_t>(chunk) * w.gp[1].max_items;
-    launch_mfma<false, _Float16, ACT>(w.gp[0], xe, W1p, b1, H, it1, w.nitems[0] + chunk, s.d_ff,
-                                      s.d_model, kStageGemm1, st);
-    launch_mfma<true, float, MOE_ACT_IDENTITY>(w.gp[1], reinterpret_cast<const uint16_t *>(H), W2p,
-                                               b2, ye, it2, w.nitems[1] + chunk, s.d_model,
-                                               s.d_ff, kStageGemm2, st);
+    if (pre != nullptr)
+        launch_mfma<false, _Float16, ACT, true>(w.gp[0], xe, W1p, b1, H, pre, it1,
+                                                w.nitems[0] + chunk, s.d_ff, s.d_model,
+                                                kStageGemm1, st);
+    else
+        launch_mfma<false, _Float16, ACT, false>(w.gp[0], xe, W1p, b1, H, nullptr, it1,
+                                                 w.nitems[0] + chunk, s.d_ff, s.d_model,
+                                                 kStageGemm1, st);
+    launch_mfma<true, float, MOE_ACT_IDENTITY, false>(w.gp[1], reinterpret_cast<const uint16_t *>(H),
+                                                      W2p, b2, ye, nullptr, it2, w.nitems[1] + chunk,
+                                                      s.d_model, s.d_ff, kStageGemm2, st);
 }
 
 }  // namespace
@@ -509,14 +523,19 @@ GemmPlan choose_gemm_plan(const moe_shape &s, int which, int n_chunks)
 
 moe_status launch_ffn(const moe_shape &s, const void *xe, const void *W1p, const float *b1,
                       const void *W2p, const float *b2, float *ye, const Workspace &w,
-                      int chunk, hipStream_t st)
+                      int chunk, hipStream_t st, void *pre)
 {
+    if (pre != nullptr && s.dtype != MOE_BF16) {
+        set_error("the pre-activations are kept for bf16 layers only");
+        return MOE_EUNSUPPORTED;
+    }
 #define MOE_FFN_CASE(ACT)                                                                      \
     case ACT:                                                                                  \
         if (s.dtype == MOE_BF16)                                                               \
             launch_mfma_pair<ACT>(s, static_cast<const uint16_t *>(xe),                         \
                                   static_cast<const uint16_t *>(W1p), b1,                       \
-                                  static_cast<const uint16_t *>(W2p), b2, ye, w, chunk, st);    \
+                                  static_cast<const uint16_t *>(W2p), b2, ye,                   \
+                                  static_cast<_Float16 *>(pre), w, chunk, st);                  \
         else                                                                                   \
             launch_f32_pair<ACT>(s, static_cast<const float *>(xe),                             \
                                  static_cast<const float *>(W1p), b1,                           \

@@ -5,7 +5,8 @@ import ctypes as C
 
 import torch
 
-from .binding import MoeError, Shape, _check, _ptr, _stream, lib, moe_max_rows
+from .binding import (MoeError, Shape, _check, _ptr, _stream, lib, moe_max_rows,
+                      moe_workspace_bytes)
 
 _ready = False
 
@@ -18,7 +19,9 @@ def _lib():
         L.moe_backward_workspace_bytes.restype = C.c_size_t
         L.moe_backward_workspace_bytes.argtypes = [sp]
         L.moe_layer_backward.restype = C.c_int
-        L.moe_layer_backward.argtypes = [sp, vp, vp, vp, i32] + [vp] * 18
+        L.moe_layer_backward.argtypes = [sp, vp, vp, vp, i32] + [vp] * 19
+        L.moe_layer_forward_keep.restype = C.c_int
+        L.moe_layer_forward_keep.argtypes = [sp, vp, vp, vp, i32] + [vp] * 16
         _ready = True
     return L
 
@@ -32,8 +35,32 @@ def _need(t: torch.Tensor, dtype, numel: int, name: str) -> None:
         raise MoeError(f"{name}: need {numel} elements of {dtype}, got {t.numel()} of {t.dtype}")
 
 
+def moe_layer_forward_keep(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1p, b1, W2p, b2, expert_idx,
+                           gate, counts, offsets, slot_of, src_of, xe, ye, pre, y, workspace,
+                           stream=None) -> None:
+    rows = moe_max_rows(s)
+    T, d, E, h, k = s.T, s.d_model, s.E, s.d_ff, s.k
+    _need(x, torch.bfloat16, T * d, "x")
+    _need(expert_idx, torch.int32, T * k, "expert_idx")
+    _need(gate, torch.float32, T * k, "gate")
+    _need(counts, torch.int32, E, "counts")
+    _need(offsets, torch.int32, E + 1, "offsets")
+    _need(slot_of, torch.int32, T * k, "slot_of")
+    _need(src_of, torch.int32, rows, "src_of")
+    _need(xe, torch.bfloat16, rows * d, "xe")
+    _need(ye, torch.float32, rows * d, "ye")
+    _need(pre, torch.float16, rows * h, "pre")
+    _need(y, torch.float32, T * d, "y")
+    _need(workspace, torch.uint8, moe_workspace_bytes(s, 1), "workspace")
+    _check(_lib().moe_layer_forward_keep(C.byref(s), _ptr(x), _ptr(Wgp), _ptr(gate_bias),
+                                         bias_token_stride, _ptr(W1p), _ptr(b1), _ptr(W2p), _ptr(b2),
+                                         _ptr(expert_idx), _ptr(gate), _ptr(counts), _ptr(offsets),
+                                         _ptr(slot_of), _ptr(src_of), _ptr(xe), _ptr(ye), _ptr(pre),
+                                         _ptr(y), _ptr(workspace), _stream(stream)))
+
+
 def moe_layer_backward(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1, W2, W1p, expert_idx, gate,
-                       offsets, slot_of, src_of, xe, ye, dy, dx, dWg, dW1, dW2, dgate, workspace,
+                       offsets, slot_of, src_of, xe, ye, pre, dy, dx, dWg, dW1, dW2, dgate, workspace,
                        stream=None) -> None:
     rows = moe_max_rows(s)
     T, d, E, h, k = s.T, s.d_model, s.E, s.d_ff, s.k
@@ -47,6 +74,8 @@ def moe_layer_backward(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1, W2, W
     _need(src_of, torch.int32, rows, "src_of")
     _need(xe, torch.bfloat16, rows * d, "xe")
     _need(ye, torch.float32, rows * d, "ye")
+    if pre is not None:
+        _need(pre, torch.float16, rows * h, "pre")
     _need(dy, torch.float32, T * d, "dy")
     _need(dx, torch.float32, T * d, "dx")
     _need(dWg, torch.float32, d * E, "dWg")
@@ -57,5 +86,5 @@ def moe_layer_backward(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1, W2, W
     _check(_lib().moe_layer_backward(C.byref(s), _ptr(x), _ptr(Wgp), _ptr(gate_bias), bias_token_stride,
                                      _ptr(W1), _ptr(W2), _ptr(W1p), _ptr(expert_idx), _ptr(gate),
                                      _ptr(offsets), _ptr(slot_of), _ptr(src_of), _ptr(xe), _ptr(ye),
-                                     _ptr(dy), _ptr(dx), _ptr(dWg), _ptr(dW1), _ptr(dW2), _ptr(dgate),
+                                     _ptr(pre), _ptr(dy), _ptr(dx), _ptr(dWg), _ptr(dW1), _ptr(dW2), _ptr(dgate),
                                      _ptr(workspace), _stream(stream)))

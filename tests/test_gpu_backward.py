@@ -26,11 +26,35 @@ CASES = {
 }
 
 
-def run_backward(li, act="gelu"):
+def run_backward(li, act="gelu", keep=False):
+    """keep: the forward is moe_layer_forward_keep and hands its pre-activations to the
+    backward pass; else the plain layer call, and the backward pass computes them again."""
     s = shape_of(li, act=act)
     L = DeviceLayer(li, s)
     L.layer(1)
     b = L.b
+    pre = None
+    if keep:
+        plain = {n: b[n].clone() for n in ("expert_idx", "gate", "counts", "offsets", "slot_of", "y")}
+        A = int(b["offsets"][-1])
+        plain["src_of"], plain["ye"] = b["src_of"][:A].clone(), b["ye"][:A * li.d].clone()
+        for n in ("expert_idx", "gate", "counts", "offsets", "slot_of", "src_of", "y", "ye"):
+            b[n].fill_(-3)
+        pre = torch.full((moe.moe_max_rows(s) * li.h,), 9.0, dtype=torch.float16, device=DEV)
+        moe.moe_layer_forward_keep(s, L.x, b["Wgp"], L.bias, L.bias_stride, b["W1p"], None, b["W2p"], None,
+                                   b["expert_idx"], b["gate"], b["counts"], b["offsets"], b["slot_of"],
+                                   b["src_of"], b["xe"], b["ye"], pre, b["y"], b["workspace"])
+        torch.cuda.synchronize()
+        # same outputs as the plain layer call, bit for bit
+        for n, want in plain.items():
+            got = b[n][:want.numel()]
+            assert torch.equal(got.view(torch.int32), want.view(torch.int32)), n
+        # kept pre-activations: fp16 roundings of xe W1 (bf16 products, fp32 accumulation)
+        o_pre = _oracle_pre(li, b, A)
+        got_pre = pre[:A * li.h].float().cpu().numpy().reshape(A, li.h)
+        rms = float(np.sqrt(np.mean(o_pre ** 2)))
+        assert np.abs(got_pre - o_pre).max() <= 2.0 ** -10 * np.abs(o_pre).max() + 1e-4 * rms
+        assert (pre[A * li.h:] == 9.0).all()              # rows beyond offsets[E] untouched
     prng = np.random.Generator(np.random.PCG64(77))
     dy = prng.standard_normal((li.T, li.d)).astype(np.float32)
     W1, W2 = upload(li.W1, "bf16"), upload(li.W2, "bf16")
@@ -39,7 +63,7 @@ def run_backward(li, act="gelu"):
              dW2=f32(li.E * li.d * li.h), dgate=f32(li.T * li.k))
     ws = torch.empty(moe.moe_backward_workspace_bytes(s), dtype=torch.uint8, device=DEV)
     moe.moe_layer_backward(s, L.x, b["Wgp"], L.bias, L.bias_stride, W1, W2, b["W1p"], b["expert_idx"],
-                           b["gate"], b["offsets"], b["slot_of"], b["src_of"], b["xe"], b["ye"],
+                           b["gate"], b["offsets"], b["slot_of"], b["src_of"], b["xe"], b["ye"], pre,
                            torch.from_numpy(dy).to(DEV), g["dx"], g["dWg"], g["dW1"], g["dW2"],
                            g["dgate"], ws)
     torch.cuda.synchronize()
@@ -49,10 +73,22 @@ def run_backward(li, act="gelu"):
     return {n: t.cpu().numpy() for n, t in g.items()}, o
 
 
+def _oracle_pre(li, b, A):
+    """xe W1 per expert in fp64 from the host inputs and the (already checked) plan."""
+    off = b["offsets"].cpu().numpy()
+    tok = b["src_of"][:A].cpu().numpy() // li.k
+    xe = li.x.astype(np.float64)[tok]
+    P = np.empty((A, li.h))
+    for e in range(li.E):
+        P[off[e]:off[e + 1]] = xe[off[e]:off[e + 1]] @ li.W1[e].astype(np.float64)
+    return P
+
+
+@pytest.mark.parametrize("keep", [False, True], ids=["recompute", "keep"])
 @pytest.mark.parametrize("name", list(CASES))
-def test_backward_matches_the_oracle(name):
+def test_backward_matches_the_oracle(name, keep):
     li = wl.make_layer(CASES[name], seed=0)
-    got, o = run_backward(li)
+    got, o = run_backward(li, keep=keep)
     T, d, E, h, k = li.T, li.d, li.E, li.h, li.k
     assert rel_rms_err(got["dgate"].reshape(T, k), o.dgate) <= 5e-3
     assert rel_rms_err(got["dx"].reshape(T, d), o.dx) <= TOL
@@ -80,7 +116,7 @@ def test_backward_matches_the_oracle(name):
 @pytest.mark.parametrize("act", ["relu", "gelu_tanh", "identity"])
 def test_backward_other_activations(act):
     li = wl.make_layer(wl.scaled("gpt2s_moe", T=400, d=128, h=256, E=4), seed=3)
-    got, o = run_backward(li, act=act)
+    got, o = run_backward(li, act=act, keep=act != "relu")
     for n, shape in (("dx", (li.T, li.d)), ("dWg", (li.d, li.E)), ("dW1", li.W1.shape), ("dW2", li.W2.shape)):
         assert rel_rms_err(got[n].reshape(shape), getattr(o, n)) <= TOL, n
 
