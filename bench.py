@@ -41,6 +41,14 @@ def main() -> int:
                     help="one of workloads.CONFIGS (default: the configuration the metric is quoted on), "
                          "or 'popularity': the inference scheduler's estimate + two-phase decision")
     ap.add_argument("--chunks", type=int, default=1, help="n_chunks of moe_layer_chunked")
+    ap.add_argument("--comm", action="store_true",
+                    help="the workload's layer in the padded equal-split layout with both all-to-alls "
+                         "on the stand-in link (moe_layer_padded), alone and while a gradient "
+                         "allreduce competes for the link under both scheduling policies")
+    ap.add_argument("--link-blocks", type=int, default=32,
+                    help="workgroups of the stand-in link's copy kernel (its rate)")
+    ap.add_argument("--micro-mib", type=int, default=16,
+                    help="with --comm: size of an allreduce micro-op in MiB")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true",
                     help="after the timed region, run extra steps with every stage timed")
@@ -89,6 +97,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.workload == "popularity":
         return bench_popularity(args, moe, np, torch, dev)
+    if args.comm:
+        return bench_comm(args, moe, wl, np, torch, dev)
     cfg = wl.CONFIGS[args.workload]
     n_layers = cfg["layers"]
     host = wl.make_stack(cfg, seed=0, threads=16) if n_layers > 1 else [wl.make_layer(cfg, seed=0, threads=16)]
@@ -374,6 +384,155 @@ def main() -> int:
                                "sample": f"{passes} pass(es) over {n_layers} layer(s): gate+plan over all "
                                          f"{l0.T} tokens, expert FFN+combine for the first {sample} "
                                          f"tokens, {elapsed:.2f} s wall"}
+    print(json.dumps(out))
+    return 0
+
+
+def bench_comm(args, moe, wl, np, torch, dev) -> int:
+    """Sec. 4.2 / 6.1 on one GPU.  (a) The layer in the padded layout with both all-to-alls cut
+    into n micro-ops on the library's own stand-in link, FFN pipelined behind each micro-op:
+    time per layer for n = 1, 2, 4, 8.  (b) The same layer through the scheduler while the
+    gradient of its expert weights (E*d*h fp32) is being "allreduced" over the same link:
+    uncut and in arrival order, against cut into micro-ops with all-to-all priority.
+    A step of the headline figure is (b)'s prioritised case: layer + allreduce together."""
+    from paper_2210_17223_amd import comm
+    cfg = wl.CONFIGS[args.workload]
+    if cfg["layers"] != 1:
+        print("bench.py: --comm takes a one-layer workload", file=sys.stderr)
+        return 2
+    li = wl.make_layer(cfg, seed=0, threads=16)
+    bf16 = li.dtype == "bf16"
+    s = moe.Shape.make(li.T, li.d, li.E, li.h, li.k, li.C, dtype="bf16" if bf16 else "f32", act="gelu")
+    esz = 2 if bf16 else 4
+
+    def up(a):
+        if bf16:
+            return torch.from_numpy(wl.bf16_bits(a).view(np.int16).reshape(a.shape)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    b = moe.alloc_buffers(s, 1, dev)
+    x = up(li.x)
+    bias = None if li.gate_bias is None else torch.from_numpy(li.gate_bias).to(dev)
+    moe.moe_pack_gate(s, up(li.Wg), b["Wgp"])
+    moe.moe_pack_weights(s, up(li.W1), up(li.W2), b["W1p"], b["W2p"])
+    slots = li.E * li.C
+    i32 = lambda n: torch.empty(n, dtype=torch.int32, device=dev)
+    p = dict(expert_idx=i32(li.T * li.k), gate=torch.empty(li.T * li.k, device=dev), counts=i32(li.E),
+             slot_of=i32(li.T * li.k), src_of=i32(slots),
+             xs=torch.empty(slots * li.d, dtype=s.torch_dtype, device=dev),
+             xr=torch.empty(slots * li.d, dtype=s.torch_dtype, device=dev),
+             ys=torch.zeros(slots * li.d, device=dev), yr=torch.zeros(slots * li.d, device=dev),
+             y=torch.empty(li.T * li.d, device=dev))
+    ws = {n: torch.empty(moe.moe_padded_workspace_bytes(s, n), dtype=torch.uint8, device=dev) for n in (1, 2, 4, 8)}
+
+    def padded(n, link=None):
+        moe.moe_layer_padded(s, n, link, args.link_blocks, x, b["Wgp"], bias, li.bias_token_stride, b["W1p"],
+                             None, b["W2p"], None, p["expert_idx"], p["gate"], p["counts"], p["slot_of"],
+                             p["src_of"], p["xs"], p["xr"], p["ys"], p["yr"], p["y"], ws[n])
+
+    def compact():
+        moe.moe_layer_chunked(s, 1, x, b["Wgp"], bias, li.bias_token_stride, b["W1p"], None, b["W2p"], None,
+                              b["expert_idx"], b["gate"], b["counts"], b["offsets"], b["slot_of"], b["src_of"],
+                              b["xe"], b["ye"], b["y"], None, b["workspace"])
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    a2a_bytes = slots * li.d * (esz + 4)                      # both all-to-alls of one layer
+    res = {"compact_layer_ms": timed(compact, args.steps, args.warmup)}
+    for n in (1, 2, 4, 8):
+        res[f"padded_own_link_n{n}_ms"] = timed(lambda: padded(n), args.steps, args.warmup)
+    assert torch.equal(p["y"].view(torch.int32), b["y"].view(torch.int32)), "padded y differs from the compact layer's"
+
+    # the link alone: one all-to-all's worth of bytes as a single micro-op, timed on the device
+    c = comm.moe_comm_create(comm.PRIORITY, args.link_blocks, 2)
+    link_ms = []
+    for i in range(6):
+        op = comm.moe_comm_submit(c, comm.ALL_TO_ALL, p["ys"], p["yr"], li.E, li.C, li.d * 4, 1)
+        comm.moe_comm_post(c, op, 0, 1)
+        link_ms.append(comm.moe_comm_finish(c, op))
+    comm.moe_comm_destroy(c)
+    link_gbps = slots * li.d * 4 / (min(link_ms[1:]) * 1e-3) / 1e9
+    res["link_GBps"] = link_gbps
+
+    # (b) contention: the layer through a scheduler that also carries a gradient allreduce
+    grad = torch.randn(li.E * li.d * li.h, device=dev)
+    gout = torch.empty_like(grad)
+    grad_bytes = grad.numel() * 4
+    micro_bytes = args.micro_mib << 20
+    steps_b = max(5, min(args.steps, 30))
+
+    def contended(policy, n_ar, n_micro, with_ar=True):
+        c = comm.moe_comm_create(policy, args.link_blocks, 2)
+        try:
+            padded(n_micro, c)                                # first use: code load
+            torch.cuda.synchronize()
+            layer_ms, ar_ms = [], []
+            for _ in range(steps_b):
+                torch.cuda.synchronize()
+                ar = None
+                if with_ar:
+                    ar = comm.moe_comm_submit(c, comm.ALLREDUCE, grad, gout, 1, grad.numel() // 4, 16, n_ar)
+                    comm.moe_comm_post(c, ar, 0, n_ar)
+                t0 = time.perf_counter()
+                padded(n_micro, c)
+                torch.cuda.synchronize()
+                layer_ms.append((time.perf_counter() - t0) * 1e3)
+                if ar is not None:
+                    ar_ms.append(comm.moe_comm_finish(c, ar))
+            return float(np.median(layer_ms)), (float(np.median(ar_ms)) if ar_ms else None)
+        finally:
+            comm.moe_comm_destroy(c)
+
+    n_ar = (grad_bytes + micro_bytes - 1) // micro_bytes
+    alone, _ = contended(comm.PRIORITY, 1, 4, with_ar=False)
+    fifo, ar_fifo = contended(comm.ARRIVAL_ORDER, 1, 4)
+    prio, ar_prio = contended(comm.PRIORITY, n_ar, 4)
+    assert torch.equal(gout, grad)
+    assert torch.equal(p["y"].view(torch.int32), b["y"].view(torch.int32))
+    res.update({"scheduled_layer_alone_ms": alone, "scheduled_layer_behind_uncut_allreduce_ms": fifo,
+                "scheduled_layer_prioritised_ms": prio, "allreduce_uncut_ms": ar_fifo,
+                "allreduce_micro_ops_ms": ar_prio, "allreduce_bytes": grad_bytes,
+                "allreduce_micro_ops": int(n_ar), "all_to_all_bytes_per_layer": a2a_bytes,
+                "layer_slowdown_arrival_order": fifo / alone, "layer_slowdown_priority": prio / alone})
+    out = {"metric": "moe_padded_layer_with_allreduce_tokens_per_s", "value": li.T / (prio * 1e-3),
+           "unit": "tokens/s", "n_gpus": 1, "steps": steps_b, "warmup": 1, "ms_per_step": prio,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+           "config": {"workload": f"{args.workload}: T={li.T} d_model={li.d} E={li.E} d_ff={li.h} k={li.k} "
+                                  f"capacity={li.C} {li.dtype}, seed 0; padded layout, 4 micro-ops per all-to-all, "
+                                  f"stand-in link of {args.link_blocks} workgroups, {grad_bytes >> 20} MiB allreduce "
+                                  f"in {int(n_ar)} micro-ops competing"},
+           "roofline": {"bound": "hbm", "kernel": "link_copy_kernel (the stand-in link, one all-to-all's bytes)",
+                        "achieved": 2 * link_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                        "frac": 2 * link_gbps / PEAK_HBM_GBPS, "traffic": None,
+                        "avg_launch_us": min(link_ms[1:]) * 1e3, "algorithmic_bytes": 2 * slots * li.d * 4,
+                        "note": "read + write of every byte; the kernel is confined to link_blocks workgroups "
+                                "on purpose (it stands for a network link), so the fraction is a setting, "
+                                "not an achievement"},
+           "comm": res}
+    if not args.no_cpu_baseline:
+        from oracle import comm_oracle as co
+        from oracle import moe_oracle as fo
+        c0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - c0 < 10.0:
+            o = fo.moe_layer(li.x, li.Wg, li.W1, li.W2, k=li.k, capacity=li.C, bias=li.gate_bias,
+                             bias_stride=li.bias_token_stride)
+            _, _, src = co.padded_plan(o.expert_idx, li.E, li.C)
+            co.pack_padded(li.x, src, li.k)
+            n += 1
+        el = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": li.T * n / el, "unit": "tokens/s", "cores": fo.threads(), "kind": "oracle",
+                               "sample": f"{n} pass(es) of the oracle layer plus the padded plan and pack over all "
+                                         f"{li.T} tokens, {el:.2f} s wall"}
     print(json.dumps(out))
     return 0
 

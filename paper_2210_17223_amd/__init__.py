@@ -1,7 +1,7 @@
 """MI355X-native one-GPU MoE-layer forward (libmoe) and its thin Python binding.
 
 The HIP kernels live in csrc/ behind the C-ABI declared in include/moe.h and
-include/moe_sched.h, include/moe_train.h, include/moe_offload.h; this
+include/moe_sched.h, include/moe_train.h, include/moe_offload.h, include/moe_comm.h; this
 package only marshals arguments.  PyTorch is used for device memory and streams.
 """
 from .binding import (ACT, DTYPE, MoeError, Shape, alloc_buffers, lib, lib_path,
@@ -19,8 +19,10 @@ from .offload_binding import (moe_expert_ffn_offloaded, moe_offload_staging_byte
                               moe_offload_workspace_bytes)
 from .train_binding import (moe_backward_workspace_bytes, moe_layer_backward,
                             moe_layer_forward_keep)
+from . import comm_binding as comm
+from .comm_binding import moe_layer_padded, moe_padded_workspace_bytes
 
-__all__ = ["moe_expert_ffn_offloaded", "moe_offload_staging_bytes", "moe_offload_workspace_bytes",
+__all__ = ["comm", "moe_layer_padded", "moe_padded_workspace_bytes", "moe_expert_ffn_offloaded", "moe_offload_staging_bytes", "moe_offload_workspace_bytes",
            "moe_backward_workspace_bytes", "moe_layer_backward", "moe_layer_forward_keep", "PathShape", "moe_devices_for_expert", "moe_path_count", "moe_path_finalize",
            "moe_path_profile", "moe_popularity_estimate", "moe_schedule_experts",
            "moe_schedule_layer", "moe_top_lists_identical",

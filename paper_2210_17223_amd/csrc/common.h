@@ -99,9 +99,15 @@ moe_status launch_route(const moe_shape &s, const void *x, const void *Wg,
                         float *gate, int32_t *seg_cnt, hipStream_t st);
 // counted = the per-segment histogram is already in w.seg_cnt (launch_route made it);
 // n_chunks == 1 also builds the GEMM work lists (otherwise launch_items does, after the ranks)
+// padded: slot = e * capacity + rank (the equal-split layout) instead of offsets[e] + rank;
+// offsets still receives the compact scan, and no work lists are built
 moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *counts,
                        int32_t *offsets, int32_t *slot_of, int32_t *src_of,
-                       const Workspace &w, bool counted, int n_chunks, hipStream_t st);
+                       const Workspace &w, bool counted, int n_chunks, hipStream_t st,
+                       bool padded = false);
+// work lists of the padded layout, one per micro-op (slot positions [m*C/n, (m+1)*C/n))
+moe_status launch_items_padded(const moe_shape &s, int n_micro, const int32_t *counts,
+                               const Workspace &w, hipStream_t st);
 moe_status launch_items(const moe_shape &s, int n_chunks, const int32_t *offsets,
                         const int32_t *src_of, const Workspace &w, hipStream_t st);
 // w.items[g] / w.nitems[g] sized for E lists: list e = the output tiles of expert e alone
@@ -109,9 +115,10 @@ moe_status launch_items_per_expert(const moe_shape &s, const int32_t *offsets, c
                                    hipStream_t st);
 moe_status launch_scatter(const moe_shape &s, const void *x, const int32_t *slot_of,
                           void *xe, int t0, int t1, hipStream_t st);
+// rows: rows of ye (slots at or beyond it are never followed); < 0 = moe_max_rows
 moe_status launch_combine(const moe_shape &s, const float *ye, const int32_t *slot_of,
                           const float *gate, float *y, void *y_act, int t0, int t1,
-                          hipStream_t st);
+                          hipStream_t st, int64_t rows = -1);
 // pre: NULL, or fp16 [rows, d_ff] receiving the pre-activations of the first GEMM (bf16 layers)
 moe_status launch_ffn(const moe_shape &s, const void *xe, const void *W1p,
                       const float *b1, const void *W2p, const float *b2, float *ye,

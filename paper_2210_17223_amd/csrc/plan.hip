@@ -156,7 +156,7 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(
 __global__ __launch_bounds__(kPlanThreads) void plan_rank_kernel(
     const int32_t *__restrict__ expert_idx, const int32_t *__restrict__ seg_base,
     const int32_t *__restrict__ offsets, int32_t *__restrict__ slot_of,
-    int32_t *__restrict__ src_of, int n, int E, int capacity, int seg_len)
+    int32_t *__restrict__ src_of, int n, int E, int capacity, int seg_len, int padded)
 {
     __shared__ int32_t run[kPlanWaves][kMaxExperts];
     __shared__ int32_t off_s[kMaxExperts];
@@ -164,7 +164,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rank_kernel(
     const int wave = threadIdx.x / kWave;
     const int seg = blockIdx.x * kPlanWaves + wave;
     const int base = seg * seg_len;
-    if (threadIdx.x < kMaxExperts) off_s[threadIdx.x] = threadIdx.x < E ? offsets[threadIdx.x] : 0;
+    // padded layout: expert e owns the slots [e * capacity, (e + 1) * capacity)
+    if (threadIdx.x < kMaxExperts)
+        off_s[threadIdx.x] = threadIdx.x >= E ? 0 : padded ? threadIdx.x * capacity : offsets[threadIdx.x];
     run[wave][lane] = base < n ? seg_base[static_cast<size_t>(seg) * kMaxExperts + lane] : 0;
     __syncthreads();
     for (int off = 0; off < seg_len; off += kWave) {
@@ -310,7 +312,47 @@ __global__ __launch_bounds__(256) void plan_items_expert_kernel(
     build_items(gp, items, nitems, lo_s, hi_s, mt_s, cum_s, 0, 1);
 }
 
+// Work lists of the padded layout: micro-op m (blockIdx.x) covers, for every expert, the slot
+// positions [m*C/n, (m+1)*C/n) of its C slots; only those below min(count, C) hold rows.
+__global__ __launch_bounds__(256) void plan_items_padded_kernel(
+    const int32_t *__restrict__ counts, WorkItem *__restrict__ items0,
+    int32_t *__restrict__ nitems0, GemmPlan gp0, WorkItem *__restrict__ items1,
+    int32_t *__restrict__ nitems1, GemmPlan gp1, int E, int capacity, int n_micro)
+{
+    __shared__ int32_t lo_s[kMaxExperts], hi_s[kMaxExperts], mt_s[kMaxExperts];
+    __shared__ int32_t cum_s[kMaxExperts + 1];
+    const int m = blockIdx.x;
+    const GemmPlan gp = blockIdx.y == 0 ? gp0 : gp1;
+    WorkItem *items = (blockIdx.y == 0 ? items0 : items1) + static_cast<size_t>(m) * gp.max_items;
+    int32_t *nitems = (blockIdx.y == 0 ? nitems0 : nitems1) + m;
+    if (threadIdx.x < kWave) {
+        const int e = threadIdx.x;
+        int lo = 0, hi = 0;
+        if (e < E) {
+            const int kept = min(counts[e], capacity);
+            const int p0 = static_cast<int>(static_cast<long>(m) * capacity / n_micro);
+            const int p1 = static_cast<int>(static_cast<long>(m + 1) * capacity / n_micro);
+            lo = e * capacity + min(p0, kept);
+            hi = e * capacity + min(p1, kept);
+        }
+        lo_s[e] = lo;
+        hi_s[e] = hi;
+    }
+    __syncthreads();
+    build_items(gp, items, nitems, lo_s, hi_s, mt_s, cum_s, blockIdx.z, gridDim.z);
+}
+
 }  // namespace
+
+moe_status launch_items_padded(const moe_shape &s, int n_micro, const int32_t *counts,
+                               const Workspace &w, hipStream_t st)
+{
+    hipLaunchKernelGGL(plan_items_padded_kernel, dim3(n_micro, 2, 4), dim3(256), 0, st, counts,
+                       w.items[0], w.nitems[0], w.gp[0], w.items[1], w.nitems[1], w.gp[1], s.E,
+                       s.capacity, n_micro);
+    MOE_TRY_HIP(hipGetLastError());
+    return MOE_OK;
+}
 
 moe_status launch_items_per_expert(const moe_shape &s, const int32_t *offsets, const Workspace &w,
                                    hipStream_t st)
@@ -323,7 +365,7 @@ moe_status launch_items_per_expert(const moe_shape &s, const int32_t *offsets, c
 
 moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *counts,
                        int32_t *offsets, int32_t *slot_of, int32_t *src_of,
-                       const Workspace &w, bool counted, int n_chunks, hipStream_t st)
+                       const Workspace &w, bool counted, int n_chunks, hipStream_t st, bool padded)
 {
     const int n = s.T * s.k;
     const int seg_len = w.seg_tok * s.k;
@@ -334,11 +376,11 @@ moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *c
         hipLaunchKernelGGL(plan_count_kernel, dim3(blocks), dim3(kPlanThreads), 0, st,
                            expert_idx, w.seg_cnt, n, s.E, seg_len);
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, w.seg_cnt, counts,
-                       offsets, w.nseg, s.E, eps, s.capacity, n_chunks == 1 ? 1 : 0, w.items[0],
+                       offsets, w.nseg, s.E, eps, s.capacity, n_chunks == 1 && !padded ? 1 : 0, w.items[0],
                        w.nitems[0], w.gp[0], w.items[1], w.nitems[1], w.gp[1]);
     hipLaunchKernelGGL(plan_rank_kernel, dim3(blocks), dim3(kPlanThreads), 0, st,
                        expert_idx, w.seg_cnt, offsets, slot_of, src_of, n, s.E, s.capacity,
-                       seg_len);
+                       seg_len, padded ? 1 : 0);
     MOE_TRY_HIP(hipGetLastError());
     return MOE_OK;
 }

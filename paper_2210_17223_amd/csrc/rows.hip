@@ -105,11 +105,11 @@ moe_status launch_scatter(const moe_shape &s, const void *x, const int32_t *slot
 
 moe_status launch_combine(const moe_shape &s, const float *ye, const int32_t *slot_of,
                           const float *gate, float *y, void *y_act, int t0, int t1,
-                          hipStream_t st)
+                          hipStream_t st, int64_t rows)
 {
     if (t1 <= t0) return MOE_OK;
     const int vec = s.d_model / 4;   // 16-byte vectors of fp32
-    const int max_rows = static_cast<int>(moe_max_rows(&s));
+    const int max_rows = static_cast<int>(rows < 0 ? moe_max_rows(&s) : rows);
     const dim3 grid(ceil_div(t1 - t0, kRowWaves)), block(kRowThreads);
     const float4 *ye4 = reinterpret_cast<const float4 *>(ye);
     float4 *y4 = reinterpret_cast<float4 *>(y);
