@@ -11,6 +11,7 @@
 //   plan_scan  : one block; exclusive scan over segments per expert, totals,
 //                capacity clamp, offsets; for an unchunked layer also the work lists
 //   plan_rank  : per-segment ranks -> slot_of / src_of
+//   plan_rank_prefix : scan and rank in one launch when there are few segments
 //   plan_items : work lists of the two expert GEMMs per chunk
 #include "common.h"
 
@@ -18,6 +19,8 @@ namespace moe {
 namespace {
 
 constexpr int kPlanWaves = 4;                    // wavefronts (segments) per block
+constexpr int kPrefixSegments = 512;             // plans up to this many segments: one launch
+constexpr int kItemBlocks = 8;                   // ... whose work lists are built by this many blocks
 constexpr int kPlanThreads = kPlanWaves * kWave;
 
 // Mask of the lanes whose (valid) expert equals this lane's.
@@ -240,6 +243,108 @@ __device__ void build_items(const GemmPlan &gp, WorkItem *__restrict__ items,
     __syncthreads();
 }
 
+// Scan and rank in one launch, for plans of few segments: every block sums the raw
+// per-segment counts itself (all of them for the totals, those before its first segment for
+// its own base -- nseg * 256 bytes from L2 per block) instead of waiting for a scan kernel's
+// launch.  The blocks beyond those that rank segments hold none: the last one writes counts
+// and offsets, and for an unchunked layer they share the building of the work lists.
+__global__ __launch_bounds__(kPlanThreads) void plan_rank_prefix_kernel(
+    const int32_t *__restrict__ expert_idx, const int32_t *__restrict__ seg_cnt,
+    int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ slot_of,
+    int32_t *__restrict__ src_of, int n, int E, int capacity, int seg_len, int nseg, int padded,
+    int with_items, WorkItem *__restrict__ items0, int32_t *__restrict__ nitems0, GemmPlan gp0,
+    WorkItem *__restrict__ items1, int32_t *__restrict__ nitems1, GemmPlan gp1)
+{
+    constexpr int kParts = kPlanWaves * 4;          // partial sums: 16-byte loads, 4 segments per wavefront load
+    __shared__ int32_t part_before[kParts][kMaxExperts], part_total[kParts][kMaxExperts];
+    __shared__ int32_t run[kPlanWaves][kMaxExperts];
+    __shared__ int32_t off_s[kMaxExperts];
+    __shared__ int32_t lo_s[kMaxExperts], hi_s[kMaxExperts], mt_s[kMaxExperts];
+    __shared__ int32_t cum_s[kMaxExperts + 1];
+    const int lane = lane_id();
+    const int wave = threadIdx.x / kWave;
+    const int first = min(static_cast<int>(blockIdx.x) * kPlanWaves, nseg);
+    {
+        // lane = (segment of the load, four experts): part p = wave * 4 + lane / 16 walks the
+        // segments p, p + 16, ...
+        const int part = wave * 4 + lane / 16, e4 = (lane % 16) * 4;
+        int4 before = make_int4(0, 0, 0, 0), total = before;
+#pragma unroll 16
+        for (int s = part; s < nseg; s += kParts) {
+            const int4 c = *reinterpret_cast<const int4 *>(seg_cnt + static_cast<size_t>(s) * kMaxExperts + e4);
+            total.x += c.x; total.y += c.y; total.z += c.z; total.w += c.w;
+            if (s < first) { before.x += c.x; before.y += c.y; before.z += c.z; before.w += c.w; }
+        }
+        *reinterpret_cast<int4 *>(&part_before[part][e4]) = before;
+        *reinterpret_cast<int4 *>(&part_total[part][e4]) = total;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        int32_t before = 0, total = 0;
+#pragma unroll
+        for (int q = 0; q < kParts; ++q) {
+            before += part_before[q][lane];
+            total += part_total[q][lane];
+        }
+        const int32_t kept = lane < E ? min(total, capacity) : 0;
+        int32_t incl = kept;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int v = __shfl_up(incl, d);
+            if (lane >= d) incl += v;
+        }
+        off_s[lane] = lane >= E ? 0 : padded ? lane * capacity : incl - kept;
+        lo_s[lane] = incl - kept;
+        hi_s[lane] = incl;
+        int32_t base = before;
+#pragma unroll
+        for (int q = 0; q < kPlanWaves; ++q) {
+            run[q][lane] = base;
+            if (first + q < nseg) base += seg_cnt[static_cast<size_t>(first + q) * kMaxExperts + lane];
+        }
+        if (first == nseg && blockIdx.x == gridDim.x - 1) {   // one of the blocks without segments
+            if (lane < E) {
+                counts[lane] = total;
+                offsets[lane] = incl - kept;
+            }
+            if (lane == E - 1) offsets[E] = incl;
+        }
+    }
+    __syncthreads();
+    if (first == nseg) {
+        if (with_items) {
+            // the kItemBlocks blocks without segments: even ones build the first GEMM's list,
+            // odd ones the second's, each its share
+            const int x = static_cast<int>(gridDim.x - 1 - blockIdx.x);
+            if (x & 1)
+                build_items(gp1, items1, nitems1, lo_s, hi_s, mt_s, cum_s, x >> 1, kItemBlocks / 2);
+            else
+                build_items(gp0, items0, nitems0, lo_s, hi_s, mt_s, cum_s, x >> 1, kItemBlocks / 2);
+        }
+        return;
+    }
+    const int seg = first + wave;
+    const int base = seg * seg_len;
+    if (seg >= nseg) return;
+    for (int off = 0; off < seg_len; off += kWave) {
+        const int i = base + off + lane;
+        const bool valid = i < n && off + lane < seg_len;
+        const int e = valid ? clamp_expert(expert_idx[i], E) : 0;
+        const uint64_t peers = same_expert_lanes(e, valid);
+        const int rank = __popcll(peers & lanes_below(lane));
+        const int32_t before = run[wave][e];
+        __builtin_amdgcn_wave_barrier();
+        if (valid && rank == 0) run[wave][e] = before + __popcll(peers);
+        __builtin_amdgcn_wave_barrier();
+        if (valid) {
+            const int32_t pos = before + rank;
+            const int32_t slot = pos < capacity ? off_s[e] + pos : -1;
+            slot_of[i] = slot;
+            if (slot >= 0) src_of[slot] = i;
+        }
+    }
+}
+
 // Work lists for chunk c (blockIdx.x) and GEMM g (blockIdx.y).  Expert e's rows of the chunk
 // are the slots whose source assignment lies in [t0*k, t1*k); src_of ascends inside an
 // expert, so both ends are binary searches (lane e of the first wavefront owns expert e).
@@ -375,6 +480,16 @@ moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *c
     if (!counted)
         hipLaunchKernelGGL(plan_count_kernel, dim3(blocks), dim3(kPlanThreads), 0, st,
                            expert_idx, w.seg_cnt, n, s.E, seg_len);
+    if (w.nseg <= kPrefixSegments) {
+        const bool with_items = n_chunks == 1 && !padded;
+        hipLaunchKernelGGL(plan_rank_prefix_kernel, dim3(blocks + (with_items ? kItemBlocks : 1)),
+                           dim3(kPlanThreads), 0, st,
+                           expert_idx, w.seg_cnt, counts, offsets, slot_of, src_of, n, s.E,
+                           s.capacity, seg_len, w.nseg, padded ? 1 : 0, with_items ? 1 : 0, w.items[0], w.nitems[0], w.gp[0],
+                           w.items[1], w.nitems[1], w.gp[1]);
+        MOE_TRY_HIP(hipGetLastError());
+        return MOE_OK;
+    }
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, w.seg_cnt, counts,
                        offsets, w.nseg, s.E, eps, s.capacity, n_chunks == 1 && !padded ? 1 : 0, w.items[0],
                        w.nitems[0], w.gp[0], w.items[1], w.nitems[1], w.gp[1]);

@@ -179,7 +179,9 @@ def test_all_to_all_completion_time_with_and_without_priority():
         try:
             warm = comm.moe_comm_submit(c, comm.ALLREDUCE, tok, tout, 1, 64, 16, 1)   # first launch: code load
             comm.moe_comm_post(c, warm, 0, 1)
+            comm.moe_comm_wait(c, warm, 0, side)               # (and the side stream's first use)
             comm.moe_comm_finish(c, warm)
+            torch.cuda.synchronize()
             ar = comm.moe_comm_submit(c, comm.ALLREDUCE, grad, gout, 1, grad.numel() // 4, 16, n_ar)
             comm.moe_comm_post(c, ar, 0, n_ar)
             comm.moe_comm_wait(c, ar, 0, side)                 # the allreduce has the link
