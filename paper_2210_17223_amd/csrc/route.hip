@@ -37,6 +37,91 @@ __device__ __forceinline__ void store_row_vec(float *dst, const u32x4 &q, uint16
     *reinterpret_cast<f32x4 *>(dst + 4) = hi;
 }
 
+// Top-k, softmax weights and the histogram of a block's tokens from their logits in LDS
+// (zs[token][expert]; the histogram sits behind them), with LP lanes per token -- all 256
+// lanes when the block has few tokens: lane `sub` of a token's group holds the logits of
+// experts sub, sub + LP, ... (NQ of them) in registers; maxima, sums and the k selections
+// are butterflies over the group.  Groups are aligned pieces of one wavefront.
+template <int NQ>
+__device__ __forceinline__ void route_tail(float (*zs)[kMaxExperts + 1], int32_t *__restrict__ expert_idx,
+                                           float *__restrict__ gate, int32_t *__restrict__ seg_cnt,
+                                           int t0, int T, int E, int TB, int LP, int k, int renorm)
+{
+    const int tid = threadIdx.x;
+    int32_t *cnt = reinterpret_cast<int32_t *>(&zs[kWave][0]);
+    if (seg_cnt != nullptr && tid < kMaxExperts) cnt[tid] = 0;
+    const int tl = tid / LP, sub = tid % LP;
+    const int t = t0 + tl;
+    const bool live = tl < TB && t < T;
+    float zl[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int e = sub + LP * q;
+        zl[q] = (live && e < E) ? zs[tl][e] : -INFINITY;
+    }
+    if (seg_cnt != nullptr) __syncthreads();     // the histogram is cleared
+    float zmax = zl[0];
+#pragma unroll
+    for (int q = 1; q < NQ; ++q) zmax = fmaxf(zmax, zl[q]);
+    for (int m = 1; m < LP; m <<= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, m));
+    float denom = 0.0f;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q)
+        if (sub + LP * q < E) denom += expf(zl[q] - zmax);
+    for (int m = 1; m < LP; m <<= 1) denom += __shfl_xor(denom, m);
+
+    constexpr int kNone = 0x7fffffff;            // "no candidate": never wins a comparison
+    float sel_z[kMaxTopK];
+    int sel_e[kMaxTopK];
+    uint32_t taken = 0;                          // bit q: this lane's q-th expert is selected
+    float gsum = 0.0f;
+#pragma unroll
+    for (int j = 0; j < kMaxTopK; ++j) {
+        sel_z[j] = 0.0f;
+        sel_e[j] = 0;
+        if (j < k) {
+            float bz = -INFINITY;
+            int be = kNone;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const int e = sub + LP * q;      // ascending in q: a strict > keeps the lower index
+                if (e < E && !((taken >> q) & 1u) && (be == kNone || zl[q] > bz)) {
+                    bz = zl[q];
+                    be = e;
+                }
+            }
+            for (int m = 1; m < LP; m <<= 1) {
+                const float oz = __shfl_xor(bz, m);
+                const int oe = __shfl_xor(be, m);
+                if (oe != kNone && (be == kNone || oz > bz || (oz == bz && oe < be))) {
+                    bz = oz;
+                    be = oe;
+                }
+            }
+            if (be != kNone && be % LP == sub) taken |= 1u << (be / LP);
+            sel_z[j] = bz;
+            sel_e[j] = be;
+            gsum += expf(bz - zmax) / denom;
+        }
+    }
+    if (live && sub == 0) {
+#pragma unroll
+        for (int j = 0; j < kMaxTopK; ++j) {
+            if (j < k) {
+                const float g = expf(sel_z[j] - zmax) / denom;
+                expert_idx[static_cast<size_t>(t) * k + j] = sel_e[j];
+                gate[static_cast<size_t>(t) * k + j] = renorm ? g / gsum : g;
+                if (seg_cnt != nullptr) atomicAdd(&cnt[sel_e[j]], 1);
+            }
+        }
+    }
+    if (seg_cnt != nullptr) {
+        __syncthreads();
+        if (tid < kMaxExperts)
+            seg_cnt[static_cast<size_t>(blockIdx.x) * kMaxExperts + tid] = cnt[tid];
+    }
+}
+
 // Block = TB tokens x EP experts (EP = E rounded up to a power of two), NG = EP / EPL
 // expert groups x TB / TPL token groups of lanes.  Lane (tg, eg) owns tokens
 // a * TG + tg and experts b * NG + eg (interleaved, so that the lanes of a wavefront read
@@ -178,55 +263,13 @@ __global__ __launch_bounds__(256, 2) void route_kernel(
         }
     }
     __syncthreads();
-    if (tid >= kWave) return;
-    const int lane = tid;
-    const int t = t0 + lane;
-    // The histogram sits behind the logits in the reused tile memory.
-    int32_t *cnt = reinterpret_cast<int32_t *>(&zs[kWave][0]);
-    if (seg_cnt != nullptr) cnt[lane] = 0;
-    __builtin_amdgcn_wave_barrier();
-    if (lane < TB && t < T) {
-    // softmax denominator over all E experts
-    float zmax = zs[lane][0];
-    for (int e = 1; e < E; ++e) zmax = fmaxf(zmax, zs[lane][e]);
-    float denom = 0.0f;
-    for (int e = 0; e < E; ++e) denom += expf(zs[lane][e] - zmax);
-
-    float gsum = 1.0f;
-    if (renorm) {
-        gsum = 0.0f;
-        uint64_t taken = 0;
-        for (int j = 0; j < k; ++j) {
-            int best = -1;
-            float bz = 0.0f;
-            for (int e = 0; e < E; ++e) {
-                if ((taken >> e) & 1ull) continue;
-                const float zv = zs[lane][e];
-                if (best < 0 || zv > bz) { best = e; bz = zv; }
-            }
-            taken |= 1ull << best;
-            gsum += expf(bz - zmax) / denom;
-        }
-    }
-    uint64_t taken = 0;
-    for (int j = 0; j < k; ++j) {
-        int best = -1;
-        float bz = 0.0f;
-        for (int e = 0; e < E; ++e) {
-            if ((taken >> e) & 1ull) continue;
-            const float zv = zs[lane][e];
-            if (best < 0 || zv > bz) { best = e; bz = zv; }   // ties: lower index stays
-        }
-        taken |= 1ull << best;
-        const float g = expf(bz - zmax) / denom;
-        expert_idx[static_cast<size_t>(t) * k + j] = best;
-        gate[static_cast<size_t>(t) * k + j] = renorm ? g / gsum : g;
-        if (seg_cnt != nullptr) atomicAdd(&cnt[best], 1);
-    }
-    }
-    if (seg_cnt != nullptr) {
-        __builtin_amdgcn_wave_barrier();
-        seg_cnt[static_cast<size_t>(blockIdx.x) * kMaxExperts + lane] = cnt[lane];
+    const int LP = min(min(256 / TB, EP), kWave);      // lanes per token in the tail
+    switch (EP / LP) {                                 // logits per lane: at most 16 (LP >= 4 when EP = 64)
+    case 1: route_tail<1>(zs, expert_idx, gate, seg_cnt, t0, T, E, TB, LP, k, renorm); break;
+    case 2: route_tail<2>(zs, expert_idx, gate, seg_cnt, t0, T, E, TB, LP, k, renorm); break;
+    case 4: route_tail<4>(zs, expert_idx, gate, seg_cnt, t0, T, E, TB, LP, k, renorm); break;
+    case 8: route_tail<8>(zs, expert_idx, gate, seg_cnt, t0, T, E, TB, LP, k, renorm); break;
+    default: route_tail<16>(zs, expert_idx, gate, seg_cnt, t0, T, E, TB, LP, k, renorm); break;
     }
 }
 
