@@ -140,6 +140,9 @@ __global__ __launch_bounds__(256, 2) void route_kernel(
     // enough for two to cover the load latency
     constexpr int PD = TPL * EPL >= 4 ? 2 : 3;
     constexpr int UNR = PD == 2 ? 2 : 6;             // stages per unrolled trip: lcm(PD, 2)
+    // LDS reads hoisted ahead of the chain: a lane with one or two chains has nothing else to
+    // cover their latency with
+    constexpr int IU = TPL * EPL <= 2 ? 16 : 4;
     constexpr int VE = 16 / sizeof(XT);              // elements per 16-byte vector
     constexpr int XRV = kKC / VE;                    // 16-byte vectors per token row per stage
     constexpr int WRV = kKC / 4;                     // ... per gate-matrix row per stage
@@ -223,7 +226,7 @@ __global__ __launch_bounds__(256, 2) void route_kernel(
                 if (s + PD < nstage) MOE_LOAD_STAGE(u % PD, (s + PD) * kKC)
                 const float *xrow = xs + buf * TB * kLDX + tg * kLDX;
                 const float *wrow = ws + buf * EP * kLDX + eg * kLDX;
-#pragma unroll 4
+#pragma unroll IU
                 for (int i4 = 0; i4 < kKC / 4; ++i4) {
                     f32x4 xv[TPL], wv[EPL];
 #pragma unroll
@@ -319,7 +322,13 @@ RouteShape route_shape(const moe_shape &s)
         const int tb = std::min(64, 256 * tpl / ng);
         if (tb < tpl) continue;
         const bool last = c == 4;
-        if (last || chains / (tpl * epl) >= 131072) return {tpl, epl, tb};
+        if (last || chains / (tpl * epl) >= 131072) {
+            // a handful of tokens: fewer blocks than compute units -- spread them (the lanes
+            // of a block share its LDS, and a chain is only as fast as its operands arrive)
+            int few = tb;
+            while (few > 8 && few > tpl && (s.T + few - 1) / few < 256) few /= 2;
+            return {tpl, epl, few};
+        }
     }
     return {1, 1, std::min(64, 256 / EP)};
 }
