@@ -142,6 +142,7 @@ def main() -> int:
                     self.bws = torch.empty(moe.moe_backward_workspace_bytes(s), dtype=torch.uint8, device=dev)
                     self.pre = None if args.recompute else torch.empty(
                         moe.moe_max_rows(s) * l0.h, dtype=torch.float16, device=dev)
+                    self.hid = None if args.recompute else torch.empty_like(self.pre)
             else:       # a second copy of the same layer at other addresses
                 self.x = None if like.x is None else like.x.clone()
                 self.bias = None if like.bias is None else like.bias.clone()
@@ -166,7 +167,7 @@ def main() -> int:
             if args.backward and self.pre is not None:
                 moe.moe_layer_forward_keep(s, x, b["Wgp"], self.bias, self.stride, b["W1p"], None, b["W2p"],
                                            None, b["expert_idx"], b["gate"], b["counts"], b["offsets"],
-                                           b["slot_of"], b["src_of"], b["xe"], b["ye"], self.pre, b["y"],
+                                           b["slot_of"], b["src_of"], b["xe"], b["ye"], self.pre, self.hid, b["y"],
                                            b["workspace"])
             else:
                 moe.moe_layer_chunked(s, args.chunks, x, b["Wgp"], self.bias, self.stride, b["W1p"], None,
@@ -176,7 +177,7 @@ def main() -> int:
             if args.backward:
                 moe.moe_layer_backward(s, x, b["Wgp"], self.bias, self.stride, self.W1, self.W2, b["W1p"],
                                        b["expert_idx"], b["gate"], b["offsets"], b["slot_of"], b["src_of"],
-                                       b["xe"], b["ye"], self.pre, self.dy, *self.g, self.bws)
+                                       b["xe"], b["ye"], self.pre, self.hid, self.dy, *self.g, self.bws)
 
     sets = [[DevLayer(li) for li in host]]
     for li in host:       # the host copies of the weights are needed again only by the oracle
@@ -231,10 +232,10 @@ def main() -> int:
     ffn_hbm_s = (2 * live * l0.d * l0.h * 2 + A * l0.d * (2 + 4)) / (PEAK_HBM_GBPS * 1e9)
     hbm_bound = ffn_hbm_s > ffn_mfma_s
     if args.backward:
-        # dW2[e] = act(P)^T dye: reads both transposed operands once, writes fp32 dW2
+        # dW2[e] = act(P)^T dye: reads both operands once, writes fp32 dW2
         g1_bytes = A * l0.h * 2 + A * l0.d * 2 + l0.E * l0.d * l0.h * 4
         g1_gbps = g1_bytes / (g1_avg_ms * 1e-3) / 1e9
-    roof = {"kernel": ("bwd_gemm_kernel<weight gradient> (dW2 = act(P)^T dye)" if args.backward else
+    roof = {"kernel": ("wgrad_gemm_kernel (dW2 = act(P)^T dye)" if args.backward else
                        "grouped_gemm_mfma_kernel<bf16 in, fp16 out, GeLU> (first expert GEMM)"),
             "avg_launch_us": g1_avg_ms * 1e3, "launches": int(g1_ms.size),
             "algorithmic_flops": g1_flops, "algorithmic_bytes": g1_bytes,

@@ -9,7 +9,9 @@
  *   dgate[t,j] = <ye[slot], dy[t]>              (0 for dropped assignments)
  *   dP         = (dye . W2[e]^T) * act'(P)      P = xe . W1[e]: kept by the forward call
  *                                               below, else recomputed here
- *   dW2[e]     = act(P)^T . dye                 rows of expert e
+ *   dW2[e]     = act(P)^T . dye                 rows of expert e; act(P) kept by the forward
+ *                                               call below (fp16, rounded to bf16 as an
+ *                                               operand), else recomputed
  *   dW1[e]     = xe^T . dP
  *   dxe        = dP . W1[e]^T
  *   dz[t,:]    = p * (dgfull - <p, dgfull>)     p = softmax of the token's logits,
@@ -40,6 +42,8 @@ extern "C" {
  * before the activation, which the backward pass would otherwise compute again.
  *   pre  [moe_max_rows, d_ff] fp16, output: pre[slot,:] = xe[slot,:] W1[e] + b1[e], rounded
  *        from the fp32 accumulator; rows at or beyond offsets[E] are left untouched
+ *   hid  [moe_max_rows, d_ff] fp16, output: act(pre) as the second GEMM reads it -- the
+ *        hidden activations, which otherwise live in the workspace; same rows
  * bf16 layers only.
  */
 moe_status moe_layer_forward_keep(const moe_shape *s, const void *x, const float *Wgp,
@@ -47,8 +51,8 @@ moe_status moe_layer_forward_keep(const moe_shape *s, const void *x, const float
                                   const void *W1p, const float *b1, const void *W2p,
                                   const float *b2, int32_t *expert_idx, float *gate,
                                   int32_t *counts, int32_t *offsets, int32_t *slot_of,
-                                  int32_t *src_of, void *xe, float *ye, void *pre, float *y,
-                                  void *workspace, void *stream);
+                                  int32_t *src_of, void *xe, float *ye, void *pre, void *hid,
+                                  float *y, void *workspace, void *stream);
 
 /* Bytes of workspace moe_layer_backward needs for this shape (0 if unsupported). */
 size_t moe_backward_workspace_bytes(const moe_shape *s);
@@ -60,7 +64,7 @@ size_t moe_backward_workspace_bytes(const moe_shape *s);
  *                    canonical layouts; W1p the packed W1 of moe_pack_weights
  *   forward outputs  expert_idx, gate, offsets, slot_of, src_of, xe, ye exactly as the
  *                    forward call left them
- *   pre              NULL, or the buffer moe_layer_forward_keep filled in that forward call
+ *   pre, hid         both NULL, or the buffers moe_layer_forward_keep filled in that forward call
  *                    (the backward pass of a layer with FFN biases is not supported either way)
  *   dy               [T,d] fp32
  *   dx [T,d], dWg [d,E], dW1 [E,d,h], dW2 [E,h,d], dgate [T*k]: fp32, overwritten (weight
@@ -72,8 +76,9 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
                               const int32_t *expert_idx, const float *gate,
                               const int32_t *offsets, const int32_t *slot_of,
                               const int32_t *src_of, const void *xe, const float *ye,
-                              const void *pre, const float *dy, float *dx, float *dWg, float *dW1,
-                              float *dW2, float *dgate, void *workspace, void *stream);
+                              const void *pre, const void *hid, const float *dy, float *dx,
+                              float *dWg, float *dW1, float *dW2, float *dgate, void *workspace,
+                              void *stream);
 
 #ifdef __cplusplus
 }

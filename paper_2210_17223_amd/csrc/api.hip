@@ -424,8 +424,8 @@ moe_status layer_forward(const moe_shape *s, int32_t n_chunks, const void *x,
                          int32_t bias_token_stride, const void *W1p, const float *b1,
                          const void *W2p, const float *b2, int32_t *expert_idx, float *gate,
                          int32_t *counts, int32_t *offsets, int32_t *slot_of,
-                         int32_t *src_of, void *xe, float *ye, void *pre, float *y, void *y_act,
-                         void *workspace, void *stream)
+                         int32_t *src_of, void *xe, float *ye, void *pre, void *hid, float *y,
+                         void *y_act, void *workspace, void *stream)
 {
     MOE_TRY(check_common(s));
     if (n_chunks < 1 || n_chunks > kMaxChunks) {
@@ -454,6 +454,7 @@ moe_status layer_forward(const moe_shape *s, int32_t n_chunks, const void *x,
 
     Workspace w;
     layout_workspace(*s, n_chunks, workspace, &w);
+    if (hid != nullptr) w.hidden = hid;       // the hidden activations go where the caller keeps them
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     MOE_TIMED(kStageRoute, st,
@@ -513,8 +514,8 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
                              void *workspace, void *stream)
 {
     return layer_forward(s, n_chunks, x, Wgp, gate_bias, bias_token_stride, W1p, b1, W2p, b2,
-                         expert_idx, gate, counts, offsets, slot_of, src_of, xe, ye, nullptr, y,
-                         y_act, workspace, stream);
+                         expert_idx, gate, counts, offsets, slot_of, src_of, xe, ye, nullptr,
+                         nullptr, y, y_act, workspace, stream);
 }
 
 moe_status moe_layer_forward_keep(const moe_shape *s, const void *x, const float *Wgp,
@@ -522,8 +523,8 @@ moe_status moe_layer_forward_keep(const moe_shape *s, const void *x, const float
                                   const void *W1p, const float *b1, const void *W2p,
                                   const float *b2, int32_t *expert_idx, float *gate,
                                   int32_t *counts, int32_t *offsets, int32_t *slot_of,
-                                  int32_t *src_of, void *xe, float *ye, void *pre, float *y,
-                                  void *workspace, void *stream)
+                                  int32_t *src_of, void *xe, float *ye, void *pre, void *hid,
+                                  float *y, void *workspace, void *stream)
 {
     MOE_TRY(check_common(s));
     if (s->dtype != MOE_BF16) {
@@ -531,8 +532,9 @@ moe_status moe_layer_forward_keep(const moe_shape *s, const void *x, const float
         return MOE_EUNSUPPORTED;
     }
     MOE_REQUIRE_PTR(pre);
+    MOE_REQUIRE_PTR(hid);
     return layer_forward(s, 1, x, Wgp, gate_bias, bias_token_stride, W1p, b1, W2p, b2, expert_idx,
-                         gate, counts, offsets, slot_of, src_of, xe, ye, pre, y, nullptr,
+                         gate, counts, offsets, slot_of, src_of, xe, ye, pre, hid, y, nullptr,
                          workspace, stream);
 }
 

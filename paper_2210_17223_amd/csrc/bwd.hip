@@ -2,20 +2,19 @@
 // trains this layer and schedules its backward pass in Sec. 2.2 and Sec. 4).
 //
 //   combine_bwd      dye[slot] = g dy[t] (bf16), dgate = <ye[slot], dy[t]>
-//   gemm (rows)      P = xe W1 (fp16) and Hb = act(P) (bf16), recomputed unless the forward
-//                    kept P (then Hb is formed while it is transposed)
+//   gemm (rows)      P = xe W1 (fp16) and Hb = act(P) (bf16) -- only when the forward did not
+//                    keep P and its hidden activations
 //   gemm (rows)      dP = (dye W2^T) * act'(P)                        (bf16)
 //   gemm (rows)      dxe = dP W1^T                                    (fp32)
-//   transposes       Hb, dye, xe, dP -> [columns][rows], each expert's rows padded to 64
-//   gemm (wgrad)     dW2[e] = Hb^T dye, dW1[e] = xe^T dP              (fp32)
+//   gemm (wgrad)     dW2[e] = act(P)^T dye, dW1[e] = xe^T dP          (fp32), operands row-major
+//                    as they are: the fragments come out of LDS through transposing reads
 //   gate_bwd         logits (from the packed gate matrix), softmax, dz,
 //                    dx = sum of the token's dxe rows + dz Wg^T
 //   dwg              dWg = x^T dz (partial sums over token ranges, then a fixed-order sum)
 //
-// The contractions use 128 x 128 output tiles of 32x32x16 bf16 MFMAs fed through a
-// double-buffered LDS tile, like the forward's expert GEMM; a row-grouped GEMM walks the
-// forward's kind of work list, a weight-gradient GEMM contracts over one expert's
-// (transposed, zero-padded) rows.
+// The contractions use 128 x 128 (or 128 x 256) output tiles of 32x32x16 bf16 MFMAs fed
+// through a double-buffered LDS tile, like the forward's expert GEMM; a row-grouped GEMM walks
+// the forward's kind of work list, a weight-gradient GEMM contracts over one expert's rows.
 #include "common.h"
 #include "moe_train.h"
 
@@ -125,48 +124,30 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(
 }
 
 // ---------------------------------------------------------------- GEMM
-// MODE 0 (rows): C[r, n] = sum_k A[r, k] W[e][n, k] for the rows of one work item.
-// MODE 1 (weight gradient): C[e][m, n] = sum_k A[m, koff[e] + k] W[n, koff[e] + k],
-//   A and W being [M or N][lda] transposed activations, k over expert e's padded rows.
+// C[r, n] = sum_k A[r, k] W[e][n, k] for the rows of one work item.
 // EPI 0: fp32 store.  EPI 1: P = acc as fp16 into Pbuf and act(acc) as bf16 into C.
 // EPI 2: acc * act'(Pbuf) as bf16 into C.
-template <int MODE, int EPI, int ACT, bool KTAIL, int WN>
+template <int EPI, int ACT, bool KTAIL, int WN>
 __global__ __launch_bounds__(128 * WN, 2) void bwd_gemm_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, void *__restrict__ Cout,
     _Float16 *__restrict__ Pbuf, const WorkItem *__restrict__ items,
-    const int32_t *__restrict__ nitems, const int32_t *__restrict__ koff, int E, int M, int N,
-    int K, int tiles_m, int tiles_n)
+    const int32_t *__restrict__ nitems, int N, int K)
 {
     constexpr int WM = 2, TM = 2, TN = 2, NT = 128 * WN;   // 2 x WN wavefronts of 64 x 64
     constexpr int kBN = 64 * WN;
     constexpr int AV = kBM * 8 / NT, WV = kBN * 8 / NT;
-    int expert, row0, row1, n0, KT;
-    size_t a_pitch, a_base, w_base;
+    int expert, row0, row1, n0;
     {
-        const int total = MODE == 0 ? *nitems : E * tiles_m * tiles_n;
+        const int total = *nitems;
         const int per_xcd = (total + 7) / 8;
         const int slot = blockIdx.x / 8;
         const int idx = (blockIdx.x % 8) * per_xcd + slot;
         if (slot >= per_xcd || idx >= total) return;
-        if constexpr (MODE == 0) {
-            const WorkItem item = items[idx];
-            expert = item.expert; row0 = item.row0; row1 = item.row1; n0 = item.n0;
-            KT = (K + kBK - 1) / kBK;
-            a_pitch = K;
-            a_base = 0;
-            w_base = static_cast<size_t>(expert) * N * K;
-        } else {
-            expert = idx / (tiles_m * tiles_n);
-            const int rem = idx % (tiles_m * tiles_n);
-            row0 = (rem / tiles_n) * kBM;
-            row1 = min(M, row0 + kBM);
-            n0 = (rem % tiles_n) * kBN;
-            KT = (koff[expert + 1] - koff[expert]) / kBK;
-            a_pitch = K;                       // K carries the row pitch of the transposed buffers
-            a_base = koff[expert];
-            w_base = koff[expert];
-        }
+        const WorkItem item = items[idx];
+        expert = item.expert; row0 = item.row0; row1 = item.row1; n0 = item.n0;
     }
+    const int KT = (K + kBK - 1) / kBK;
+    const size_t w_base = static_cast<size_t>(expert) * N * K;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     constexpr int A_BUF = kBM * kLD, W_BUF = kBN * kLD;
     uint16_t *As = smem;
@@ -193,13 +174,13 @@ __global__ __launch_bounds__(128 * WN, 2) void bwd_gemm_kernel(
         for (int q = 0; q < AV; ++q) {
             const int r = (tid + NT * q) >> 3;
             a_off[q] = r * kLD + ld_col;
-            a_src[q] = A + a_base + static_cast<size_t>(min(row0 + r, row1 - 1)) * a_pitch + ld_col;
+            a_src[q] = A + static_cast<size_t>(min(row0 + r, row1 - 1)) * K + ld_col;
         }
 #pragma unroll
         for (int q = 0; q < WV; ++q) {
             const int r = (tid + NT * q) >> 3;
             w_off[q] = r * kLD + ld_col;
-            w_src[q] = W + w_base + static_cast<size_t>(min(n0 + r, N - 1)) * a_pitch + ld_col;
+            w_src[q] = W + w_base + static_cast<size_t>(min(n0 + r, N - 1)) * K + ld_col;
         }
         u32x4 a_reg[AV], w_reg[WV], a_reg2[AV], w_reg2[WV];   // two register stages of prefetch
         u32x4 wf[2][TN], af[2][TM];
@@ -283,7 +264,6 @@ __global__ __launch_bounds__(128 * WN, 2) void bwd_gemm_kernel(
 
     // acc[i][j][4*g + c]: column n0 + (wn*TN + i)*32 + 8*g + 4*(lane/32) + c,
     //                     row row0 + (wm*TM + j)*32 + lane%32
-    const size_t c_base = MODE == 0 ? 0 : static_cast<size_t>(expert) * M * N;
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
         const int r = row0 + (wm * TM + j) * 32 + fr;
@@ -294,7 +274,7 @@ __global__ __launch_bounds__(128 * WN, 2) void bwd_gemm_kernel(
             for (int g = 0; g < 4; ++g) {
                 const int n = n0 + (wn * TN + i) * 32 + 8 * g + 4 * (lane >> 5);
                 if (n >= N) continue;
-                const size_t at = c_base + static_cast<size_t>(r) * N + n;
+                const size_t at = static_cast<size_t>(r) * N + n;
                 float v[4];
 #pragma unroll
                 for (int c = 0; c < 4; ++c) v[c] = acc[i][j][4 * g + c];
@@ -323,65 +303,221 @@ __global__ __launch_bounds__(128 * WN, 2) void bwd_gemm_kernel(
     }
 }
 
-// ---------------------------------------------------------------- transposes
-// koff[e] = sum over earlier experts of their row counts rounded up to 64.
-__global__ void padded_offsets_kernel(const int32_t *__restrict__ offsets, int32_t *__restrict__ koff,
-                                      int E)
+// ---------------------------------------------------------------- weight gradient, row-major operands
+// C[e][m, n] = sum over the rows r of expert e of A[r, m] B[r, n]: both operands are stored
+// with the contraction index (the row) as the SLOW one.  The tiles go to LDS as they are --
+// 64 rows x 128 columns, 16-byte vectors -- and the MFMA fragments (eight consecutive rows for
+// one column per lane) come out of LDS through gfx950's transposing 64-bit read, which hands
+// each lane of a 16-lane group four consecutive ROWS of one column: lane i of the group points
+// at row i / 4, columns 4 (i % 4) .. + 3, and receives rows 0 .. 3 of column i.  The 64-byte
+// pieces of a row are XOR-swizzled with the row number so that the four rows a group reads
+// fall into different banks.  128 x 128 output tile, four wavefronts, the row-grouped GEMM's
+// software pipeline; rows beyond the expert's last one are zeroed in the last stage only.
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+__device__ __forceinline__ u32x2 lds_read_tr16(const uint16_t *p)
 {
-    const int e = threadIdx.x;
-    int incl = e < E ? (offsets[e + 1] - offsets[e] + 63) / 64 * 64 : 0;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int v = __shfl_up(incl, d);
-        if (e >= d) incl += v;
-    }
-    if (e < E) koff[e + 1] = incl;
-    if (e == 0) koff[0] = 0;
+    const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4 *)(p));
+    return __builtin_bit_cast(u32x2, v);
 }
 
-// out[m][koff[e] + i] = in[offsets[e] + i][m] for i < rows of expert e, 0 for the padding;
-// one block per 64 padded rows x 64 columns, through LDS, 16 bytes per lane on both sides
-// (M is a multiple of 8).
-// ACT >= 0: `in` holds fp16 pre-activations and the copy is act(in) rounded to bf16.
-template <int ACT>
-__global__ __launch_bounds__(256) void transpose_rows_kernel(
-    const uint16_t *__restrict__ in, uint16_t *__restrict__ out, const int32_t *__restrict__ offsets,
-    const int32_t *__restrict__ koff, int E, int M, int lda)
+// AF16: A holds fp16 values (the forward's hidden activations); they are rounded to bf16 on
+// their way into LDS (two conversions to fp32 and one packed conversion per pair).
+__device__ __forceinline__ uint32_t f16x2_to_bf16x2(uint32_t w)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t tile[64][72];   // [column][row]
-    const int kb = blockIdx.x * 64;
-    if (kb >= koff[E]) return;
-    int e = 0;
-    while (e + 1 < E && koff[e + 1] <= kb) ++e;
-    const int r_base = offsets[e] + (kb - koff[e]);
-    const int r_end = offsets[e + 1];
-    const int m0 = blockIdx.y * 64;
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-        const int v = threadIdx.x + pass * 256;
-        const int rr = v / 8, c8 = (v % 8) * 8;
-        u32x4 q = {0u, 0u, 0u, 0u};
-        if (r_base + rr < r_end && m0 + c8 < M)
-            q = *reinterpret_cast<const u32x4 *>(in + static_cast<size_t>(r_base + rr) * M + m0 + c8);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            uint16_t lo = static_cast<uint16_t>(q[i] & 0xFFFFu), hi = static_cast<uint16_t>(q[i] >> 16);
-            if constexpr (ACT >= 0) {
-                lo = f32_to_bf16(act_value<ACT>(static_cast<float>(__builtin_bit_cast(_Float16, lo))));
-                hi = f32_to_bf16(act_value<ACT>(static_cast<float>(__builtin_bit_cast(_Float16, hi))));
-            }
-            tile[c8 + 2 * i][rr] = lo;
-            tile[c8 + 2 * i + 1][rr] = hi;
-        }
+    typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    const f16x2 hv = __builtin_bit_cast(f16x2, w);
+    bf16x2 b;
+    b[0] = static_cast<__bf16>(static_cast<float>(hv[0]));
+    b[1] = static_cast<__bf16>(static_cast<float>(hv[1]));
+    return __builtin_bit_cast(uint32_t, b);
+}
+
+template <bool AF16>
+__global__ __launch_bounds__(256, 2) void wgrad_gemm_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, float *__restrict__ C,
+    const int32_t *__restrict__ offsets, int E, int M, int N, int tiles_m, int tiles_n)
+{
+    constexpr int WM = 2, TM = 2, TN = 2, NT = 256;     // 2 x 2 wavefronts of 64 x 64
+    constexpr int kTile = 128, kRowB = kTile * 2;        // tile columns, bytes per LDS row
+    constexpr int kBuf = kBK * kTile;                    // elements per LDS buffer
+    constexpr int V = kBK * (kTile / 8) / NT;            // 16-byte vectors per thread, stage, operand
+    int expert, m0, n0;
+    {
+        const int total = E * tiles_m * tiles_n;
+        const int per_xcd = (total + 7) / 8;
+        const int slot = blockIdx.x / 8;
+        const int idx = (blockIdx.x % 8) * per_xcd + slot;
+        if (slot >= per_xcd || idx >= total) return;
+        expert = idx / (tiles_m * tiles_n);
+        const int rem = idx % (tiles_m * tiles_n);
+        m0 = (rem / tiles_n) * kTile;
+        n0 = (rem % tiles_n) * kTile;
     }
-    __syncthreads();
+    const int r0 = offsets[expert], r1 = offsets[expert + 1];
+    const int KT = (r1 - r0 + kBK - 1) / kBK;
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    uint16_t *As = smem;                 // [2][kBK][kTile], swizzled
+    uint16_t *Bs = smem + 2 * kBuf;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM;
+
+    f32x16 acc[TN][TM];
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-        const int v = threadIdx.x + pass * 256;
-        const int mm = v / 8, r8 = (v % 8) * 8;
-        if (m0 + mm < M)
-            *reinterpret_cast<u32x4 *>(out + static_cast<size_t>(m0 + mm) * lda + kb + r8) =
-                *reinterpret_cast<const u32x4 *>(&tile[mm][r8]);
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    if (KT > 0) {
+        // staging: vector v = tid + 256 q is row v / 16, columns 8 (v % 16) .. + 7 of the tile
+        int st_row[V], st_off[V];
+        size_t a_col[V], b_col[V];
+        const uint16_t *a_ptr[V], *b_ptr[V];
+#pragma unroll
+        for (int q = 0; q < V; ++q) {
+            const int v = tid + NT * q;
+            const int k = v >> 4, c16 = v & 15;
+            st_row[q] = k;
+            st_off[q] = (k * kRowB + (((c16 >> 2) ^ (k & 3)) << 6) + ((c16 & 3) << 4)) >> 1;   // elements
+            a_col[q] = static_cast<size_t>(min(m0 + c16 * 8, M - 8));
+            b_col[q] = static_cast<size_t>(min(n0 + c16 * 8, N - 8));
+            a_ptr[q] = A + static_cast<size_t>(r0 + k) * M + a_col[q];
+            b_ptr[q] = B + static_cast<size_t>(r0 + k) * N + b_col[q];
+        }
+        const size_t a_step = static_cast<size_t>(kBK) * M, b_step = static_cast<size_t>(kBK) * N;
+        u32x4 a_reg[V], b_reg[V], a_reg2[V], b_reg2[V];
+        u32x4 bf[2][TN], af[2][TM];
+        // fragment addresses: lane = 16 g + i reads row 8 (g / 2) + i / 4 (+ 4 for the upper
+        // half) of the 16-row step, columns 16 (g % 2) + 4 (i % 4) .. + 3 of the 32-column sub-tile
+        const int fi = lane & 15, fg = lane >> 4;
+        const int frow = 8 * (fg >> 1) + (fi >> 2);
+        const int fcol = 16 * (fg & 1) + 4 * (fi & 3);
+// Stages are loaded in ascending order: the pointers walk 64 rows per call; only a stage that
+// reaches past the expert's last row (the last one) clamps its rows and zeroes the surplus.
+#define WG_LOADG(kt_, AR, BR)                                                                   \
+    {                                                                                           \
+        const int rbase_ = r0 + (kt_) * kBK;                                                    \
+        if (rbase_ + kBK <= r1) {                                                               \
+            _Pragma("unroll") for (int q = 0; q < V; ++q)                                       \
+            {                                                                                   \
+                AR[q] = *reinterpret_cast<const u32x4 *>(a_ptr[q]);                             \
+                BR[q] = *reinterpret_cast<const u32x4 *>(b_ptr[q]);                             \
+                a_ptr[q] += a_step;                                                             \
+                b_ptr[q] += b_step;                                                             \
+            }                                                                                   \
+        } else {                                                                                \
+            _Pragma("unroll") for (int q = 0; q < V; ++q)                                       \
+            {                                                                                   \
+                const int row_ = rbase_ + st_row[q];                                            \
+                const size_t at_ = static_cast<size_t>(min(row_, r1 - 1));                      \
+                AR[q] = *reinterpret_cast<const u32x4 *>(A + at_ * M + a_col[q]);               \
+                BR[q] = *reinterpret_cast<const u32x4 *>(B + at_ * N + b_col[q]);               \
+                if (row_ >= r1) {                                                               \
+                    AR[q] = (u32x4){0u, 0u, 0u, 0u};                                            \
+                    BR[q] = (u32x4){0u, 0u, 0u, 0u};                                            \
+                }                                                                               \
+            }                                                                                   \
+        }                                                                                       \
+    }
+#define WG_STOREL(buf, AR, BR)                                                                  \
+    {                                                                                           \
+        _Pragma("unroll") for (int q = 0; q < V; ++q)                                           \
+        {                                                                                       \
+            u32x4 av_ = AR[q];                                                                  \
+            if constexpr (AF16)                                                                 \
+                av_ = (u32x4){f16x2_to_bf16x2(av_[0]), f16x2_to_bf16x2(av_[1]),                 \
+                              f16x2_to_bf16x2(av_[2]), f16x2_to_bf16x2(av_[3])};                \
+            *reinterpret_cast<u32x4 *>(As + (buf) * kBuf + st_off[q]) = av_;                    \
+            *reinterpret_cast<u32x4 *>(Bs + (buf) * kBuf + st_off[q]) = BR[q];                  \
+        }                                                                                       \
+    }
+// eight consecutive rows of one column per lane: two transposing reads, four rows each
+#define WG_FRAG(dst, base, cb, ks)                                                              \
+    {                                                                                           \
+        const int col_ = (cb) + fcol;                                                           \
+        const int k_ = (ks) * 16 + frow;                                                        \
+        const int lo_ = (k_ * kRowB + (((col_ >> 5) ^ (k_ & 3)) << 6) + ((col_ & 31) << 1)) >> 1; \
+        const u32x2 l_ = lds_read_tr16((base) + lo_);                                           \
+        const u32x2 h_ = lds_read_tr16((base) + lo_ + 4 * kTile);                               \
+        dst = (u32x4){l_[0], l_[1], h_[0], h_[1]};                                              \
+    }
+#define WG_READF(slot_, buf, ks)                                                                \
+    {                                                                                           \
+        _Pragma("unroll") for (int i = 0; i < TN; ++i)                                          \
+            WG_FRAG(bf[slot_][i], Bs + (buf) * kBuf, (wn * TN + i) * 32, ks)                    \
+        _Pragma("unroll") for (int j = 0; j < TM; ++j)                                          \
+            WG_FRAG(af[slot_][j], As + (buf) * kBuf, (wm * TM + j) * 32, ks)                    \
+    }
+#define WG_MMA(slot_)                                                                           \
+    {                                                                                           \
+        _Pragma("unroll") for (int j = 0; j < TM; ++j)                                          \
+            _Pragma("unroll") for (int i = 0; i < TN; ++i)                                      \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                            \
+                    __builtin_bit_cast(bf16x8, bf[slot_][i]),                                   \
+                    __builtin_bit_cast(bf16x8, af[slot_][j]), acc[i][j], 0, 0, 0);              \
+    }
+#define WG_STAGE(buf, AR, BR)                                                                   \
+    {                                                                                           \
+        const bool next1 = kt + 1 < KT, next3 = kt + 3 < KT;                                    \
+        if (next1) WG_STOREL(buf ^ 1, AR, BR)                                                   \
+        if (next3) WG_LOADG(kt + 3, AR, BR)                                                     \
+        WG_READF(1, buf, 1)                                                                     \
+        WG_MMA(0)                                                                               \
+        WG_READF(0, buf, 2)                                                                     \
+        WG_MMA(1)                                                                               \
+        WG_READF(1, buf, 3)                                                                     \
+        WG_MMA(0)                                                                               \
+        __syncthreads();                                                                        \
+        __builtin_amdgcn_sched_barrier(0);                                                      \
+        if (next1) WG_READF(0, buf ^ 1, 0)                                                      \
+        WG_MMA(1)                                                                               \
+    }
+        WG_LOADG(0, a_reg, b_reg)
+        WG_STOREL(0, a_reg, b_reg)
+        if (KT > 1) WG_LOADG(1, a_reg, b_reg)
+        if (KT > 2) WG_LOADG(2, a_reg2, b_reg2)
+        __syncthreads();
+        WG_READF(0, 0, 0)
+        int kt = 0;
+        for (; kt + 1 < KT; kt += 2) {
+            WG_STAGE(0, a_reg, b_reg)
+            ++kt;
+            WG_STAGE(1, a_reg2, b_reg2)
+            --kt;
+        }
+        if (kt < KT) WG_STAGE(0, a_reg, b_reg)
+#undef WG_STAGE
+#undef WG_LOADG
+#undef WG_STOREL
+#undef WG_FRAG
+#undef WG_READF
+#undef WG_MMA
+    }
+
+    // acc[i][j][4*g + c]: column n0 + (wn*TN + i)*32 + 8*g + 4*(lane/32) + c,
+    //                     row m0 + (wm*TM + j)*32 + lane%32
+    float *Ce = C + static_cast<size_t>(expert) * M * N;
+    const int fr = lane & 31;
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int m = m0 + (wm * TM + j) * 32 + fr;
+        if (m >= M) continue;
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + (wn * TN + i) * 32 + 8 * g + 4 * (lane >> 5);
+                if (n >= N) continue;
+                *reinterpret_cast<float4 *>(Ce + static_cast<size_t>(m) * N + n) =
+                    make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
+                                acc[i][j][4 * g + 3]);
+            }
+        }
     }
 }
 
@@ -539,10 +675,8 @@ struct BwdWorkspace {
     _Float16 *P;              // [R][h]
     uint16_t *Hb, *dye, *dP;  // [R][h], [R][d], [R][h]
     float *dxe;               // [R][d]
-    int32_t *koff;            // [E+1]
-    uint16_t *HT, *dPT, *dyeT, *xeT;   // [h][lda], [h][lda], [d][lda], [d][lda]
     float *dz, *partial;      // [T][E], [splits][d][E]
-    int lda, splits, per_split;
+    int splits, per_split;
     size_t bytes;
 };
 
@@ -583,12 +717,6 @@ void layout_bwd(const moe_shape &s, void *base, BwdWorkspace *w)
     w->dye = reinterpret_cast<uint16_t *>(take(Rd * 2));
     w->dP = reinterpret_cast<uint16_t *>(take(Rh * 2));
     w->dxe = reinterpret_cast<float *>(take(Rd * 4));
-    w->koff = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * (s.E + 1)));
-    w->lda = static_cast<int>((R + 63) / 64 * 64 + 64 * s.E);
-    w->HT = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(s.d_ff) * w->lda * 2));
-    w->dPT = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(s.d_ff) * w->lda * 2));
-    w->dyeT = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(s.d_model) * w->lda * 2));
-    w->xeT = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(s.d_model) * w->lda * 2));
     w->dz = reinterpret_cast<float *>(take(static_cast<size_t>(s.T) * s.E * 4));
     w->splits = std::max(1, std::min(32, (s.T + 127) / 128));
     w->per_split = (s.T + w->splits - 1) / w->splits;
@@ -605,37 +733,32 @@ bool supported(const moe_shape *s)
     return s->d_model % 8 == 0 && s->d_ff % 8 == 0;
 }
 
-template <int MODE, int EPI, int ACT, bool KTAIL, int WN>
+template <int EPI, int ACT, bool KTAIL, int WN>
 void launch_gemm_k(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, const WorkItem *items,
-                   const int32_t *nitems, const int32_t *koff, int E, int M, int N, int K,
-                   int grid_items, int stage, hipStream_t st)
+                   const int32_t *nitems, int N, int K, int grid_items, int stage, hipStream_t st)
 {
-    auto kern = bwd_gemm_kernel<MODE, EPI, ACT, KTAIL, WN>;
+    auto kern = bwd_gemm_kernel<EPI, ACT, KTAIL, WN>;
     constexpr size_t kGemmLds = gemm_lds(WN);
-    constexpr int kBN = 64 * WN;
     static PerDeviceOnce once;   // raising the dynamic LDS limit: once per kernel and device
     if (once.first()) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                   hipFuncAttributeMaxDynamicSharedMemorySize,
                                   static_cast<int>(kGemmLds));
     }
-    const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
     const int grid = static_cast<int>(align_up(static_cast<size_t>(grid_items), 8));
     hipEvent_t t0, t1;
     prof_kernel_events(stage, &t0, &t1);
     hipExtLaunchKernelGGL(kern, dim3(grid), dim3(128 * WN), kGemmLds, st, t0, t1, 0, A, W, C, P, items,
-                          nitems, koff, E, M, N, K, tiles_m, tiles_n);
+                          nitems, N, K);
 }
 
-template <int MODE, int EPI, int ACT>
+template <int EPI, int ACT>
 void launch_gemm(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, const WorkItem *items,
-                 const int32_t *nitems, const int32_t *koff, int E, int M, int N, int K, int bn,
-                 int grid_items, int stage, hipStream_t st)
+                 const int32_t *nitems, int N, int K, int bn, int grid_items, int stage, hipStream_t st)
 {
 #define MOE_BWD_GEMM(KTAIL_, WN_)                                                                 \
-    launch_gemm_k<MODE, EPI, ACT, KTAIL_, WN_>(A, W, C, P, items, nitems, koff, E, M, N, K,       \
-                                               grid_items, stage, st)
-    const bool tail = MODE == 0 && K % kBK != 0;
+    launch_gemm_k<EPI, ACT, KTAIL_, WN_>(A, W, C, P, items, nitems, N, K, grid_items, stage, st)
+    const bool tail = K % kBK != 0;
     if (bn == 256) {
         if (tail) MOE_BWD_GEMM(true, 4); else MOE_BWD_GEMM(false, 4);
     } else {
@@ -644,54 +767,61 @@ void launch_gemm(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, con
 #undef MOE_BWD_GEMM
 }
 
+// dW[e] [M][N] = A[rows of e]^T B[rows of e] from row-major operands
+template <bool AF16>
+void launch_wgrad(const uint16_t *A, const uint16_t *B, float *C, const int32_t *offsets, int E, int M,
+                  int N, int stage, hipStream_t st)
+{
+    constexpr size_t kLds = 2 * 2 * kBK * 128 * sizeof(uint16_t);
+    auto kern = wgrad_gemm_kernel<AF16>;
+    static PerDeviceOnce once;
+    if (once.first()) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLds));
+    }
+    const int tiles_m = (M + 127) / 128, tiles_n = (N + 127) / 128;
+    const int grid = static_cast<int>(align_up(static_cast<size_t>(E) * tiles_m * tiles_n, 8));
+    hipEvent_t t0, t1;
+    prof_kernel_events(stage, &t0, &t1);
+    hipExtLaunchKernelGGL(kern, dim3(grid), dim3(256), kLds, st, t0, t1, 0, A, B, C, offsets, E, M, N,
+                          tiles_m, tiles_n);
+}
+
 template <int ACT>
 moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, const float *bias,
                       int bias_stride, const uint16_t *W1, const uint16_t *W2, const uint16_t *W1p,
                       const int32_t *expert_idx, const float *gate, const int32_t *offsets,
                       const int32_t *slot_of, const int32_t *src_of, const uint16_t *xe,
-                      const float *ye, const _Float16 *pre, const float *dy, float *dx, float *dWg,
+                      const float *ye, const _Float16 *pre, const _Float16 *hid, const float *dy,
+                      float *dx, float *dWg,
                       float *dW1, float *dW2, float *dgate, const BwdWorkspace &w, hipStream_t st)
 {
     const int T = s.T, d = s.d_model, h = s.d_ff, E = s.E, k = s.k;
     const int R = static_cast<int>(moe_max_rows(&s));
-    // work lists of the row-grouped GEMMs (one chunk) and the padded row offsets
+    // work lists of the row-grouped GEMMs (one chunk)
     moe_status rc = launch_items(s, 1, offsets, src_of, w.lists, st);
     if (rc != MOE_OK) return rc;
-    hipLaunchKernelGGL(padded_offsets_kernel, dim3(1), dim3(kWave), 0, st, offsets, w.koff, E);
     hipLaunchKernelGGL(combine_bwd_kernel, dim3(ceil_div(T, 4)), dim3(256), 0, st, dy, ye, slot_of,
                        gate, w.dye, dgate, T, d, k, R);
     const GemmPlan &g0 = w.lists.gp[0], &g1 = w.lists.gp[1];
-    // P = xe W1 (fp16), Hb = act(P) (bf16) -- unless the forward kept P
+    // P = xe W1 (fp16), Hb = act(P) (bf16) -- unless the forward kept P and its hidden activations
     _Float16 *P = pre != nullptr ? const_cast<_Float16 *>(pre) : w.P;
     if (pre == nullptr)
-        launch_gemm<0, 1, ACT>(xe, W1p, w.Hb, w.P, w.lists.items[0], w.lists.nitems[0], nullptr, E, 0,
-                               h, d, g0.bn, g0.max_items, kStageBwdRecompute, st);
+        launch_gemm<1, ACT>(xe, W1p, w.Hb, w.P, w.lists.items[0], w.lists.nitems[0], h, d, g0.bn,
+                            g0.max_items, kStageBwdRecompute, st);
     // dP = (dye W2^T) * act'(P): W2 [E][h][d] is already "rows n = h, contraction d contiguous"
-    launch_gemm<0, 2, ACT>(w.dye, W2, w.dP, P, w.lists.items[0], w.lists.nitems[0], nullptr, E, 0,
-                           h, d, g0.bn, g0.max_items, kStageBwdDP, st);
+    launch_gemm<2, ACT>(w.dye, W2, w.dP, P, w.lists.items[0], w.lists.nitems[0], h, d, g0.bn,
+                        g0.max_items, kStageBwdDP, st);
     // dxe = dP W1^T: W1 [E][d][h] is "rows n = d, contraction h contiguous"
-    launch_gemm<0, 0, ACT>(w.dP, W1, w.dxe, nullptr, w.lists.items[1], w.lists.nitems[1], nullptr, E,
-                           0, d, h, g1.bn, g1.max_items, kStageBwdDxe, st);
-    // transposed, per-expert zero-padded copies for the weight gradients
-    const dim3 tb(256);
-    const int kblocks = w.lda / 64;
-    if (pre != nullptr)   // act(P) is formed on the way
-        hipLaunchKernelGGL(transpose_rows_kernel<ACT>, dim3(kblocks, ceil_div(h, 64)), tb, 0, st,
-                           reinterpret_cast<const uint16_t *>(pre), w.HT, offsets, w.koff, E, h, w.lda);
+    launch_gemm<0, ACT>(w.dP, W1, w.dxe, nullptr, w.lists.items[1], w.lists.nitems[1], d, h, g1.bn,
+                        g1.max_items, kStageBwdDxe, st);
+    // dW2[e] [h][d] = act(P)^T dye ; dW1[e] [d][h] = xe^T dP, operands as they are
+    if (pre != nullptr)      // the forward's own hidden activations, fp16
+        launch_wgrad<true>(reinterpret_cast<const uint16_t *>(hid), w.dye, dW2, offsets, E, h, d,
+                           kStageBwdWgrad2, st);
     else
-        hipLaunchKernelGGL(transpose_rows_kernel<-1>, dim3(kblocks, ceil_div(h, 64)), tb, 0, st, w.Hb,
-                           w.HT, offsets, w.koff, E, h, w.lda);
-    hipLaunchKernelGGL(transpose_rows_kernel<-1>, dim3(kblocks, ceil_div(h, 64)), tb, 0, st, w.dP, w.dPT,
-                       offsets, w.koff, E, h, w.lda);
-    hipLaunchKernelGGL(transpose_rows_kernel<-1>, dim3(kblocks, ceil_div(d, 64)), tb, 0, st, w.dye,
-                       w.dyeT, offsets, w.koff, E, d, w.lda);
-    hipLaunchKernelGGL(transpose_rows_kernel<-1>, dim3(kblocks, ceil_div(d, 64)), tb, 0, st, xe, w.xeT,
-                       offsets, w.koff, E, d, w.lda);
-    // dW2[e] [h][d] = Hb^T dye ; dW1[e] [d][h] = xe^T dP
-    launch_gemm<1, 0, ACT>(w.HT, w.dyeT, dW2, nullptr, nullptr, nullptr, w.koff, E, h, d, w.lda, 128,
-                           E * ceil_div(h, kBM) * ceil_div(d, 128), kStageBwdWgrad2, st);
-    launch_gemm<1, 0, ACT>(w.xeT, w.dPT, dW1, nullptr, nullptr, nullptr, w.koff, E, d, h, w.lda, 128,
-                           E * ceil_div(d, kBM) * ceil_div(h, 128), kStageBwdWgrad1, st);
+        launch_wgrad<false>(w.Hb, w.dye, dW2, offsets, E, h, d, kStageBwdWgrad2, st);
+    launch_wgrad<false>(xe, w.dP, dW1, offsets, E, d, h, kStageBwdWgrad1, st);
     // gate: dz, dx, dWg
     int EP = 1;
     while (EP < E) EP <<= 1;
@@ -734,8 +864,9 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
                               const int32_t *expert_idx, const float *gate,
                               const int32_t *offsets, const int32_t *slot_of,
                               const int32_t *src_of, const void *xe, const float *ye,
-                              const void *pre, const float *dy, float *dx, float *dWg, float *dW1,
-                              float *dW2, float *dgate, void *workspace, void *stream)
+                              const void *pre, const void *hid, const float *dy, float *dx,
+                              float *dWg, float *dW1, float *dW2, float *dgate, void *workspace,
+                              void *stream)
 {
     if (!supported(s)) {
         set_error("moe_layer_backward: bf16 layers without top-k renormalisation only, E <= %d, "
@@ -754,14 +885,16 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
             return MOE_EINVAL;
         }
     }
-    if ((reinterpret_cast<uintptr_t>(pre) & 15u) != 0) {
-        set_error("moe_layer_backward: pre is not 16-byte aligned");
+    if (((reinterpret_cast<uintptr_t>(pre) | reinterpret_cast<uintptr_t>(hid)) & 15u) != 0 ||
+        (pre == nullptr) != (hid == nullptr)) {
+        set_error("moe_layer_backward: pre and hid come together (both or neither), 16-byte aligned");
         return MOE_EINVAL;
     }
     BwdWorkspace w;
     layout_bwd(*s, workspace, &w);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const _Float16 *preh = static_cast<const _Float16 *>(pre);
+    const _Float16 *hidh = static_cast<const _Float16 *>(hid);
     const uint16_t *xb = static_cast<const uint16_t *>(x);
     const float *Wgf = static_cast<const float *>(Wgp);
     const uint16_t *W1b = static_cast<const uint16_t *>(W1), *W2b = static_cast<const uint16_t *>(W2);
@@ -769,8 +902,8 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
 #define MOE_BWD_CASE(ACT)                                                                         \
     case ACT:                                                                                     \
         return backward_t<ACT>(*s, xb, Wgf, gate_bias, bias_token_stride, W1b, W2b, W1pb,         \
-                               expert_idx, gate, offsets, slot_of, src_of, xeb, ye, preh, dy, dx, \
-                               dWg, dW1, dW2, dgate, w, st);
+                               expert_idx, gate, offsets, slot_of, src_of, xeb, ye, preh, hidh,   \
+                               dy, dx, dWg, dW1, dW2, dgate, w, st);
     switch (s->act) {
         MOE_BWD_CASE(MOE_ACT_GELU_ERF)
         MOE_BWD_CASE(MOE_ACT_GELU_TANH)

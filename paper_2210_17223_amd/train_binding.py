@@ -19,9 +19,9 @@ def _lib():
         L.moe_backward_workspace_bytes.restype = C.c_size_t
         L.moe_backward_workspace_bytes.argtypes = [sp]
         L.moe_layer_backward.restype = C.c_int
-        L.moe_layer_backward.argtypes = [sp, vp, vp, vp, i32] + [vp] * 19
+        L.moe_layer_backward.argtypes = [sp, vp, vp, vp, i32] + [vp] * 20
         L.moe_layer_forward_keep.restype = C.c_int
-        L.moe_layer_forward_keep.argtypes = [sp, vp, vp, vp, i32] + [vp] * 16
+        L.moe_layer_forward_keep.argtypes = [sp, vp, vp, vp, i32] + [vp] * 17
         _ready = True
     return L
 
@@ -36,7 +36,7 @@ def _need(t: torch.Tensor, dtype, numel: int, name: str) -> None:
 
 
 def moe_layer_forward_keep(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1p, b1, W2p, b2, expert_idx,
-                           gate, counts, offsets, slot_of, src_of, xe, ye, pre, y, workspace,
+                           gate, counts, offsets, slot_of, src_of, xe, ye, pre, hid, y, workspace,
                            stream=None) -> None:
     rows = moe_max_rows(s)
     T, d, E, h, k = s.T, s.d_model, s.E, s.d_ff, s.k
@@ -50,17 +50,18 @@ def moe_layer_forward_keep(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1p, 
     _need(xe, torch.bfloat16, rows * d, "xe")
     _need(ye, torch.float32, rows * d, "ye")
     _need(pre, torch.float16, rows * h, "pre")
+    _need(hid, torch.float16, rows * h, "hid")
     _need(y, torch.float32, T * d, "y")
     _need(workspace, torch.uint8, moe_workspace_bytes(s, 1), "workspace")
     _check(_lib().moe_layer_forward_keep(C.byref(s), _ptr(x), _ptr(Wgp), _ptr(gate_bias),
                                          bias_token_stride, _ptr(W1p), _ptr(b1), _ptr(W2p), _ptr(b2),
                                          _ptr(expert_idx), _ptr(gate), _ptr(counts), _ptr(offsets),
                                          _ptr(slot_of), _ptr(src_of), _ptr(xe), _ptr(ye), _ptr(pre),
-                                         _ptr(y), _ptr(workspace), _stream(stream)))
+                                         _ptr(hid), _ptr(y), _ptr(workspace), _stream(stream)))
 
 
 def moe_layer_backward(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1, W2, W1p, expert_idx, gate,
-                       offsets, slot_of, src_of, xe, ye, pre, dy, dx, dWg, dW1, dW2, dgate, workspace,
+                       offsets, slot_of, src_of, xe, ye, pre, hid, dy, dx, dWg, dW1, dW2, dgate, workspace,
                        stream=None) -> None:
     rows = moe_max_rows(s)
     T, d, E, h, k = s.T, s.d_model, s.E, s.d_ff, s.k
@@ -76,6 +77,8 @@ def moe_layer_backward(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1, W2, W
     _need(ye, torch.float32, rows * d, "ye")
     if pre is not None:
         _need(pre, torch.float16, rows * h, "pre")
+    if hid is not None:
+        _need(hid, torch.float16, rows * h, "hid")
     _need(dy, torch.float32, T * d, "dy")
     _need(dx, torch.float32, T * d, "dx")
     _need(dWg, torch.float32, d * E, "dWg")
@@ -86,5 +89,5 @@ def moe_layer_backward(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1, W2, W
     _check(_lib().moe_layer_backward(C.byref(s), _ptr(x), _ptr(Wgp), _ptr(gate_bias), bias_token_stride,
                                      _ptr(W1), _ptr(W2), _ptr(W1p), _ptr(expert_idx), _ptr(gate),
                                      _ptr(offsets), _ptr(slot_of), _ptr(src_of), _ptr(xe), _ptr(ye),
-                                     _ptr(pre), _ptr(dy), _ptr(dx), _ptr(dWg), _ptr(dW1), _ptr(dW2), _ptr(dgate),
+                                     _ptr(pre), _ptr(hid), _ptr(dy), _ptr(dx), _ptr(dWg), _ptr(dW1), _ptr(dW2), _ptr(dgate),
                                      _ptr(workspace), _stream(stream)))

@@ -33,7 +33,7 @@ def run_backward(li, act="gelu", keep=False):
     L = DeviceLayer(li, s)
     L.layer(1)
     b = L.b
-    pre = None
+    pre = hid = None
     if keep:
         plain = {n: b[n].clone() for n in ("expert_idx", "gate", "counts", "offsets", "slot_of", "y")}
         A = int(b["offsets"][-1])
@@ -41,9 +41,10 @@ def run_backward(li, act="gelu", keep=False):
         for n in ("expert_idx", "gate", "counts", "offsets", "slot_of", "src_of", "y", "ye"):
             b[n].fill_(-3)
         pre = torch.full((moe.moe_max_rows(s) * li.h,), 9.0, dtype=torch.float16, device=DEV)
+        hid = torch.full_like(pre, 5.0)
         moe.moe_layer_forward_keep(s, L.x, b["Wgp"], L.bias, L.bias_stride, b["W1p"], None, b["W2p"], None,
                                    b["expert_idx"], b["gate"], b["counts"], b["offsets"], b["slot_of"],
-                                   b["src_of"], b["xe"], b["ye"], pre, b["y"], b["workspace"])
+                                   b["src_of"], b["xe"], b["ye"], pre, hid, b["y"], b["workspace"])
         torch.cuda.synchronize()
         # same outputs as the plain layer call, bit for bit
         for n, want in plain.items():
@@ -55,6 +56,12 @@ def run_backward(li, act="gelu", keep=False):
         rms = float(np.sqrt(np.mean(o_pre ** 2)))
         assert np.abs(got_pre - o_pre).max() <= 2.0 ** -10 * np.abs(o_pre).max() + 1e-4 * rms
         assert (pre[A * li.h:] == 9.0).all()              # rows beyond offsets[E] untouched
+        # kept hidden activations: act of the fp32 accumulator, rounded to fp16
+        from oracle import bwd_oracle as _bo
+        o_hid = _bo.act_and_derivative(o_pre, act)[0]
+        got_hid = hid[:A * li.h].float().cpu().numpy().reshape(A, li.h)
+        assert np.abs(got_hid - o_hid).max() <= 2.0 ** -10 * np.abs(o_hid).max() + 1e-4 * rms
+        assert (hid[A * li.h:] == 5.0).all()
     prng = np.random.Generator(np.random.PCG64(77))
     dy = prng.standard_normal((li.T, li.d)).astype(np.float32)
     W1, W2 = upload(li.W1, "bf16"), upload(li.W2, "bf16")
@@ -63,7 +70,7 @@ def run_backward(li, act="gelu", keep=False):
              dW2=f32(li.E * li.d * li.h), dgate=f32(li.T * li.k))
     ws = torch.empty(moe.moe_backward_workspace_bytes(s), dtype=torch.uint8, device=DEV)
     moe.moe_layer_backward(s, L.x, b["Wgp"], L.bias, L.bias_stride, W1, W2, b["W1p"], b["expert_idx"],
-                           b["gate"], b["offsets"], b["slot_of"], b["src_of"], b["xe"], b["ye"], pre,
+                           b["gate"], b["offsets"], b["slot_of"], b["src_of"], b["xe"], b["ye"], pre, hid,
                            torch.from_numpy(dy).to(DEV), g["dx"], g["dWg"], g["dW1"], g["dW2"],
                            g["dgate"], ws)
     torch.cuda.synchronize()

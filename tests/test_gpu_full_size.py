@@ -148,16 +148,17 @@ def test_backward_at_the_bench_configuration():
     L = DeviceLayer(li, s)
     b = L.b
     pre = torch.empty(moe.moe_max_rows(s) * h, dtype=torch.float16, device="cuda:0")
+    hid = torch.empty_like(pre)
     moe.moe_layer_forward_keep(s, L.x, b["Wgp"], None, 0, b["W1p"], None, b["W2p"], None, b["expert_idx"],
                                b["gate"], b["counts"], b["offsets"], b["slot_of"], b["src_of"], b["xe"],
-                               b["ye"], pre, b["y"], b["workspace"])
+                               b["ye"], pre, hid, b["y"], b["workspace"])
     dy = np.random.Generator(np.random.PCG64(31)).standard_normal((T, d)).astype(np.float32)
     W1, W2 = upload(li.W1, "bf16"), upload(li.W2, "bf16")
     f32 = lambda n: torch.full((n,), 3.0, dtype=torch.float32, device="cuda:0")
     g = dict(dx=f32(T * d), dWg=f32(d * E), dW1=f32(E * d * h), dW2=f32(E * d * h), dgate=f32(T * k))
     ws = torch.empty(moe.moe_backward_workspace_bytes(s), dtype=torch.uint8, device="cuda:0")
     moe.moe_layer_backward(s, L.x, b["Wgp"], None, 0, W1, W2, b["W1p"], b["expert_idx"], b["gate"],
-                           b["offsets"], b["slot_of"], b["src_of"], b["xe"], b["ye"], pre,
+                           b["offsets"], b["slot_of"], b["src_of"], b["xe"], b["ye"], pre, hid,
                            torch.from_numpy(dy).to("cuda:0"), g["dx"], g["dWg"], g["dW1"], g["dW2"],
                            g["dgate"], ws)
     torch.cuda.synchronize()
