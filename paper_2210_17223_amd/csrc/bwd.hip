@@ -631,10 +631,16 @@ __global__ __launch_bounds__(256) void dwg_partial_kernel(
     for (int q = 0; q < EQ; ++q) acc[q] = 0.0f;
     for (int tb = t0; tb < t1; tb += 64) {
         __syncthreads();
-        for (int v = threadIdx.x; v < 64 * 64; v += 256) {
-            const int tt = v / 64, ii = v % 64;
-            xs[tt][ii] = (tb + tt < t1 && i0 + ii < d)
-                             ? bf16_to_f32(x[static_cast<size_t>(tb + tt) * d + i0 + ii]) : 0.0f;
+        for (int v = threadIdx.x; v < 64 * 8; v += 256) {          // eight columns per load
+            const int tt = v / 8, c8 = (v % 8) * 8;
+            u32x4 q = {0u, 0u, 0u, 0u};
+            if (tb + tt < t1 && i0 + c8 < d)
+                q = *reinterpret_cast<const u32x4 *>(x + static_cast<size_t>(tb + tt) * d + i0 + c8);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                xs[tt][c8 + 2 * c] = __uint_as_float(q[c] << 16);
+                xs[tt][c8 + 2 * c + 1] = __uint_as_float(q[c] & 0xFFFF0000u);
+            }
         }
         for (int v = threadIdx.x; v < 64 * EP; v += 256) {
             const int tt = v / EP, ee = v % EP;
