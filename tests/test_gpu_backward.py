@@ -142,6 +142,24 @@ def test_backward_with_empty_experts_and_gate_bias():
         assert not got["dW1"].reshape(li.W1.shape)[e].any()
 
 
+def test_kept_buffers_come_together():
+    li = wl.make_layer(wl.scaled("gpt2s_moe", T=64, d=64, h=64, E=4), seed=0)
+    s = shape_of(li)
+    L = DeviceLayer(li, s)
+    L.layer(1)
+    b = L.b
+    pre = torch.zeros(moe.moe_max_rows(s) * li.h, dtype=torch.float16, device=DEV)
+    W1, W2 = upload(li.W1, "bf16"), upload(li.W2, "bf16")
+    f32 = lambda n: torch.zeros(n, dtype=torch.float32, device=DEV)
+    ws = torch.empty(moe.moe_backward_workspace_bytes(s), dtype=torch.uint8, device=DEV)
+    for keep in ((pre, None), (None, pre)):
+        with pytest.raises(moe.MoeError):
+            moe.moe_layer_backward(s, L.x, b["Wgp"], None, 0, W1, W2, b["W1p"], b["expert_idx"], b["gate"],
+                                   b["offsets"], b["slot_of"], b["src_of"], b["xe"], b["ye"], keep[0], keep[1],
+                                   f32(li.T * li.d), f32(li.T * li.d), f32(li.d * li.E), f32(li.E * li.d * li.h),
+                                   f32(li.E * li.d * li.h), f32(li.T * li.k), ws)
+
+
 def test_refusals():
     li = wl.make_layer(wl.CONFIGS["tiny_fp32"], seed=0)
     assert moe.moe_backward_workspace_bytes(shape_of(li)) == 0          # fp32 layers: unsupported

@@ -89,6 +89,22 @@ def test_padded_layer_matches_the_oracle(name, n_micro):
     check_padded(li, L, s, p)
 
 
+def test_padded_layer_with_empty_experts_and_overflowing_ones():
+    cfg = wl.scaled("gpt2s_moe", T=600, d=128, h=256, E=8, k=2, cf=None)
+    li = wl.make_layer(cfg, seed=5)
+    bias = np.zeros(li.E, np.float32)
+    bias[[1, 6]] = 30.0                                  # every token picks experts 1 and 6 ...
+    li.gate_bias, li.bias_token_stride, li.C = bias, 0, 400      # ... which hold 400 of the 600
+    s = shape_of(li)
+    L = DeviceLayer(li, s)
+    for n_micro in (1, 5):
+        p = run_padded(L, s, n_micro)
+        check_padded(li, L, s, p)
+        counts = p["counts"].cpu().numpy()
+        assert sorted(np.nonzero(counts)[0]) == [1, 6] and (counts[[1, 6]] == 600).all()
+        assert (p["slot_of"].cpu().numpy() < 0).sum() == 2 * 200
+
+
 def test_padded_layer_with_as_many_micro_ops_as_slots_and_a_wide_link():
     li = wl.make_layer(wl.scaled("gpt2s_moe", T=96, d=64, h=128, E=4, k=2, cf=1.0), seed=2)
     s = shape_of(li)
