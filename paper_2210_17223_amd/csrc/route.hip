@@ -140,9 +140,9 @@ __global__ __launch_bounds__(256, 2) void route_kernel(
     // enough for two to cover the load latency
     constexpr int PD = TPL * EPL >= 4 ? 2 : 3;
     constexpr int UNR = PD == 2 ? 2 : 6;             // stages per unrolled trip: lcm(PD, 2)
-    // LDS reads hoisted ahead of the chain: a lane with one or two chains has nothing else to
-    // cover their latency with
-    constexpr int IU = TPL * EPL <= 2 ? 16 : 4;
+    // LDS reads this many four-column steps ahead of the chain, in a register ring: a lane with
+    // few chains has nothing else to cover their latency with
+    constexpr int PF = TPL + EPL <= 2 ? 8 : TPL + EPL <= 4 ? 4 : 0;
     constexpr int VE = 16 / sizeof(XT);              // elements per 16-byte vector
     constexpr int XRV = kKC / VE;                    // 16-byte vectors per token row per stage
     constexpr int WRV = kKC / 4;                     // ... per gate-matrix row per stage
@@ -226,7 +226,42 @@ __global__ __launch_bounds__(256, 2) void route_kernel(
                 if (s + PD < nstage) MOE_LOAD_STAGE(u % PD, (s + PD) * kKC)
                 const float *xrow = xs + buf * TB * kLDX + tg * kLDX;
                 const float *wrow = ws + buf * EP * kLDX + eg * kLDX;
-#pragma unroll IU
+                if constexpr (PF > 0) {
+                    // a ring of PF four-column steps of operands in registers: the reads of step
+                    // i + PF are issued right after step i's multiply-adds, so a read has PF
+                    // steps of the chain to arrive (left alone, the compiler keeps one step ahead)
+                    f32x4 xr[PF][TPL], wr[PF][EPL];
+#pragma unroll
+                    for (int p = 0; p < PF; ++p) {
+#pragma unroll
+                        for (int a = 0; a < TPL; ++a)
+                            xr[p][a] = *reinterpret_cast<const f32x4 *>(xrow + a * TG * kLDX + p * 4);
+#pragma unroll
+                        for (int b = 0; b < EPL; ++b)
+                            wr[p][b] = *reinterpret_cast<const f32x4 *>(wrow + b * NG * kLDX + p * 4);
+                    }
+#pragma unroll
+                    for (int i4 = 0; i4 < kKC / 4; ++i4) {
+                        const int slot = i4 % PF;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+#pragma unroll
+                            for (int a = 0; a < TPL; ++a)
+#pragma unroll
+                                for (int b = 0; b < EPL; ++b)
+                                    acc[a][b] = __builtin_fmaf(xr[slot][a][c], wr[slot][b][c], acc[a][b]);
+                        if (i4 + PF < kKC / 4) {
+#pragma unroll
+                            for (int a = 0; a < TPL; ++a)
+                                xr[slot][a] = *reinterpret_cast<const f32x4 *>(xrow + a * TG * kLDX + (i4 + PF) * 4);
+#pragma unroll
+                            for (int b = 0; b < EPL; ++b)
+                                wr[slot][b] = *reinterpret_cast<const f32x4 *>(wrow + b * NG * kLDX + (i4 + PF) * 4);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                } else {
+#pragma unroll 4
                 for (int i4 = 0; i4 < kKC / 4; ++i4) {
                     f32x4 xv[TPL], wv[EPL];
 #pragma unroll
@@ -242,6 +277,7 @@ __global__ __launch_bounds__(256, 2) void route_kernel(
 #pragma unroll
                             for (int b = 0; b < EPL; ++b)
                                 acc[a][b] = __builtin_fmaf(xv[a][c], wv[b][c], acc[a][b]);
+                }
                 }
             }
         }
