@@ -50,6 +50,8 @@ def main() -> int:
     ap.add_argument("--micro-mib", type=int, default=16,
                     help="with --comm: size of an allreduce micro-op in MiB")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a HIP graph (reported beside the eager figure)")
     ap.add_argument("--stages", action="store_true",
                     help="after the timed region, run extra steps with every stage timed")
     ap.add_argument("--cold-sets", type=int, default=4,
@@ -275,6 +277,23 @@ def main() -> int:
                    "count_min": int(min(c.min() for c in cnts)), "count_max": int(max(c.max() for c in cnts))},
         "roofline": roof,
     }
+
+    # ---- the same steps replayed from a HIP graph (launch overhead off the host) -----------
+    if args.graph and not args.offload:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(sets[0])
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        out["graph_replay"] = {"ms_per_step": g_ms, "value": l0.T * n_layers / (g_ms * 1e-3), "unit": "tokens/s",
+                               "note": "one step captured into a HIP graph and replayed; outputs are "
+                                       "bit-identical to the eager call (tests/test_gpu_graph.py)"}
 
     # ---- the same steps with cold caches -------------------------------------------------
     set_bytes = sum(L.bytes() for L in sets[0])
