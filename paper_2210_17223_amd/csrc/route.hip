@@ -312,6 +312,235 @@ __global__ __launch_bounds__(256, 2) void route_kernel(
     }
 }
 
+// The gate for problems with few chains (one chain per lane, T * EP of them): there the
+// chain of d dependent FMAs IS the time, so neither its operands nor the LDS pipe may make
+// it wait.
+//  * Operands: the tiles of a 64-column stage go from global memory straight into an LDS
+//    ring of kChainStages stages (gfx950's 16-byte load-to-LDS: a wavefront's 64 lanes fill
+//    1 KiB of consecutive LDS, so a stage is laid out in 1 KiB chunks and each lane fetches
+//    whatever belongs at its place), several stages ahead of the chain, with an exact count
+//    of the loads in flight; no registers, no LDS store phase, one barrier per stage.
+//  * LDS pipe: a lane that reads both of its operands from LDS moves 32 bytes per four FMAs,
+//    and the four wavefronts of a block then keep the pipe busier than the chains keep the
+//    ALUs.  So a row of 16 lanes is one expert and its lanes are 16 tokens: every lane reads
+//    its own token's 16 columns (storage type: 32 bytes of bf16), ONE 4-byte read per lane
+//    brings the row's 16 gate-matrix values, and each FMA takes its value from the lane
+//    that holds it through the DPP row broadcast -- about a third of the LDS traffic.
+//  * The 16-byte pieces of both tiles are XOR-swizzled with their row, so that the 16
+//    tokens (x) and the 4 experts (gate matrix) a wavefront reads at once fall into
+//    different banks.
+// Reads run two 16-column groups ahead of the chain, across stage boundaries (the barrier
+// that publishes stage s + 1 sits in the middle of stage s).
+// Shapes: d a multiple of 64, a stage of at most 8 KiB, EP * ceil(TB / 16) <= 16 rows.
+constexpr int kChainStages = 8;
+
+#define MOE_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+// acc += w[lane J of this lane's row of 16] * xv.  FIRST: w may just have been written.
+template <int J, bool FIRST>
+__device__ __forceinline__ void fmac_row_bcast(float &acc, float w, float xv)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    if constexpr (FIRST)
+        asm("s_nop 1\n\tv_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+            : "+v"(acc) : "v"(w), "v"(xv), "n"(J));
+    else
+        asm("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+            : "+v"(acc) : "v"(w), "v"(xv), "n"(J));
+#endif
+}
+
+template <typename XT>
+struct ChainGroup {                    // operands of 16 columns
+    static constexpr int XQ = 16 * sizeof(XT) / 16;      // 16-byte pieces of the token row
+    float w;
+    uint4 xq[XQ];
+};
+
+template <typename XT, int CPW>
+__global__ __launch_bounds__(256, 2) void route_chain_kernel(
+    const XT *__restrict__ x, const float *__restrict__ Wgp, const float *__restrict__ bias,
+    int bias_stride, int32_t *__restrict__ expert_idx, float *__restrict__ gate,
+    int32_t *__restrict__ seg_cnt, int T, int d, int dP, int E, int EP, int TB, int k, int renorm)
+{
+#if defined(__HIP_DEVICE_COMPILE__)   // (the host pass needs the launch stub only)
+    constexpr int NS = kChainStages;
+    constexpr int XROWB = kKC * static_cast<int>(sizeof(XT));     // bytes of a token row per stage
+    constexpr int WROWB = kKC * 4;                                // ... of a gate-matrix row
+    constexpr int XPIECES = XROWB / 16;                           // 8 (bf16) or 16 (fp32)
+    constexpr int XQ = ChainGroup<XT>::XQ;
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    char *ring = reinterpret_cast<char *>(smem);
+    float (*zs)[kMaxExperts + 1] = reinterpret_cast<float (*)[kMaxExperts + 1]>(smem);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // row of 16 lanes = (expert, sixteen tokens); lane of the row = token
+    const int TB16 = (TB + 15) >> 4;
+    const int row_e = (tid >> 4) / TB16, tok = ((tid >> 4) % TB16) * 16 + (tid & 15);
+    const bool active = row_e < EP && tok < TB;
+    const int eg = min(row_e, EP - 1), tg = min(tok, TB - 1);     // idle lanes repeat a chain
+    const int t0 = blockIdx.x * TB;
+    const int xbytes = (TB * XROWB + 1023) / 1024 * 1024;         // a stage: token rows, then
+    const int wbytes = (EP * WROWB + 1023) / 1024 * 1024;         // gate-matrix rows, in 1 KiB chunks
+    const int stage_bytes = xbytes + wbytes;
+    const int chunks = stage_bytes / 1024;
+    // where piece v of a row's 16-byte pieces sits: v ^ swizzle(row)
+    auto xswizzle = [](int row) { return sizeof(XT) == 2 ? ((row ^ (row >> 3)) & 7) : (row & 15); };
+
+    // this lane's CPW loads per stage: chunk wave + 4 j (surplus loads repeat the last chunk)
+    const char *gsrc[CPW];
+    int gstep[CPW], cbyte[CPW];
+#pragma unroll
+    for (int j = 0; j < CPW; ++j) {
+        const int c = min(wave + 4 * j, chunks - 1);
+        cbyte[j] = c * 1024;
+        const int p = c * 1024 + lane * 16;                       // this lane's place in the stage
+        if (p < xbytes) {
+            const int row = min(p / XROWB, TB - 1), vec = ((p % XROWB) / 16) ^ xswizzle(row);
+            gsrc[j] = reinterpret_cast<const char *>(x + static_cast<size_t>(min(t0 + row, T - 1)) * d) + vec * 16;
+            gstep[j] = XROWB;
+        } else {
+            const int q = p - xbytes;
+            const int row = min(q / WROWB, EP - 1), vec = ((q % WROWB) / 16) ^ (row & 15);
+            gsrc[j] = reinterpret_cast<const char *>(Wgp + static_cast<size_t>(row) * dP) + vec * 16;
+            gstep[j] = WROWB;
+        }
+    }
+    // The load is written out rather than taken from the compiler's builtin: behind the
+    // builtin every later LDS read is made to wait until NO load is in flight, which is the
+    // one thing this kernel must not do.  M0 = the wavefront's place in LDS; lane l lands at
+    // M0 + 16 l.  Completion is counted by hand below.
+    const uint32_t ring_lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(MOE_LDS_PTR(ring)));
+#define MOE_CHAIN_LOAD(s_)                                                                    \
+    {                                                                                         \
+        const uint32_t slot_ = ring_lds + ((s_) % NS) * stage_bytes;                          \
+        _Pragma("unroll") for (int j = 0; j < CPW; ++j) {                                     \
+            const char *g_ = gsrc[j] + static_cast<size_t>(s_) * gstep[j];                    \
+            const uint32_t m_ = __builtin_amdgcn_readfirstlane(slot_ + cbyte[j]);             \
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"    \
+                         ::"v"(g_), "s"(m_) : "memory", "m0");                                \
+        }                                                                                     \
+    }
+    // Stage s_ becomes readable: this wavefront's part of it has landed once at most the
+    // loads of the NS - 3 stages behind it are in flight; after the barrier everybody's has,
+    // and everybody has consumed stage s_ - 2, whose place the next loads take.  A plain
+    // s_barrier: __syncthreads() would first wait for ALL loads into LDS in flight.
+#define MOE_CHAIN_SYNC(s_)                                                                    \
+    {                                                                                         \
+        if ((s_) + NS - 3 <= nstage - 1)                                                      \
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * CPW) : "memory");             \
+        else                                                                                  \
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                  \
+        __builtin_amdgcn_s_barrier();                                                         \
+        asm volatile("" ::: "memory");                                                        \
+        if ((s_) - 2 + NS < nstage) MOE_CHAIN_LOAD((s_) - 2 + NS)                             \
+    }
+    const int nstage = d / kKC;                       // (columns past d meet zeros of the matrix)
+    for (int s = 0; s < NS - 2; ++s)
+        if (s < nstage) MOE_CHAIN_LOAD(s)
+
+    float acc = 0.0f;
+    const int xoff = tg * XROWB, xswz = xswizzle(tg);
+    const int woff = xbytes + eg * WROWB, wswz = eg & 15;
+    const int wl = tid & 15;                          // the gate-matrix column this lane fetches
+    ChainGroup<XT> grp[4];
+    // group g_ of stage s_: columns 16 g_ .. 16 g_ + 15
+#define MOE_CHAIN_READ(slot_, s_, g_)                                                         \
+    {                                                                                         \
+        const char *base_ = ring + ((s_) % NS) * stage_bytes;                                 \
+        grp[slot_].w = *reinterpret_cast<const float *>(                                      \
+            base_ + woff + ((((g_) * 4 + (wl >> 2)) ^ wswz) << 4) + ((wl & 3) << 2));         \
+        _Pragma("unroll") for (int q = 0; q < XQ; ++q)                                        \
+            grp[slot_].xq[q] = *reinterpret_cast<const uint4 *>(                              \
+                base_ + xoff + ((((g_) * XQ + q) ^ xswz) << 4));                              \
+    }
+    auto compute = [&](const ChainGroup<XT> &g) {
+        float xv[16];
+#pragma unroll
+        for (int q = 0; q < XQ; ++q) {
+            const uint32_t u[4] = {g.xq[q].x, g.xq[q].y, g.xq[q].z, g.xq[q].w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if constexpr (sizeof(XT) == 2) {
+                    xv[q * 8 + 2 * c] = __uint_as_float(u[c] << 16);
+                    xv[q * 8 + 2 * c + 1] = __uint_as_float(u[c] & 0xFFFF0000u);
+                } else {
+                    xv[q * 4 + c] = __uint_as_float(u[c]);
+                }
+            }
+        }
+        fmac_row_bcast<0, true>(acc, g.w, xv[0]);
+        fmac_row_bcast<1, false>(acc, g.w, xv[1]);
+        fmac_row_bcast<2, false>(acc, g.w, xv[2]);
+        fmac_row_bcast<3, false>(acc, g.w, xv[3]);
+        fmac_row_bcast<4, false>(acc, g.w, xv[4]);
+        fmac_row_bcast<5, false>(acc, g.w, xv[5]);
+        fmac_row_bcast<6, false>(acc, g.w, xv[6]);
+        fmac_row_bcast<7, false>(acc, g.w, xv[7]);
+        fmac_row_bcast<8, false>(acc, g.w, xv[8]);
+        fmac_row_bcast<9, false>(acc, g.w, xv[9]);
+        fmac_row_bcast<10, false>(acc, g.w, xv[10]);
+        fmac_row_bcast<11, false>(acc, g.w, xv[11]);
+        fmac_row_bcast<12, false>(acc, g.w, xv[12]);
+        fmac_row_bcast<13, false>(acc, g.w, xv[13]);
+        fmac_row_bcast<14, false>(acc, g.w, xv[14]);
+        fmac_row_bcast<15, false>(acc, g.w, xv[15]);
+    };
+    // every kernel argument is in its registers before the loop: a scalar load still in
+    // flight there would make each wait on an LDS read a wait for all of them
+    asm volatile("" ::"s"(bias), "s"(seg_cnt), "s"(expert_idx), "s"(gate), "s"(bias_stride),
+                 "s"(E), "s"(k), "s"(renorm), "s"(T));
+    MOE_CHAIN_SYNC(0)
+    MOE_CHAIN_READ(0, 0, 0)
+    MOE_CHAIN_READ(1, 0, 1)
+    // (every iteration issues the same reads, so that the counts of reads in flight are
+    // static: behind the last stage they fetch a place of the ring that nobody consumes)
+    for (int s = 0; s < nstage; ++s) {
+        // (the fences keep the compiler from gathering the reads in one place, where it
+        // would then wait for all of them)
+        MOE_CHAIN_READ(2, s, 2)
+        __builtin_amdgcn_sched_barrier(0);
+        compute(grp[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        MOE_CHAIN_READ(3, s, 3)
+        __builtin_amdgcn_sched_barrier(0);
+        compute(grp[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (s + 1 < nstage) MOE_CHAIN_SYNC(s + 1)
+        MOE_CHAIN_READ(0, s + 1, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        compute(grp[2]);
+        __builtin_amdgcn_sched_barrier(0);
+        MOE_CHAIN_READ(1, s + 1, 1)
+        __builtin_amdgcn_sched_barrier(0);
+        compute(grp[3]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#undef MOE_CHAIN_READ
+#undef MOE_CHAIN_SYNC
+#undef MOE_CHAIN_LOAD
+    __syncthreads();                  // every wavefront is done with the ring: reuse it for logits
+    {
+        const int t = t0 + tg;
+        if (active && eg < E) {
+            float z = acc;
+            if (bias != nullptr && t < T) z = z + bias[static_cast<size_t>(t) * bias_stride + eg];
+            zs[tg][eg] = z;
+        }
+    }
+    __syncthreads();
+    const int LP = min(min(256 / TB, EP), kWave);
+    switch (EP / LP) {
+    case 1: route_tail<1>(zs, expert_idx, gate, seg_cnt, t0, T, E, TB, LP, k, renorm); break;
+    case 2: route_tail<2>(zs, expert_idx, gate, seg_cnt, t0, T, E, TB, LP, k, renorm); break;
+    case 4: route_tail<4>(zs, expert_idx, gate, seg_cnt, t0, T, E, TB, LP, k, renorm); break;
+    case 8: route_tail<8>(zs, expert_idx, gate, seg_cnt, t0, T, E, TB, LP, k, renorm); break;
+    default: route_tail<16>(zs, expert_idx, gate, seg_cnt, t0, T, E, TB, LP, k, renorm); break;
+    }
+#endif
+}
+
 // Gate matrix [d][E] (fp32 or bf16) -> fp32 [EP][dP], expert-major, zero padded.
 template <typename XT>
 __global__ void pack_gate_kernel(const XT *__restrict__ Wg, float *__restrict__ Wgp,
@@ -378,6 +607,33 @@ moe_status launch_route_t(const moe_shape &s, const XT *x, const float *Wgp,
     const int dP = padded_dim(s.d_model);
     const RouteShape rs = route_shape(s);
     const int blocks = ceil_div(s.T, rs.tb);
+    // one chain per lane and a small stage: the kernel that streams its operands through LDS
+    {
+        const int xrowb = kKC * static_cast<int>(sizeof(XT));
+        const int stage = (rs.tb * xrowb + 1023) / 1024 * 1024 + (EP * kKC * 4 + 1023) / 1024 * 1024;
+        const size_t logits = sizeof(float) * (kWave + 2) * (kMaxExperts + 1);
+        if (rs.tpl == 1 && rs.epl == 1 && s.d_model % kKC == 0 && stage <= 8192 &&
+            EP * ((rs.tb + 15) / 16) <= 16) {
+            const int cpw = (stage / 1024 + 3) / 4;
+            const size_t lds = std::max(static_cast<size_t>(kChainStages) * stage, logits);
+#define MOE_CHAIN_CASE(CPW_)                                                                  \
+    if (cpw == CPW_) {                                                                        \
+        auto kern = route_chain_kernel<XT, CPW_>;                                             \
+        static PerDeviceOnce once;                                                            \
+        if (once.first()) {                                                                   \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                   \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024); \
+        }                                                                                     \
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, x, Wgp, bias, bias_stride, \
+                           expert_idx, gate, seg_cnt, s.T, s.d_model, dP, s.E, EP, rs.tb,     \
+                           s.k, s.renorm_topk);                                               \
+    }
+            MOE_CHAIN_CASE(1) MOE_CHAIN_CASE(2)
+#undef MOE_CHAIN_CASE
+            MOE_TRY_HIP(hipGetLastError());
+            return MOE_OK;
+        }
+    }
     const size_t tiles = sizeof(float) * 2 * (rs.tb + EP) * kLDX;
     const size_t logits = sizeof(float) * (kWave + 2) * (kMaxExperts + 1);
     const size_t lds = std::max(tiles, logits);

@@ -187,6 +187,12 @@ GATE_SHAPES = [
     ("block_1x2_f32",  "tiny_fp32", 8192,  100, 32, 2, 1.0),
     ("e64_few_tokens", "gpt2s_moe", 100,   200, 64, 2, 2.0),
     ("e2",             "gpt2s_moe", 3000,  136, 2,  1, 0.75),
+    # one chain per lane, operands streamed through the LDS ring (d a multiple of 64):
+    # 32 tokens x 8 experts (one padded), 16 x 16 in fp32 (three padded), 16 x 16 ragged
+    ("chain_32x8_e7",  "gpt2s_moe", 9000,  128, 7,  2, 1.0),
+    ("chain_16x16_f32", "tiny_fp32", 5000, 320, 13, 2, 1.0),
+    ("chain_16x16",    "gpt2s_moe", 4100,  192, 16, 1, 1.25),
+    ("chain_one_stage", "gpt2s_moe", 4096, 64,  16, 2, 1.0),
 ]
 
 
@@ -194,7 +200,7 @@ GATE_SHAPES = [
 def test_gate_register_blocks_and_segments(name, base, T, d, E, k, cf):
     cfg = wl.scaled(base, T=T, d=d, h=64, E=E, k=k, cf=cf)
     li = wl.make_layer(cfg, seed=11, threads=8)
-    if name == "block_4x4":                     # per-token bias on the largest shape
+    if name in ("block_4x4", "chain_16x16"):    # per-token bias
         prng = np.random.Generator(np.random.PCG64(5))
         li.gate_bias = (0.05 * prng.standard_normal((T, E))).astype(np.float32)
         li.bias_token_stride = E
