@@ -334,13 +334,16 @@ def main() -> int:
         kept_tokens = float(np.mean([(L.b["slot_of"].view(l0.T, l0.k) >= 0).any(1).sum().item() for L in sets[0]]))
         disp_bytes = (kept_tokens + A) * l0.d * esz * n_layers      # read routed tokens, write slots
         comb_bytes = (A + l0.T) * l0.d * 4 * n_layers               # fp32 expert rows in, fp32 y out
-        st["dispatch_GBps"] = disp_bytes / (st["scatter"] * 1e-6) / 1e9
+        # (an unchunked layer packs the rows in its plan launch: then there is no pack stage and
+        # the bytes are set against the plan stage's time)
+        pack_us = st["scatter"] if st["scatter"] is not None else st["plan"]
+        st["dispatch_GBps"] = disp_bytes / (pack_us * 1e-6) / 1e9
         # gate: T*d*E sequential-order fp32 FMAs against the unpacked vector rate
         # (256 CUs x 64 lanes x 2.4 GHz = 39.3 TFMA/s; packed-fp32 instructions are off)
         st["route_alu_frac"] = (l0.T * l0.d * l0.E * n_layers) / (st["route"] * 1e-6) / 39.3e12
         st["combine_GBps"] = comb_bytes / (st["combine"] * 1e-6) / 1e9
         st["dispatch_combine_frac_of_hbm_peak"] = ((disp_bytes + comb_bytes) /
-                                                   ((st["scatter"] + st["combine"]) * 1e-6) / 1e9 / PEAK_HBM_GBPS)
+                                                   ((pack_us + st["combine"]) * 1e-6) / 1e9 / PEAK_HBM_GBPS)
         st["ffn_mfma_util"] = (4.0 * A * l0.d * l0.h * n_layers) / ((st["gemm1"] + st["gemm2"]) * 1e-6) / 1e12 / PEAK_BF16_TFLOPS
         ffn_bytes = (2 * live * l0.d * l0.h * 2 + A * l0.d * 2 + 2 * A * l0.h * 2 + A * l0.d * 4) * n_layers
         st["ffn_GBps"] = ffn_bytes / ((st["gemm1"] + st["gemm2"]) * 1e-6) / 1e9

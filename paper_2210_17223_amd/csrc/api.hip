@@ -374,9 +374,10 @@ moe_status moe_dispatch(const moe_shape *s, const void *x, const int32_t *expert
     Workspace w;
     layout_workspace(*s, 1, workspace, &w);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    bool packed = false;
     MOE_TIMED(kStagePlan, st, launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w,
-                                          false, 0, st));
-    MOE_TIMED(kStageScatter, st, launch_scatter(*s, x, slot_of, xe, 0, s->T, st));
+                                          false, 0, st, false, x, xe, &packed));
+    if (!packed) MOE_TIMED(kStageScatter, st, launch_scatter(*s, x, slot_of, xe, 0, s->T, st));
     return MOE_OK;
 }
 
@@ -460,13 +461,16 @@ moe_status layer_forward(const moe_shape *s, int32_t n_chunks, const void *x,
     MOE_TIMED(kStageRoute, st,
               launch_route(*s, x, Wgp, gate_bias, bias_token_stride, expert_idx, gate,
                            w.seg_cnt, st));
+    bool packed = false;       // an unchunked layer's plan launch packs the token rows as well
     MOE_TIMED(kStagePlan, st,
-              launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w, true, n_chunks, st));
+              launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w, true, n_chunks, st,
+                          false, n_chunks == 1 ? x : nullptr, xe, &packed));
     if (n_chunks > 1)
         MOE_TIMED(kStageTiles, st, launch_items(*s, n_chunks, offsets, src_of, w, st));
 
     if (n_chunks == 1) {
-        MOE_TIMED(kStageScatter, st, launch_scatter(*s, x, slot_of, xe, 0, s->T, st));
+        if (!packed)
+            MOE_TIMED(kStageScatter, st, launch_scatter(*s, x, slot_of, xe, 0, s->T, st));
         MOE_TRY(launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, 0, st, pre));
         MOE_TIMED(kStageCombine, st,
                   launch_combine(*s, ye, slot_of, gate, y, y_act, 0, s->T, st));

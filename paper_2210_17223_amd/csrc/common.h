@@ -101,10 +101,14 @@ moe_status launch_route(const moe_shape &s, const void *x, const void *Wg,
 // n_chunks == 1 also builds the GEMM work lists (otherwise launch_items does, after the ranks)
 // padded: slot = e * capacity + rank (the equal-split layout) instead of offsets[e] + rank;
 // offsets still receives the compact scan, and no work lists are built
+// x, xe, packed: when all three are given and the plan is short enough for one launch, that
+// launch also copies every token row to its kept slots (what launch_scatter does for all
+// tokens) and sets *packed; otherwise *packed = false and the caller runs launch_scatter
 moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *counts,
                        int32_t *offsets, int32_t *slot_of, int32_t *src_of,
                        const Workspace &w, bool counted, int n_chunks, hipStream_t st,
-                       bool padded = false);
+                       bool padded = false, const void *x = nullptr, void *xe = nullptr,
+                       bool *packed = nullptr);
 // work lists of the padded layout, one per micro-op (slot positions [m*C/n, (m+1)*C/n))
 moe_status launch_items_padded(const moe_shape &s, int n_micro, const int32_t *counts,
                                const Workspace &w, hipStream_t st);

@@ -253,17 +253,19 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rank_prefix_kernel(
     int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ slot_of,
     int32_t *__restrict__ src_of, int n, int E, int capacity, int seg_len, int nseg, int padded,
     int with_items, WorkItem *__restrict__ items0, int32_t *__restrict__ nitems0, GemmPlan gp0,
-    WorkItem *__restrict__ items1, int32_t *__restrict__ nitems1, GemmPlan gp1)
+    WorkItem *__restrict__ items1, int32_t *__restrict__ nitems1, GemmPlan gp1,
+    int spb, const uint4 *__restrict__ x, uint4 *__restrict__ xe, int vec, int k, int T)
 {
     constexpr int kParts = kPlanWaves * 4;          // partial sums: 16-byte loads, 4 segments per wavefront load
     __shared__ int32_t part_before[kParts][kMaxExperts], part_total[kParts][kMaxExperts];
     __shared__ int32_t run[kPlanWaves][kMaxExperts];
+    __shared__ int32_t slot_s[kSegTok * kMaxTopK];  // the segment's slots, for the packing below
     __shared__ int32_t off_s[kMaxExperts];
     __shared__ int32_t lo_s[kMaxExperts], hi_s[kMaxExperts], mt_s[kMaxExperts];
     __shared__ int32_t cum_s[kMaxExperts + 1];
     const int lane = lane_id();
     const int wave = threadIdx.x / kWave;
-    const int first = min(static_cast<int>(blockIdx.x) * kPlanWaves, nseg);
+    const int first = min(static_cast<int>(blockIdx.x) * spb, nseg);
     {
         // lane = (segment of the load, four experts): part p = wave * 4 + lane / 16 walks the
         // segments p, p + 16, ...
@@ -300,7 +302,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rank_prefix_kernel(
 #pragma unroll
         for (int q = 0; q < kPlanWaves; ++q) {
             run[q][lane] = base;
-            if (first + q < nseg) base += seg_cnt[static_cast<size_t>(first + q) * kMaxExperts + lane];
+            if (q < spb && first + q < nseg)
+                base += seg_cnt[static_cast<size_t>(first + q) * kMaxExperts + lane];
         }
         if (first == nseg && blockIdx.x == gridDim.x - 1) {   // one of the blocks without segments
             if (lane < E) {
@@ -325,22 +328,58 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rank_prefix_kernel(
     }
     const int seg = first + wave;
     const int base = seg * seg_len;
-    if (seg >= nseg) return;
-    for (int off = 0; off < seg_len; off += kWave) {
-        const int i = base + off + lane;
-        const bool valid = i < n && off + lane < seg_len;
-        const int e = valid ? clamp_expert(expert_idx[i], E) : 0;
-        const uint64_t peers = same_expert_lanes(e, valid);
-        const int rank = __popcll(peers & lanes_below(lane));
-        const int32_t before = run[wave][e];
-        __builtin_amdgcn_wave_barrier();
-        if (valid && rank == 0) run[wave][e] = before + __popcll(peers);
-        __builtin_amdgcn_wave_barrier();
-        if (valid) {
-            const int32_t pos = before + rank;
-            const int32_t slot = pos < capacity ? off_s[e] + pos : -1;
-            slot_of[i] = slot;
-            if (slot >= 0) src_of[slot] = i;
+    const bool ranks = wave < spb && seg < nseg;
+    if (!ranks && x == nullptr) return;
+    if (ranks) {
+        for (int off = 0; off < seg_len; off += kWave) {
+            const int i = base + off + lane;
+            const bool valid = i < n && off + lane < seg_len;
+            const int e = valid ? clamp_expert(expert_idx[i], E) : 0;
+            const uint64_t peers = same_expert_lanes(e, valid);
+            const int rank = __popcll(peers & lanes_below(lane));
+            const int32_t before = run[wave][e];
+            __builtin_amdgcn_wave_barrier();
+            if (valid && rank == 0) run[wave][e] = before + __popcll(peers);
+            __builtin_amdgcn_wave_barrier();
+            int32_t slot = -1;
+            if (valid) {
+                const int32_t pos = before + rank;
+                slot = pos < capacity ? off_s[e] + pos : -1;
+                slot_of[i] = slot;
+                if (slot >= 0) src_of[slot] = i;
+            }
+            if (x != nullptr && off + lane < seg_len) slot_s[off + lane] = slot;
+        }
+    }
+    if (x == nullptr) return;
+    // Packing in the same launch (one segment per block: spb = 1): the block's wavefronts
+    // copy the segment's token rows to their kept slots, two tokens per round.
+    __syncthreads();
+    const int seg_tok = seg_len / k;
+    const int t_seg = first * seg_tok;
+    for (int tt = wave; tt < seg_tok; tt += 2 * kPlanWaves) {
+        const int ta = tt, tb = tt + kPlanWaves;
+        const bool has_a = t_seg + ta < T, has_b = tb < seg_tok && t_seg + tb < T;
+        int sa[kMaxTopK], sb[kMaxTopK];
+        bool any_a = false, any_b = false;
+#pragma unroll
+        for (int j = 0; j < kMaxTopK; ++j) {
+            sa[j] = has_a && j < k ? slot_s[ta * k + j] : -1;
+            sb[j] = has_b && j < k ? slot_s[tb * k + j] : -1;
+            any_a |= sa[j] >= 0;
+            any_b |= sb[j] >= 0;
+        }
+        const uint4 *src_a = x + static_cast<size_t>(t_seg + ta) * vec;
+        const uint4 *src_b = x + static_cast<size_t>(t_seg + tb) * vec;
+        for (int c = lane; c < vec; c += kWave) {
+            uint4 va = make_uint4(0, 0, 0, 0), vb = va;
+            if (any_a) va = src_a[c];
+            if (any_b) vb = src_b[c];
+#pragma unroll
+            for (int j = 0; j < kMaxTopK; ++j) {
+                if (sa[j] >= 0) xe[static_cast<size_t>(sa[j]) * vec + c] = va;
+                if (sb[j] >= 0) xe[static_cast<size_t>(sb[j]) * vec + c] = vb;
+            }
         }
     }
 }
@@ -470,8 +509,10 @@ moe_status launch_items_per_expert(const moe_shape &s, const int32_t *offsets, c
 
 moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *counts,
                        int32_t *offsets, int32_t *slot_of, int32_t *src_of,
-                       const Workspace &w, bool counted, int n_chunks, hipStream_t st, bool padded)
+                       const Workspace &w, bool counted, int n_chunks, hipStream_t st, bool padded,
+                       const void *x, void *xe, bool *packed)
 {
+    if (packed != nullptr) *packed = false;
     const int n = s.T * s.k;
     const int seg_len = w.seg_tok * s.k;
     int eps = 1;
@@ -482,12 +523,21 @@ moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *c
                            expert_idx, w.seg_cnt, n, s.E, seg_len);
     if (w.nseg <= kPrefixSegments) {
         const bool with_items = n_chunks == 1 && !padded;
-        hipLaunchKernelGGL(plan_rank_prefix_kernel, dim3(blocks + (with_items ? kItemBlocks : 1)),
+        // with the token rows at hand the same launch packs them: then one segment per block
+        const bool pack = x != nullptr && xe != nullptr && packed != nullptr && !padded;
+        const int spb = pack ? 1 : kPlanWaves;
+        const int elem = s.dtype == MOE_BF16 ? 2 : 4;
+        hipLaunchKernelGGL(plan_rank_prefix_kernel,
+                           dim3(ceil_div(w.nseg, spb) + (with_items ? kItemBlocks : 1)),
                            dim3(kPlanThreads), 0, st,
                            expert_idx, w.seg_cnt, counts, offsets, slot_of, src_of, n, s.E,
                            s.capacity, seg_len, w.nseg, padded ? 1 : 0, with_items ? 1 : 0, w.items[0], w.nitems[0], w.gp[0],
-                           w.items[1], w.nitems[1], w.gp[1]);
+                           w.items[1], w.nitems[1], w.gp[1], spb,
+                           pack ? static_cast<const uint4 *>(x) : nullptr,
+                           pack ? static_cast<uint4 *>(xe) : nullptr, s.d_model * elem / 16, s.k,
+                           s.T);
         MOE_TRY_HIP(hipGetLastError());
+        if (pack) *packed = true;
         return MOE_OK;
     }
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, w.seg_cnt, counts,
