@@ -82,12 +82,19 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
     const int b_k = tid / 16, b_n = (tid % 16) * 4;
     const float *Bexp = B + static_cast<size_t>(tile.expert) * K * N;
 
+    // the loads of stage k0 + 16 are in flight while stage k0 is multiplied
+    float4 av, bv;
+#define MOE_F32_LOAD(k0_)                                                                        \
+    {                                                                                            \
+        av = make_float4(0.f, 0.f, 0.f, 0.f);                                                    \
+        bv = av;                                                                                 \
+        if ((k0_) + a_k < K)                                                                     \
+            av = *reinterpret_cast<const float4 *>(A + static_cast<size_t>(a_row_g) * K + (k0_) + a_k); \
+        if ((k0_) + b_k < K && n0 + b_n < N)                                                     \
+            bv = *reinterpret_cast<const float4 *>(Bexp + static_cast<size_t>((k0_) + b_k) * N + n0 + b_n); \
+    }
+    MOE_F32_LOAD(0)
     for (int k0 = 0; k0 < K; k0 += kF32BK) {
-        float4 av = make_float4(0.f, 0.f, 0.f, 0.f), bv = av;
-        if (k0 + a_k < K)
-            av = *reinterpret_cast<const float4 *>(A + static_cast<size_t>(a_row_g) * K + k0 + a_k);
-        if (k0 + b_k < K && n0 + b_n < N)
-            bv = *reinterpret_cast<const float4 *>(Bexp + static_cast<size_t>(k0 + b_k) * N + n0 + b_n);
         __syncthreads();
         As[a_k + 0][a_row] = av.x;
         As[a_k + 1][a_row] = av.y;
@@ -95,6 +102,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
         As[a_k + 3][a_row] = av.w;
         *reinterpret_cast<float4 *>(&Bs[b_k][b_n]) = bv;
         __syncthreads();
+        if (k0 + kF32BK < K) MOE_F32_LOAD(k0 + kF32BK)
 #pragma unroll
         for (int kk = 0; kk < kF32BK; ++kk) {
             const float4 a4 = *reinterpret_cast<const float4 *>(&As[kk][ty * 4]);
@@ -107,6 +115,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
                 for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
         }
     }
+#undef MOE_F32_LOAD
     const int n = n0 + tx * 4;
     if (n >= N) return;
     float4 bs = make_float4(0.f, 0.f, 0.f, 0.f);
