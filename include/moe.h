@@ -177,6 +177,8 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
  * (+ activation), 5 second expert GEMM, 6 combine; backward pass (moe_train.h): 7 recomputed
  * pre-activation GEMM, 8 hidden-gradient GEMM, 9 input-gradient GEMM, 10 and 11 the weight
  * gradient GEMMs of the second and first layer, 12 all its other kernels together.
+ * An unchunked layer (and moe_dispatch) whose plan fits one launch packs the rows in
+ * that launch: stage 3 then records nothing and stage 1 covers both.
  * moe_profile_enable: for every stage whose bit is set in stage_mask, the next
  * max_samples launches of that stage are bracketed by a pair of timing events
  * recorded on the stream the stage runs on.  (0, 0) switches it off and frees the

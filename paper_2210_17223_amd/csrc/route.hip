@@ -614,7 +614,7 @@ moe_status launch_route_t(const moe_shape &s, const XT *x, const float *Wgp,
         const size_t logits = sizeof(float) * (kWave + 2) * (kMaxExperts + 1);
         if (rs.tpl == 1 && rs.epl == 1 && s.d_model % kKC == 0 && stage <= 8192 &&
             EP * ((rs.tb + 15) / 16) <= 16) {
-            const int cpw = (stage / 1024 + 3) / 4;
+            const int cpw = (stage / 1024 + 3) / 4;       // 1 or 2: a stage is at most 8 chunks
             const size_t lds = std::max(static_cast<size_t>(kChainStages) * stage, logits);
 #define MOE_CHAIN_CASE(CPW_)                                                                  \
     if (cpw == CPW_) {                                                                        \
