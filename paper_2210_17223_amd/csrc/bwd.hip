@@ -528,17 +528,37 @@ __global__ __launch_bounds__(256, 2) void wgrad_gemm_kernel(
 // differs from the forward's chain, which only the top-k decision needed.  Softmax, dz with
 // lane = expert, and finally, lane = column again,
 // dx[t, i] = sum of the token's kept dxe rows + sum_e dz[e] Wg[i, e].
-template <int EP>
-__global__ __launch_bounds__(256) void gate_bwd_kernel(
+// STAGED: the gate matrix (EP x d floats, at most 64 KiB) is copied to LDS once per block of
+// 16 wavefronts (16 tokens) and read from there -- a wavefront that reads the matrix twice
+// per token from the caches moves 8 EP d bytes per token through the L1, which is what
+// bounded the kernel.  (Still one token per wavefront and four wavefronts per SIMD: the
+// token's own chain of loads, butterflies and stores is covered by the other wavefronts.)
+template <int EP, bool STAGED>
+__global__ __launch_bounds__(STAGED ? 1024 : 256) void gate_bwd_kernel(
     const uint16_t *__restrict__ x, const float *__restrict__ Wgp, const float *__restrict__ bias,
     int bias_stride, const int32_t *__restrict__ expert_idx, const int32_t *__restrict__ slot_of,
     const float *__restrict__ dgate, const float *__restrict__ dxe, float *__restrict__ dz,
     float *__restrict__ dx, int T, int d, int dP, int E, int k, int max_rows)
 {
-    __shared__ float dzs[4][kWave];
+    constexpr int NW = STAGED ? 16 : 4;                              // wavefronts per block
+    __shared__ float dzs[NW][kWave];
+    extern __shared__ __attribute__((aligned(16))) float wlds[];     // STAGED: [EP][d]
     const int lane = lane_id();
     const int w = threadIdx.x / kWave;
-    const int t = blockIdx.x * 4 + w;
+    const float *Wsrc = Wgp;
+    int wpitch = dP;
+    if constexpr (STAGED) {
+        const int rv = d / 4;                                        // 16-byte vectors per row
+        for (int v = threadIdx.x; v < EP * rv; v += NW * kWave) {
+            const int e = v / rv, i = (v % rv) * 4;
+            *reinterpret_cast<float4 *>(wlds + e * d + i) =
+                *reinterpret_cast<const float4 *>(Wgp + static_cast<size_t>(e) * dP + i);
+        }
+        __syncthreads();
+        Wsrc = wlds;
+        wpitch = d;
+    }
+    const int t = blockIdx.x * NW + w;
     if (t >= T) return;
     const uint16_t *xrow = x + static_cast<size_t>(t) * d;
     float acc[EP];
@@ -550,7 +570,7 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(
         const float x2 = __uint_as_float(xq[1] << 16), x3 = __uint_as_float(xq[1] & 0xFFFF0000u);
 #pragma unroll
         for (int e = 0; e < EP; ++e) {
-            const float4 wv = *reinterpret_cast<const float4 *>(Wgp + static_cast<size_t>(e) * dP + i);
+            const float4 wv = *reinterpret_cast<const float4 *>(Wsrc + static_cast<size_t>(e) * wpitch + i);
             acc[e] = __builtin_fmaf(x0, wv.x, acc[e]);
             acc[e] = __builtin_fmaf(x1, wv.y, acc[e]);
             acc[e] = __builtin_fmaf(x2, wv.z, acc[e]);
@@ -601,7 +621,7 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(
         }
 #pragma unroll
         for (int ee = 0; ee < EP; ++ee) {
-            const float4 wv = *reinterpret_cast<const float4 *>(Wgp + static_cast<size_t>(ee) * dP + i);
+            const float4 wv = *reinterpret_cast<const float4 *>(Wsrc + static_cast<size_t>(ee) * wpitch + i);
             o.x = __builtin_fmaf(dzr[ee], wv.x, o.x);
             o.y = __builtin_fmaf(dzr[ee], wv.y, o.y);
             o.z = __builtin_fmaf(dzr[ee], wv.z, o.z);
@@ -834,9 +854,21 @@ moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, c
     const int dPad = (d + 127) / 128 * 128;            // the packed gate matrix's row length
 #define MOE_GATE_BWD_CASE(EP_)                                                                    \
     if (EP == EP_) {                                                                              \
-        hipLaunchKernelGGL(gate_bwd_kernel<EP_>, dim3(ceil_div(T, 4)), dim3(256), 0, st, x, Wgp,  \
-                           bias, bias_stride, expert_idx, slot_of, dgate, w.dxe, w.dz, dx, T, d,  \
-                           dPad, E, k, R);                                                        \
+        const size_t wbytes = static_cast<size_t>(EP_) * d * sizeof(float);                       \
+        if (wbytes <= 64 * 1024 && T >= 16 * 256) {                                               \
+            auto kern = gate_bwd_kernel<EP_, true>;                                               \
+            static PerDeviceOnce once;                                                            \
+            if (once.first())                                                                     \
+                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                   \
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024); \
+            hipLaunchKernelGGL(kern, dim3(ceil_div(T, 16)), dim3(1024), wbytes,                   \
+                               st, x, Wgp, bias, bias_stride, expert_idx, slot_of, dgate, w.dxe,  \
+                               w.dz, dx, T, d, dPad, E, k, R);                                    \
+        } else {                                                                                  \
+            hipLaunchKernelGGL((gate_bwd_kernel<EP_, false>), dim3(ceil_div(T, 4)), dim3(256), 0, \
+                               st, x, Wgp, bias, bias_stride, expert_idx, slot_of, dgate, w.dxe,  \
+                               w.dz, dx, T, d, dPad, E, k, R);                                    \
+        }                                                                                         \
         hipLaunchKernelGGL(dwg_partial_kernel<EP_>, dim3(ceil_div(d, 64), w.splits), dim3(256), 0, \
                            st, x, w.dz, w.partial, T, d, E, w.per_split);                         \
     }
