@@ -169,7 +169,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rank_kernel(
     const int base = seg * seg_len;
     // padded layout: expert e owns the slots [e * capacity, (e + 1) * capacity)
     if (threadIdx.x < kMaxExperts)
-        off_s[threadIdx.x] = threadIdx.x >= E ? 0 : padded ? threadIdx.x * capacity : offsets[threadIdx.x];
+        off_s[threadIdx.x] = static_cast<int>(threadIdx.x) >= E ? 0 : padded ? threadIdx.x * capacity : offsets[threadIdx.x];
     run[wave][lane] = base < n ? seg_base[static_cast<size_t>(seg) * kMaxExperts + lane] : 0;
     __syncthreads();
     for (int off = 0; off < seg_len; off += kWave) {

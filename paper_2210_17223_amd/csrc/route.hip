@@ -367,7 +367,6 @@ __global__ __launch_bounds__(256, 2) void route_chain_kernel(
     constexpr int NS = kChainStages;
     constexpr int XROWB = kKC * static_cast<int>(sizeof(XT));     // bytes of a token row per stage
     constexpr int WROWB = kKC * 4;                                // ... of a gate-matrix row
-    constexpr int XPIECES = XROWB / 16;                           // 8 (bf16) or 16 (fp32)
     constexpr int XQ = ChainGroup<XT>::XQ;
     extern __shared__ __attribute__((aligned(16))) float smem[];
     char *ring = reinterpret_cast<char *>(smem);
@@ -418,8 +417,10 @@ __global__ __launch_bounds__(256, 2) void route_chain_kernel(
         _Pragma("unroll") for (int j = 0; j < CPW; ++j) {                                     \
             const char *g_ = gsrc[j] + static_cast<size_t>(s_) * gstep[j];                    \
             const uint32_t m_ = __builtin_amdgcn_readfirstlane(slot_ + cbyte[j]);             \
-            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"    \
-                         ::"v"(g_), "s"(m_) : "memory", "m0");                                \
+            uint32_t keep_;                                  /* M0 is handed back as found */ \
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\t"               \
+                         "global_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"                 \
+                         : "=&s"(keep_) : "v"(g_), "s"(m_) : "memory");                       \
         }                                                                                     \
     }
     // Stage s_ becomes readable: this wavefront's part of it has landed once at most the
