@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void popularity_estimate_kernel(
         }
     }
     __syncthreads();
-    if (threadIdx.x < E && acc[threadIdx.x] != 0ull) atomicAdd(&S[threadIdx.x], acc[threadIdx.x]);
+    if (static_cast<int>(threadIdx.x) < E && acc[threadIdx.x] != 0ull) atomicAdd(&S[threadIdx.x], acc[threadIdx.x]);
 }
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
