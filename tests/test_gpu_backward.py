@@ -120,6 +120,15 @@ def test_backward_matches_the_oracle(name, keep):
     assert not got["dx"].reshape(T, d)[dropped].any()
 
 
+def test_backward_is_bitwise_reproducible():
+    # fixed-order sums everywhere (no floating-point atomics): two runs, the same bits
+    li = wl.make_layer(CASES[list(CASES)[0]], seed=3)
+    a, _ = run_backward(li, keep=True)
+    b, _ = run_backward(li, keep=True)
+    for name in a:
+        assert np.array_equal(a[name].view(np.uint32), b[name].view(np.uint32)), name
+
+
 @pytest.mark.parametrize("act", ["relu", "gelu_tanh", "identity"])
 def test_backward_other_activations(act):
     li = wl.make_layer(wl.scaled("gpt2s_moe", T=400, d=128, h=256, E=4), seed=3)

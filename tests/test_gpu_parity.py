@@ -106,6 +106,30 @@ def test_whole_layer_and_chunk_invariance(name):
         assert np.array_equal(y_act.view(np.uint32), want.view(np.uint32))
 
 
+def test_layer_is_bitwise_reproducible():
+    # no floating-point atomics on the path: the same call gives the same bits, also when
+    # the output buffers hold other values beforehand and other work ran in between
+    li = wl.make_layer(wl.scaled("skewed", T=3000, d=256, h=512), seed=9)
+    s = shape_of(li)
+    L = DeviceLayer(li, s, n_chunks=4)
+    keys = ("expert_idx", "gate", "counts", "offsets", "slot_of", "xe", "ye", "y")
+    ref = None
+    for run, n_chunks in enumerate((1, 1, 4, 1)):
+        for key in ("y", "ye", "xe", "gate"):
+            L.b[key].fill_(float(run) + 0.5)
+        L.layer(n_chunks)
+        got = {key: L.b[key].clone() for key in keys}
+        if ref is None:
+            ref = got
+        else:
+            A = int(ref["offsets"][-1])
+            for key in keys:
+                a, b = got[key], ref[key]
+                if key in ("xe", "ye"):                 # rows past offsets[E] belong to nobody
+                    a, b = a[:A * li.d], b[:A * li.d]
+                assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (run, key)
+
+
 @pytest.mark.parametrize("act", ["gelu", "gelu_tanh", "relu", "identity"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_activations_biases_and_renorm(act, dtype):
