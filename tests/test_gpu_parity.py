@@ -106,6 +106,35 @@ def test_whole_layer_and_chunk_invariance(name):
         assert np.array_equal(y_act.view(np.uint32), want.view(np.uint32))
 
 
+@pytest.mark.parametrize("T,d,E,k", [(600, 128, 16, 2), (9000, 64, 32, 2), (700, 72, 5, 3)],
+                         ids=["chain_kernel", "register_blocks", "odd_shape"])
+def test_gate_ties_go_to_the_lowest_index(T, d, E, k):
+    # inputs on a coarse grid (token values in {-1, 0, 1}, matrix entries multiples of 1/2):
+    # every logit is exact in fp32 whatever the order of its sum, and equal logits abound; the
+    # first third of the tokens is all zeros, so all their logits tie and experts 0..k-1 win
+    cfg = wl.scaled("gpt2s_moe", T=T, d=d, h=64, E=E, k=k, cf=1.0)
+    li = wl.make_layer(cfg, seed=2)
+    prng = np.random.Generator(np.random.PCG64(123))
+    li.x = prng.integers(-1, 2, size=(T, d)).astype(np.float32)
+    li.x[:T // 3] = 0.0
+    li.Wg = (prng.integers(-2, 3, size=(d, E)) * 0.5).astype(np.float32)
+    o = oracle.moe_layer(li.x, li.Wg, li.W1, li.W2, k=li.k, capacity=li.C)
+    assert (o.expert_idx[:T // 3] == np.arange(k)).all()          # the oracle's own tie rule
+    ties = 0
+    z = li.x.astype(np.float64) @ li.Wg.astype(np.float64)
+    for t in range(T // 3, T):
+        ties += len(np.unique(z[t])) < E
+    assert ties > (T - T // 3) // 10                               # ties really are common
+    s = shape_of(li)
+    L = DeviceLayer(li, s)
+    b = L.b
+    moe.moe_route(s, L.x, b["Wgp"], L.bias, L.bias_stride, b["expert_idx"], b["gate"])
+    torch.cuda.synchronize()
+    assert np.array_equal(b["expert_idx"].cpu().numpy().reshape(T, k), o.expert_idx)
+    np.testing.assert_allclose(b["gate"].cpu().numpy().reshape(T, k), o.gate, rtol=1e-6)
+    np.testing.assert_allclose(b["gate"].cpu().numpy().reshape(T, k)[:T // 3], 1.0 / E, rtol=1e-6)
+
+
 def test_layer_is_bitwise_reproducible():
     # no floating-point atomics on the path: the same call gives the same bits, also when
     # the output buffers hold other values beforehand and other work ran in between
