@@ -5,10 +5,13 @@ A step is one pass of the whole hot path -- gate, dispatch plan, pack, expert FF
 combine -- over one batch of seeded synthetic tokens, through moe_layer_chunked (for
 the 4-layer inference workload: the four layers back to back, each reading the
 previous layer's output).  Inputs and packed weights are resident in HBM before the
-timed region.  Prints one JSON line: layer tokens/s, the roofline position of the
-dominant kernel (first expert GEMM, timed with HIP events attached to its own
-dispatches during the timed steps), and the CPU oracle's rate on the same workload
-as a baseline.
+timed region.  The default workload is the largest single-GPU configuration
+(large_chunked: T=32768, d_model=2048, E=64, d_ff=8192, top-2), unchunked.  Prints one
+JSON line: layer tokens/s, the roofline position of the dominant kernel (first expert
+GEMM, timed with HIP events attached to its own dispatches during the timed steps), the
+metric's two other quantities (dispatch+combine HBM rate, expert-FFN matrix-core
+utilisation, from stage-timed steps after the timed region), and the CPU oracle's rate
+on a bounded sample of the same workload as a baseline.
 """
 from __future__ import annotations
 
@@ -26,19 +29,26 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
 INFINITY_CACHE_BYTES = 256 << 20
 
 # HBM bytes per launch of the first expert GEMM, from rocprofv3 --pmc FETCH_SIZE and
-# --pmc WRITE_SIZE runs of this script (readings and scale factors: profiles/).  The
-# counters cannot be read from inside the process, so the figure is a stored measurement,
-# reported only for the workload and launch configuration it was taken on.
-GEMM1_TRAFFIC_BYTES = {("gpt2s_moe", 1): (68752.4 * 2.0 + 50056.2 * 1.0) * 1024}
+# --pmc WRITE_SIZE runs of this script (readings, scale factors and commands: profiles/).
+# The counters cannot be read from inside the process, so the figure is a stored
+# measurement, reported only for the workload and launch configuration it was taken on
+# (null for any other): {(workload, n_chunks): (FETCH_SIZE KiB, WRITE_SIZE KiB)} per launch.
+GEMM1_TRAFFIC_KIB = {}
+FETCH_UNIT, WRITE_UNIT = 2.0, 1.0     # what the plain-copy calibration reads per counted KiB
+
+
+def gemm1_traffic_bytes(workload, chunks):
+    kib = GEMM1_TRAFFIC_KIB.get((workload, chunks))
+    return None if kib is None else (kib[0] * FETCH_UNIT + kib[1] * WRITE_UNIT) * 1024.0
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="gpt2s_moe",
-                    help="one of workloads.CONFIGS (default: the configuration the metric is quoted on), "
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="large_chunked",
+                    help="one of workloads.CONFIGS (default: the largest single-GPU configuration), "
                          "or 'popularity': the inference scheduler's estimate + two-phase decision")
     ap.add_argument("--chunks", type=int, default=1, help="n_chunks of moe_layer_chunked")
     ap.add_argument("--comm", action="store_true",
@@ -53,7 +63,8 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a HIP graph (reported beside the eager figure)")
     ap.add_argument("--stages", action="store_true",
-                    help="after the timed region, run extra steps with every stage timed")
+                    help="also print the per-stage times (mean, median, min) of the stage-timed steps "
+                         "that follow the timed region (their summary figures are always printed)")
     ap.add_argument("--cold-sets", type=int, default=4,
                     help="after the timed region, time the same steps rotating through this many "
                          "copies of every buffer, so that no step finds its data in the 256 MB "
@@ -68,24 +79,18 @@ def main() -> int:
                     help="expert weights stay in (pinned) host memory and stream through R device "
                          "slots (moe_expert_ffn_offloaded); the step is gate, dispatch, that FFN and "
                          "combine; a stack workload contributes its first layer")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="run ten plain device copies of 256 MiB and exit: under rocprofv3 --pmc "
-                         "FETCH_SIZE / WRITE_SIZE the copy kernel's reading fixes the counter's unit")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="measure the two roofs and exit: the library's plain copy kernel over 1 GiB "
+                         "(HBM GB/s, read + write; under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE its "
+                         "reading fixes the counters' unit) and its register-resident MFMA loop with "
+                         "constant and with random operands (TFLOP/s)")
     args = ap.parse_args()
-    if args.copy_calibration:
-        import torch
-        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
-        dst = torch.empty_like(src)
-        for _ in range(10):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4}))
-        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
         return 2
-
+    if args.calibrate:
+        return calibrate()
     import numpy as np
     import torch
 
@@ -241,7 +246,7 @@ def main() -> int:
                        "grouped_gemm_mfma_kernel<bf16 in, fp16 out, GeLU> (first expert GEMM)"),
             "avg_launch_us": g1_avg_ms * 1e3, "launches": int(g1_ms.size),
             "algorithmic_flops": g1_flops, "algorithmic_bytes": g1_bytes,
-            "traffic": None if args.backward else GEMM1_TRAFFIC_BYTES.get((args.workload, args.chunks)),
+            "traffic": None if args.backward else gemm1_traffic_bytes(args.workload, args.chunks),
             "mfma_tflops": g1_tflops, "hbm_gbps": g1_gbps}
     if hbm_bound:
         roof.update({"bound": "hbm", "achieved": g1_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
@@ -268,7 +273,8 @@ def main() -> int:
         "value": tokens_per_s * n_layers, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "dtype": ("bf16 (x, Wg, W1, xe bf16; hidden activations and W2 fp16; fp32 accumulate; "
+                  "gate fp32; expert output ye fp16; y fp32)") if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: T={l0.T} d_model={l0.d} E={l0.E} d_ff={l0.h} "
                                f"k={l0.k} capacity={l0.C} {l0.dtype}, seed 0"
                                + (f", {n_layers} layers back to back (value counts layer-tokens)" if n_layers > 1 else ""),
@@ -329,31 +335,54 @@ def main() -> int:
         moe.moe_profile_enable(0, 0)
         return mean, med, mn
 
-    if args.stages:
+    if not args.offload:
         st, med, mn = stage_times()
         kept_tokens = float(np.mean([(L.b["slot_of"].view(l0.T, l0.k) >= 0).any(1).sum().item() for L in sets[0]]))
-        disp_bytes = (kept_tokens + A) * l0.d * esz * n_layers      # read routed tokens, write slots
-        comb_bytes = (A + l0.T) * l0.d * 4 * n_layers               # fp32 expert rows in, fp32 y out
-        # (an unchunked layer packs the rows in its plan launch: then there is no pack stage and
-        # the bytes are set against the plan stage's time)
-        pack_us = st["scatter"] if st["scatter"] is not None else st["plan"]
-        st["dispatch_GBps"] = disp_bytes / (pack_us * 1e-6) / 1e9
+        ye_sz = sets[0][0].b["ye"].element_size()
+        # The method's bytes (what the two all-to-all payloads carry, in the storage type):
+        # pack reads every routed token once and writes every kept slot; unpack reads every kept
+        # row and writes every token.  The bytes this build really moves differ where it keeps
+        # the expert output and y wider than the storage type.
+        disp_alg = (kept_tokens + A) * l0.d * esz * n_layers
+        comb_alg = (A + l0.T) * l0.d * esz * n_layers
+        comb_moved = (A * ye_sz + l0.T * 4 + (l0.T * esz if n_layers > 1 else 0)) * l0.d * n_layers + 8.0 * l0.T * l0.k * n_layers
+        # (an unchunked layer of up to 64 MiB of token rows packs them in its plan launch: then
+        # there is no pack stage and the bytes are set against the plan stage's time)
+        pack_in_plan = st["scatter"] is None
+        pack_us = st["plan"] if pack_in_plan else st["scatter"]
+        dc_us = (pack_us + st["combine"]) * 1e-6
+        out["dispatch_combine"] = {
+            "pack_us": pack_us, "combine_us": st["combine"], "pack_in_plan_launch": pack_in_plan,
+            "algorithmic_bytes": disp_alg + comb_alg,
+            "GBps": (disp_alg + comb_alg) / dc_us / 1e9,
+            "frac_of_hbm_peak": (disp_alg + comb_alg) / dc_us / 1e9 / PEAK_HBM_GBPS,
+            "pack_GBps": disp_alg / (pack_us * 1e-6) / 1e9,
+            "combine_GBps": comb_alg / (st["combine"] * 1e-6) / 1e9,
+            "moved_bytes": disp_alg + comb_moved,
+            "moved_GBps": (disp_alg + comb_moved) / dc_us / 1e9,
+            "combine_moved_GBps": comb_moved / (st["combine"] * 1e-6) / 1e9,
+            "note": "algorithmic = (T'+A)*d*s packed + (A+T)*d*s unpacked, s = storage element size (the "
+                    "target figure); moved = what the kernels transfer: expert rows as stored "
+                    f"({ye_sz} B/element), y in fp32"}
+        ffn_us = (st["gemm1"] + st["gemm2"]) * 1e-6
+        ffn_bytes = (2 * live * l0.d * l0.h * 2 + A * l0.d * 2 + 2 * A * l0.h * 2 + A * l0.d * ye_sz) * n_layers
+        out["ffn"] = {"gemm1_us": st["gemm1"], "gemm2_us": st["gemm2"],
+                      "mfma_tflops": (4.0 * A * l0.d * l0.h * n_layers) / ffn_us / 1e12,
+                      "mfma_util": (4.0 * A * l0.d * l0.h * n_layers) / ffn_us / 1e12 / PEAK_BF16_TFLOPS,
+                      "gemm2_mfma_util": (2.0 * A * l0.d * l0.h * n_layers) / (st["gemm2"] * 1e-6) / 1e12 / PEAK_BF16_TFLOPS,
+                      "GBps": ffn_bytes / ffn_us / 1e9}
         # gate: T*d*E sequential-order fp32 FMAs against the unpacked vector rate
         # (256 CUs x 64 lanes x 2.4 GHz = 39.3 TFMA/s; packed-fp32 instructions are off)
-        st["route_alu_frac"] = (l0.T * l0.d * l0.E * n_layers) / (st["route"] * 1e-6) / 39.3e12
-        st["combine_GBps"] = comb_bytes / (st["combine"] * 1e-6) / 1e9
-        st["dispatch_combine_frac_of_hbm_peak"] = ((disp_bytes + comb_bytes) /
-                                                   ((pack_us + st["combine"]) * 1e-6) / 1e9 / PEAK_HBM_GBPS)
-        st["ffn_mfma_util"] = (4.0 * A * l0.d * l0.h * n_layers) / ((st["gemm1"] + st["gemm2"]) * 1e-6) / 1e12 / PEAK_BF16_TFLOPS
-        ffn_bytes = (2 * live * l0.d * l0.h * 2 + A * l0.d * 2 + 2 * A * l0.h * 2 + A * l0.d * 4) * n_layers
-        st["ffn_GBps"] = ffn_bytes / ((st["gemm1"] + st["gemm2"]) * 1e-6) / 1e9
+        out["gate"] = {"us": st["route"],
+                       "alu_frac": (l0.T * l0.d * l0.E * n_layers) / (st["route"] * 1e-6) / 39.3e12}
         if args.backward:
             bw = [n for n in ("bwd_recompute", "bwd_dP", "bwd_dxe", "bwd_wgrad2", "bwd_wgrad1")
                   if st[n] is not None]          # no recomputation when the forward kept P
-            st["bwd_gemm_mfma_util"] = (len(bw) * 2.0 * A * l0.d * l0.h) / (sum(st[n] for n in bw) * 1e-6) / 1e12 / PEAK_BF16_TFLOPS
-        out["stages_us"] = st
-        out["stages_us_median"] = med
-        out["stages_us_min"] = mn
+            out["bwd_gemm_mfma_util"] = (len(bw) * 2.0 * A * l0.d * l0.h) / (sum(st[n] for n in bw) * 1e-6) / 1e12 / PEAK_BF16_TFLOPS
+        if args.stages:
+            out["stages_us"] = st
+            out["stages_us_median"] = med
+            out["stages_us_min"] = mn
         if args.chunks > 1:
             # How much of the pack and unpack time the chunk pipeline hides behind the expert
             # FFN (Sec. 4.2's pipelining efficiency, with the pack kernel in the all-to-all's
@@ -407,6 +436,54 @@ def main() -> int:
                                "sample": f"{passes} pass(es) over {n_layers} layer(s): gate+plan over all "
                                          f"{l0.T} tokens, expert FFN+combine for the first {sample} "
                                          f"tokens, {elapsed:.2f} s wall"}
+    print(json.dumps(out))
+    return 0
+
+
+def calibrate() -> int:
+    """Measured roofs of this box, one JSON line (not a step of the layer)."""
+    import torch
+
+    import paper_2210_17223_amd as moe
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    out = {"calibration": True, "nominal": {"hbm_GBps": PEAK_HBM_GBPS, "bf16_mfma_tflops": PEAK_BF16_TFLOPS}}
+    nbytes = 1 << 30
+    src = torch.full((nbytes // 4,), 1.0, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    times = []
+    for _ in range(12):
+        a, b = ev(), ev()
+        a.record()
+        moe.moe_calib_copy(dst, src, nbytes)
+        b.record()
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(b))
+    assert torch.equal(dst[:1 << 20], src[:1 << 20])
+    best, med = min(times[2:]), sorted(times[2:])[len(times[2:]) // 2]
+    out["copy"] = {"bytes_read": nbytes, "bytes_written": nbytes, "launches": len(times),
+                   "us_median": med * 1e3, "us_min": best * 1e3,
+                   "GBps_median": 2 * nbytes / (med * 1e-3) / 1e9, "GBps_best": 2 * nbytes / (best * 1e-3) / 1e9,
+                   "frac_of_nominal": 2 * nbytes / (med * 1e-3) / 1e9 / PEAK_HBM_GBPS}
+    del src, dst
+    out["mfma"] = {}
+    for wps in (1, 2):
+        sink = torch.empty(256 * wps * 256, dtype=torch.float32, device=dev)
+        for rnd in (False, True):
+            iters = 20000
+            ms = []
+            for _ in range(4):
+                a, b = ev(), ev()
+                a.record()
+                flops = moe.moe_calib_mfma(sink, wps, iters, rnd)
+                b.record()
+                torch.cuda.synchronize()
+                ms.append(a.elapsed_time(b))
+            t = sorted(ms[1:])[1]
+            out["mfma"][f"{'random' if rnd else 'constant'}_operands_{wps}_wave_per_simd"] = {
+                "ms": t, "tflops": flops / (t * 1e-3) / 1e12,
+                "frac_of_nominal": flops / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
     print(json.dumps(out))
     return 0
 

@@ -23,9 +23,20 @@
  *     work has finished.  Buffers must be 16-byte aligned and must not overlap.
  *   - Matrices are row-major and dense.  Row lengths in bytes (d_model, d_ff
  *     times the element size) must be multiples of 16.
- *   - Return value: MOE_OK, or an error code with nothing enqueued;
- *     moe_last_error() then describes the problem (thread-local string).
+ *   - Return value: MOE_OK, or an error code; moe_last_error() then describes the
+ *     problem (thread-local string).  Argument errors (MOE_EINVAL,
+ *     MOE_EUNSUPPORTED) are found before anything is enqueued.  MOE_EHIP means a
+ *     HIP runtime call failed part-way: work enqueued before it stays enqueued,
+ *     the library's side streams are joined back into `stream` before the call
+ *     returns, and the outputs are unspecified.
  *     No C++ exception crosses this boundary.
+ *   - Threads: any host thread may call any entry point.  Calls that use the
+ *     library's own side streams on one device (moe_layer_chunked with
+ *     n_chunks > 1) take a per-device lock for the time they enqueue, so two
+ *     threads' calls do not interleave on those streams; their work then runs
+ *     one call after the other.  Two calls that write the same buffers race as
+ *     any two writers do.  The measurement aid at the end of this file is the
+ *     exception: one thread, no call in progress.
  *   - Inputs are assumed finite.
  *
  * Element types.  `dtype` is the storage type of x, Wg, W1, W2, xe.  Gate logits,
@@ -109,8 +120,11 @@ moe_status moe_pack_weights(const moe_shape *s, const void *W1, const void *W2,
 size_t moe_packed_gate_bytes(const moe_shape *s);
 
 /* One-time re-layout of the gating network's matrix (Sec. 2.1: "its trainable
- * matrix"): Wg [d_model, E] in `dtype` -> Wgp fp32 [d_model, EP], EP = E rounded
- * up to a power of two, zero padded.  Every bf16 value converts exactly. */
+ * matrix"): Wg [d_model, E] in `dtype` -> Wgp fp32 [EP][dP], expert-major:
+ * Wgp[e*dP + i] = Wg[i, e], EP = E rounded up to a power of two, dP = d_model
+ * rounded up to a multiple of 128, zeros elsewhere (moe_packed_gate_bytes =
+ * EP*dP*4).  Every bf16 value converts exactly.  Treat the buffer as opaque:
+ * build it with this call, not by hand. */
 moe_status moe_pack_gate(const moe_shape *s, const void *Wg, float *Wgp, void *stream);
 
 /* Gate (Sec. 2.1).  z[t,e] = sum_i x[t,i] Wg[i,e] accumulated in fp32 in
@@ -128,6 +142,8 @@ moe_status moe_route(const moe_shape *s, const void *x, const float *Wgp,
  * i = t*k + j is kept iff fewer than `capacity` assignments with a smaller i chose
  * the same expert; kept assignments of expert e fill slots
  * [offsets[e], offsets[e+1]) in ascending i.
+ * An expert_idx entry outside [0, E) names no expert (a padding marker): that
+ * assignment is in no count, takes no slot, and gets slot_of = -1.
  *   counts int32 [E]: assignments per expert before the capacity bound.
  *   offsets int32 [E+1]: exclusive scan of min(counts, capacity).
  *   slot_of int32 [T*k]: slot of assignment i, -1 if dropped.
@@ -189,6 +205,23 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
  * returns n <= cap and forgets the samples. */
 moe_status moe_profile_enable(uint32_t stage_mask, int32_t max_samples);
 int32_t moe_profile_read(int32_t stage, float *ms, int32_t cap);
+
+/* Calibration of the two roofs the measurements are quoted against (measurement aid,
+ * not part of the layer; the caller times the calls with events on `stream`).
+ * moe_calib_copy: dst[0..bytes) = src[0..bytes) by a plain copy kernel (16 bytes per
+ *   lane and step); bytes and both pointers multiples of 16.  Reads `bytes` and writes
+ *   `bytes`: the HBM rate it reaches on buffers far larger than the caches is the
+ *   measured memory roof, and its reading under the profiler's FETCH_SIZE / WRITE_SIZE
+ *   counters fixes their unit.
+ * moe_calib_mfma: 256 x waves_per_simd blocks of four wavefronts, each wavefront
+ *   issuing iters x 8 independent 32x32x16 bf16 matrix instructions on register
+ *   operands (random_operands != 0: operand bits differ per lane; 0: all ones, which
+ *   draws less power and holds a higher clock).  sink: fp32 [256*waves_per_simd*256].
+ *   moe_calib_mfma_flops gives the launch's floating-point operations. */
+moe_status moe_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
+moe_status moe_calib_mfma(float *sink, int32_t waves_per_simd, int32_t iters,
+                          int32_t random_operands, void *stream);
+double moe_calib_mfma_flops(int32_t waves_per_simd, int32_t iters);
 
 #ifdef __cplusplus
 }

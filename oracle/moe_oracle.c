@@ -103,24 +103,40 @@ void oracle_topk_softmax(const float *z, int T, int E, int k, int renorm,
     }
 }
 
+/* Slots per expert for a capacity factor cf: the smallest integer that is not
+ * below cf*k*T/E, the product and the quotient evaluated in double from left to
+ * right (the paper names no capacity; this is the usual rule of the MoE layer
+ * it builds on, Sec. 2.1, and the benchmark configurations are stated by cf). */
+int64_t oracle_capacity(int T, int E, int k, double cf)
+{
+    return (int64_t)ceil(cf * (double)k * (double)T / (double)E);
+}
+
 /* Dispatch plan: per-expert histogram, token-order rank, capacity bound,
  * exclusive scan, slot of every assignment.  Flat assignment index i = t*k + j;
  * an assignment is kept iff fewer than C earlier assignments (smaller i) chose
  * the same expert.  Kept rows of expert e occupy slots [off[e], off[e+1]) in
  * ascending i.  slot_of[i] = -1 for dropped assignments; src_of[slot] = i.
+ * An index outside [0, E) names no expert (a padding marker): that assignment is
+ * dispatched nowhere -- it is in no count, takes no slot, and has slot_of = -1.
  * Returns A = off[E], the number of kept assignments. */
 int oracle_plan(const int32_t *expert_idx, int T, int k, int E, int C,
                 int32_t *count, int32_t *off, int32_t *slot_of, int32_t *src_of)
 {
     int n = T * k;
     for (int e = 0; e < E; ++e) count[e] = 0;
-    for (int i = 0; i < n; ++i) count[expert_idx[i]] += 1;
+    for (int i = 0; i < n; ++i)
+        if (expert_idx[i] >= 0 && expert_idx[i] < E) count[expert_idx[i]] += 1;
     off[0] = 0;
     for (int e = 0; e < E; ++e)
         off[e + 1] = off[e] + (count[e] < C ? count[e] : C);
     int32_t *run = (int32_t *)calloc(64, sizeof(int32_t));
     for (int i = 0; i < n; ++i) {
         int e = expert_idx[i];
+        if (e < 0 || e >= E) {
+            slot_of[i] = -1;
+            continue;
+        }
         int pos = run[e];
         run[e] += 1;
         if (pos < C) {

@@ -42,6 +42,8 @@ def _load():
         _lib.oracle_plan.restype = C.c_int
         _lib.oracle_act.restype = C.c_double
         _lib.oracle_act.argtypes = [C.c_double, C.c_int]
+        _lib.oracle_capacity.restype = C.c_int64
+        _lib.oracle_capacity.argtypes = [C.c_int, C.c_int, C.c_int, C.c_double]
     return _lib
 
 
@@ -59,6 +61,13 @@ def _p(a: Optional[np.ndarray]):
 
 def threads() -> int:
     return int(_load().oracle_threads())
+
+
+def capacity(T: int, E: int, k: int, cf: Optional[float]) -> int:
+    """Slots per expert; cf=None means no dropping (every expert can hold all T tokens)."""
+    if cf is None:
+        return int(T)
+    return int(_load().oracle_capacity(int(T), int(E), int(k), float(cf)))
 
 
 def act_value(v: float, act: str) -> float:
@@ -93,7 +102,6 @@ def topk_softmax(z, k: int, renorm: bool = False):
 def plan(expert_idx, E: int, capacity: int):
     idx = _i32(expert_idx)
     T, k = idx.shape
-    assert idx.size == 0 or (idx.min() >= 0 and idx.max() < E)
     count = np.empty(E, np.int32)
     off = np.empty(E + 1, np.int32)
     slot_of = np.empty(T * k, np.int32)

@@ -75,6 +75,12 @@ def lib() -> C.CDLL:
         L.moe_expert_ffn.argtypes = [sp] + [vp] * 9
         L.moe_combine.argtypes = [sp] + [vp] * 6
         L.moe_layer_chunked.argtypes = [sp, i32, vp, vp, vp, i32] + [vp] * 16
+        L.moe_calib_copy.argtypes = [vp, vp, sz, vp]
+        L.moe_calib_copy.restype = C.c_int
+        L.moe_calib_mfma.argtypes = [vp, i32, i32, i32, vp]
+        L.moe_calib_mfma.restype = C.c_int
+        L.moe_calib_mfma_flops.argtypes = [i32, i32]
+        L.moe_calib_mfma_flops.restype = C.c_double
         L.moe_profile_enable.restype = C.c_int
         L.moe_profile_enable.argtypes = [C.c_uint32, i32]
         L.moe_profile_read.restype = i32
@@ -171,6 +177,17 @@ def moe_dispatch(s: Shape, x, expert_idx, counts, offsets, slot_of, src_of, xe, 
     _check(lib().moe_dispatch(C.byref(s), _ptr(x), _ptr(expert_idx), _ptr(counts), _ptr(offsets),
                               _ptr(slot_of), _ptr(src_of), _ptr(xe), _ptr(workspace),
                               _stream(stream)))
+
+
+def moe_calib_copy(dst, src, nbytes: int, stream=None) -> None:
+    _check(lib().moe_calib_copy(_ptr(dst), _ptr(src), int(nbytes), _stream(stream)))
+
+
+def moe_calib_mfma(sink, waves_per_simd: int, iters: int, random_operands: bool, stream=None) -> float:
+    """Enqueues the matrix-core calibration loop; returns the launch's flops."""
+    _need(sink, torch.float32, 256 * waves_per_simd * 256, "sink")
+    _check(lib().moe_calib_mfma(_ptr(sink), waves_per_simd, iters, int(random_operands), _stream(stream)))
+    return float(lib().moe_calib_mfma_flops(waves_per_simd, iters))
 
 
 def moe_expert_ffn(s: Shape, xe, offsets, W1p, b1, W2p, b2, ye, workspace, stream=None) -> None:

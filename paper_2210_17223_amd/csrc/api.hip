@@ -1,5 +1,6 @@
 // C-ABI entry points of libmoe: argument checks, workspace layout, and the order in
 // which the kernels are enqueued.  No arithmetic of the layer happens here.
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -41,6 +42,24 @@ struct Profiler {
     hipEvent_t *stop[kNumStages] = {};
 };
 Profiler g_prof;
+
+// Destroys every event and array of the profiler and switches it off (entries never created
+// are null and skipped).
+void prof_release()
+{
+    g_prof.mask = 0;
+    for (int st = 0; st < kNumStages; ++st) {
+        for (int i = 0; i < g_prof.cap; ++i) {
+            if (g_prof.start[st] && g_prof.start[st][i]) (void)hipEventDestroy(g_prof.start[st][i]);
+            if (g_prof.stop[st] && g_prof.stop[st][i]) (void)hipEventDestroy(g_prof.stop[st][i]);
+        }
+        delete[] g_prof.start[st];
+        delete[] g_prof.stop[st];
+        g_prof.start[st] = g_prof.stop[st] = nullptr;
+        g_prof.n[st] = 0;
+    }
+    g_prof.cap = 0;
+}
 }  // namespace
 
 void prof_begin(int stage, hipStream_t st)
@@ -91,9 +110,12 @@ bool check_shape(const moe_shape *s)
         set_error("k = %d exceeds E = %d", s->k, s->E);
         return false;
     }
-    if (static_cast<int64_t>(s->T) * s->k >= (1ll << 31) ||
-        static_cast<int64_t>(s->E) * s->capacity >= (1ll << 40)) {
-        set_error("T*k does not fit 31 bits");
+    if (static_cast<int64_t>(s->T) * s->k >= (1ll << 31)) {
+        set_error("T*k = %lld does not fit 31 bits", static_cast<long long>(s->T) * s->k);
+        return false;
+    }
+    if (static_cast<int64_t>(s->E) * s->capacity >= (1ll << 40)) {
+        set_error("E*capacity = %lld is not below 2^40", static_cast<long long>(s->E) * s->capacity);
         return false;
     }
     return true;
@@ -167,6 +189,7 @@ moe_status check_bias(const moe_shape &s, const float *gate_bias, int32_t stride
 // kept until the process ends.
 struct ChunkResources {
     bool ready = false;
+    std::mutex enqueue;        // held while a call enqueues on the side streams
     hipStream_t pack = nullptr, unpack = nullptr;
     hipEvent_t planned = nullptr, unpacked = nullptr;
     hipEvent_t packed[kMaxChunks] = {};
@@ -238,9 +261,10 @@ int64_t moe_capacity(int32_t T, int32_t E, int32_t k, double cf)
 {
     if (T < 1 || E < 1 || k < 1) return 0;
     if (!(cf > 0.0)) return T;
+    // the product and the quotient in double, left to right, then the ceiling: a value that
+    // comes out above an integer by any amount rounds up
     const double v = cf * static_cast<double>(k) * static_cast<double>(T) / static_cast<double>(E);
-    int64_t c = static_cast<int64_t>(v);
-    if (static_cast<double>(c) < v - 1e-9) c += 1;
+    const int64_t c = static_cast<int64_t>(std::ceil(v));
     return c < 1 ? 1 : c;
 }
 
@@ -271,29 +295,22 @@ moe_status moe_profile_enable(uint32_t stage_mask, int32_t max_samples)
         set_error("moe_profile_enable: bad stage mask or sample count");
         return MOE_EINVAL;
     }
-    for (int st = 0; st < kNumStages; ++st) {
-        for (int i = 0; i < g_prof.cap; ++i) {
-            if (g_prof.start[st]) (void)hipEventDestroy(g_prof.start[st][i]);
-            if (g_prof.stop[st]) (void)hipEventDestroy(g_prof.stop[st][i]);
-        }
-        delete[] g_prof.start[st];
-        delete[] g_prof.stop[st];
-        g_prof.start[st] = g_prof.stop[st] = nullptr;
-        g_prof.n[st] = 0;
-    }
-    g_prof.mask = 0;
-    g_prof.cap = 0;
+    prof_release();
     if (stage_mask == 0 || max_samples == 0) return MOE_OK;
+    g_prof.cap = max_samples;       // prof_release walks this many entries per enabled stage
     for (int st = 0; st < kNumStages; ++st) {
         if (!((stage_mask >> st) & 1u)) continue;
-        g_prof.start[st] = new hipEvent_t[max_samples];
-        g_prof.stop[st] = new hipEvent_t[max_samples];
+        g_prof.start[st] = new hipEvent_t[max_samples]();
+        g_prof.stop[st] = new hipEvent_t[max_samples]();
         for (int i = 0; i < max_samples; ++i) {
-            MOE_TRY_HIP(hipEventCreate(&g_prof.start[st][i]));
-            MOE_TRY_HIP(hipEventCreate(&g_prof.stop[st][i]));
+            hipError_t e = hipEventCreate(&g_prof.start[st][i]);
+            if (e == hipSuccess) e = hipEventCreate(&g_prof.stop[st][i]);
+            if (e != hipSuccess) {      // give back what was created so far, stay switched off
+                prof_release();
+                return hip_fail(e, "hipEventCreate (moe_profile_enable)");
+            }
         }
     }
-    g_prof.cap = max_samples;
     g_prof.mask = stage_mask;
     return MOE_OK;
 }
@@ -481,27 +498,40 @@ moe_status layer_forward(const moe_shape *s, int32_t n_chunks, const void *x,
     // is packed; unpack stream: combine of a chunk once its FFN is done.
     ChunkResources *r = nullptr;
     MOE_TRY(chunk_resources(&r));
+    // One call at a time enqueues on this device's side streams: two threads' records and
+    // waits on the shared events must not interleave.
+    std::lock_guard<std::mutex> enqueue(r->enqueue);
     MOE_TRY_HIP(hipEventRecord(r->planned, st));
     MOE_TRY_HIP(hipStreamWaitEvent(r->pack, r->planned, 0));
     MOE_TRY_HIP(hipStreamWaitEvent(r->unpack, r->planned, 0));
-    for (int c = 0; c < n_chunks; ++c) {
-        const int t0 = static_cast<int>(static_cast<int64_t>(c) * s->T / n_chunks);
-        const int t1 = static_cast<int>(static_cast<int64_t>(c + 1) * s->T / n_chunks);
-        MOE_TIMED(kStageScatter, r->pack, launch_scatter(*s, x, slot_of, xe, t0, t1, r->pack));
-        MOE_TRY_HIP(hipEventRecord(r->packed[c], r->pack));
-    }
-    for (int c = 0; c < n_chunks; ++c) {
-        const int t0 = static_cast<int>(static_cast<int64_t>(c) * s->T / n_chunks);
-        const int t1 = static_cast<int>(static_cast<int64_t>(c + 1) * s->T / n_chunks);
-        MOE_TRY_HIP(hipStreamWaitEvent(st, r->packed[c], 0));
-        MOE_TRY(launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, c, st));
-        MOE_TRY_HIP(hipEventRecord(r->computed[c], st));
-        MOE_TRY_HIP(hipStreamWaitEvent(r->unpack, r->computed[c], 0));
-        MOE_TIMED(kStageCombine, r->unpack,
-                  launch_combine(*s, ye, slot_of, gate, y, y_act, t0, t1, r->unpack));
-    }
-    MOE_TRY_HIP(hipEventRecord(r->unpacked, r->unpack));
-    MOE_TRY_HIP(hipStreamWaitEvent(st, r->unpacked, 0));
+    auto enqueue_chunks = [&]() -> moe_status {
+        for (int c = 0; c < n_chunks; ++c) {
+            const int t0 = static_cast<int>(static_cast<int64_t>(c) * s->T / n_chunks);
+            const int t1 = static_cast<int>(static_cast<int64_t>(c + 1) * s->T / n_chunks);
+            MOE_TIMED(kStageScatter, r->pack, launch_scatter(*s, x, slot_of, xe, t0, t1, r->pack));
+            MOE_TRY_HIP(hipEventRecord(r->packed[c], r->pack));
+        }
+        for (int c = 0; c < n_chunks; ++c) {
+            const int t0 = static_cast<int>(static_cast<int64_t>(c) * s->T / n_chunks);
+            const int t1 = static_cast<int>(static_cast<int64_t>(c + 1) * s->T / n_chunks);
+            MOE_TRY_HIP(hipStreamWaitEvent(st, r->packed[c], 0));
+            MOE_TRY(launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, c, st));
+            MOE_TRY_HIP(hipEventRecord(r->computed[c], st));
+            MOE_TRY_HIP(hipStreamWaitEvent(r->unpack, r->computed[c], 0));
+            MOE_TIMED(kStageCombine, r->unpack,
+                      launch_combine(*s, ye, slot_of, gate, y, y_act, t0, t1, r->unpack));
+        }
+        return MOE_OK;
+    };
+    const moe_status rc = enqueue_chunks();
+    // Join both side streams back into the caller's stream, also after a failure part-way:
+    // whatever was enqueued there must not outlive the call unobserved.
+    hipError_t je = hipEventRecord(r->unpacked, r->unpack);
+    if (je == hipSuccess) je = hipStreamWaitEvent(st, r->unpacked, 0);
+    if (je == hipSuccess) je = hipEventRecord(r->planned, r->pack);
+    if (je == hipSuccess) je = hipStreamWaitEvent(st, r->planned, 0);
+    if (rc != MOE_OK) return rc;
+    if (je != hipSuccess) return hip_fail(je, "joining the side streams");
     return MOE_OK;
 }
 

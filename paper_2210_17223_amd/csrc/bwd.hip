@@ -766,11 +766,7 @@ void launch_gemm_k(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, c
     auto kern = bwd_gemm_kernel<EPI, ACT, KTAIL, WN>;
     constexpr size_t kGemmLds = gemm_lds(WN);
     static PerDeviceOnce once;   // raising the dynamic LDS limit: once per kernel and device
-    if (once.first()) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  static_cast<int>(kGemmLds));
-    }
+    once.raise_lds(reinterpret_cast<const void *>(kern), static_cast<int>(kGemmLds));
     const int grid = static_cast<int>(align_up(static_cast<size_t>(grid_items), 8));
     hipEvent_t t0, t1;
     prof_kernel_events(stage, &t0, &t1);
@@ -801,10 +797,7 @@ void launch_wgrad(const uint16_t *A, const uint16_t *B, float *C, const int32_t 
     constexpr size_t kLds = 2 * 2 * kBK * 128 * sizeof(uint16_t);
     auto kern = wgrad_gemm_kernel<AF16>;
     static PerDeviceOnce once;
-    if (once.first()) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLds));
-    }
+    once.raise_lds(reinterpret_cast<const void *>(kern), static_cast<int>(kLds));
     const int tiles_m = (M + 127) / 128, tiles_n = (N + 127) / 128;
     const int grid = static_cast<int>(align_up(static_cast<size_t>(E) * tiles_m * tiles_n, 8));
     hipEvent_t t0, t1;
@@ -858,9 +851,7 @@ moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, c
         if (wbytes <= 64 * 1024 && T >= 16 * 256) {                                               \
             auto kern = gate_bwd_kernel<EP_, true>;                                               \
             static PerDeviceOnce once;                                                            \
-            if (once.first())                                                                     \
-                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                   \
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024); \
+            once.raise_lds(reinterpret_cast<const void *>(kern), 64 * 1024);                              \
             hipLaunchKernelGGL(kern, dim3(ceil_div(T, 16)), dim3(1024), wbytes,                   \
                                st, x, Wgp, bias, bias_stride, expert_idx, slot_of, dgate, w.dxe,  \
                                w.dz, dx, T, d, dPad, E, k, R);                                    \

@@ -306,6 +306,7 @@ Op *find_op(moe_comm *c, int64_t id)
 // Side stream and events of moe_layer_padded's own link, per device, kept for the process.
 struct PaddedResources {
     bool ready = false;
+    std::mutex enqueue;        // held while a call enqueues on the link stream
     hipStream_t link = nullptr;
     hipEvent_t packed[kMaxChunks] = {}, arrived[kMaxChunks] = {}, computed[kMaxChunks] = {};
     hipEvent_t returned = nullptr;
@@ -752,6 +753,8 @@ moe_status moe_layer_padded(const moe_shape *s, int32_t n_micro, moe_comm *link,
 
     PaddedResources *r = nullptr;
     MOE_TRY(padded_resources(&r));
+    // one call at a time enqueues on this device's link stream and shared events
+    std::lock_guard<std::mutex> enqueue(r->enqueue);
     auto range = [&](int m, int64_t *r0, int64_t *r1) {
         *r0 = static_cast<int64_t>(m) * C / n_micro;
         *r1 = static_cast<int64_t>(m + 1) * C / n_micro;

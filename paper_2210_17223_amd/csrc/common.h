@@ -5,6 +5,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "moe.h"
 
 namespace moe {
@@ -25,18 +28,22 @@ moe_status hip_fail(hipError_t e, const char *what);
         if (e_ != hipSuccess) return ::moe::hip_fail(e_, #expr);      \
     } while (0)
 
-// True the first time it is called for the current device with this flag set (a kernel's
-// dynamic-LDS limit is raised once per kernel and per device).
+// Raises a kernel's dynamic-LDS limit once per kernel and per device.  Any host thread may be
+// the first to launch a kernel: the flag word is atomic, and a thread that arrives while
+// another is still setting the attribute waits for it instead of launching too early.
 struct PerDeviceOnce {
-    uint64_t done = 0;                       // bit per device ordinal (up to 64 devices)
-    bool first()
+    std::atomic<uint64_t> done{0};           // bit per device ordinal (up to 64 devices)
+    std::mutex setting;
+    void raise_lds(const void *kernel, int bytes)
     {
         int dev = 0;
         (void)hipGetDevice(&dev);
         const uint64_t bit = 1ull << (dev & 63);
-        if (done & bit) return false;
-        done |= bit;
-        return true;
+        if (done.load(std::memory_order_acquire) & bit) return;
+        std::lock_guard<std::mutex> lock(setting);
+        if (done.load(std::memory_order_relaxed) & bit) return;
+        (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        done.fetch_or(bit, std::memory_order_release);
     }
 };
 

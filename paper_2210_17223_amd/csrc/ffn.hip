@@ -426,10 +426,7 @@ void launch_mfma_cfg_k(const uint16_t *A, const uint16_t *W, const float *bias, 
     constexpr size_t lds = 2 * (BM + BN) * (64 + 8) * sizeof(uint16_t);
     auto kern = grouped_gemm_mfma_kernel<F16, TOut, ACT, WM, WN, TM, TN, KTAIL, KEEP>;
     static PerDeviceOnce once;   // raising the dynamic LDS limit: once per kernel and device
-    if (once.first()) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-    }
+    once.raise_lds(reinterpret_cast<const void *>(kern), static_cast<int>(lds));
     const int grid = static_cast<int>(align_up(static_cast<size_t>(max_items), 8));
     hipEvent_t t0, t1;
     prof_kernel_events(stage, &t0, &t1);

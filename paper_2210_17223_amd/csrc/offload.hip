@@ -18,6 +18,7 @@ struct OffloadResources {
     hipEvent_t freed[kMaxExperts] = {};     // slot's expert computed
     hipEvent_t begin = nullptr;
     bool ok = false;
+    std::mutex enqueue;                     // held while a call enqueues on the copy stream
 };
 OffloadResources g_res[16];
 std::mutex g_res_mutex;
@@ -117,6 +118,8 @@ moe_status moe_expert_ffn_offloaded(const moe_shape *s, const void *xe, const in
     OffloadResources *r = nullptr;
     const moe_status rs = resources(&r);
     if (rs != MOE_OK) return rs;
+    // one call at a time enqueues on this device's copy stream and shared events
+    std::lock_guard<std::mutex> enqueue(r->enqueue);
     Workspace w;
     layout(*s, workspace, &w);
     hipStream_t st = static_cast<hipStream_t>(stream);

@@ -41,9 +41,11 @@ __device__ __forceinline__ uint64_t lanes_below(int lane)
     return (1ull << lane) - 1ull;
 }
 
-__device__ __forceinline__ int clamp_expert(int e, int E)
+// An index outside [0, E) names no expert (a padding marker such as -1): the assignment is
+// left out of the counts, takes no slot and gets slot_of = -1.
+__device__ __forceinline__ bool names_expert(int e, int E)
 {
-    return static_cast<unsigned>(e) < static_cast<unsigned>(E) ? e : E - 1;
+    return static_cast<unsigned>(e) < static_cast<unsigned>(E);
 }
 
 __device__ void build_items(const GemmPlan &gp, WorkItem *__restrict__ items,
@@ -64,8 +66,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(
     const int base = seg * seg_len;
     for (int off = 0; off < seg_len; off += kWave) {
         const int i = base + off + lane;
-        const bool valid = i < n && off + lane < seg_len;
-        const int e = valid ? clamp_expert(expert_idx[i], E) : 0;
+        const bool in_seg = i < n && off + lane < seg_len;
+        const int e_raw = in_seg ? expert_idx[i] : 0;
+        const bool valid = in_seg && names_expert(e_raw, E);
+        const int e = valid ? e_raw : 0;
         const uint64_t peers = same_expert_lanes(e, valid);
         const bool leader = valid && (peers & lanes_below(lane)) == 0;
         if (leader) run[wave][e] += __popcll(peers);
@@ -174,17 +178,19 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rank_kernel(
     __syncthreads();
     for (int off = 0; off < seg_len; off += kWave) {
         const int i = base + off + lane;
-        const bool valid = i < n && off + lane < seg_len;
-        const int e = valid ? clamp_expert(expert_idx[i], E) : 0;
+        const bool in_seg = i < n && off + lane < seg_len;
+        const int e_raw = in_seg ? expert_idx[i] : 0;
+        const bool valid = in_seg && names_expert(e_raw, E);
+        const int e = valid ? e_raw : 0;
         const uint64_t peers = same_expert_lanes(e, valid);
         const int rank = __popcll(peers & lanes_below(lane));
         const int32_t before = run[wave][e];
         __builtin_amdgcn_wave_barrier();
         if (valid && rank == 0) run[wave][e] = before + __popcll(peers);
         __builtin_amdgcn_wave_barrier();
-        if (valid) {
+        if (in_seg) {
             const int32_t pos = before + rank;
-            const int32_t slot = pos < capacity ? off_s[e] + pos : -1;
+            const int32_t slot = valid && pos < capacity ? off_s[e] + pos : -1;
             slot_of[i] = slot;
             if (slot >= 0) src_of[slot] = i;
         }
@@ -333,8 +339,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rank_prefix_kernel(
     if (ranks) {
         for (int off = 0; off < seg_len; off += kWave) {
             const int i = base + off + lane;
-            const bool valid = i < n && off + lane < seg_len;
-            const int e = valid ? clamp_expert(expert_idx[i], E) : 0;
+            const bool in_seg = i < n && off + lane < seg_len;
+            const int e_raw = in_seg ? expert_idx[i] : 0;
+            const bool valid = in_seg && names_expert(e_raw, E);
+            const int e = valid ? e_raw : 0;
             const uint64_t peers = same_expert_lanes(e, valid);
             const int rank = __popcll(peers & lanes_below(lane));
             const int32_t before = run[wave][e];
@@ -342,9 +350,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rank_prefix_kernel(
             if (valid && rank == 0) run[wave][e] = before + __popcll(peers);
             __builtin_amdgcn_wave_barrier();
             int32_t slot = -1;
-            if (valid) {
+            if (in_seg) {
                 const int32_t pos = before + rank;
-                slot = pos < capacity ? off_s[e] + pos : -1;
+                slot = valid && pos < capacity ? off_s[e] + pos : -1;
                 slot_of[i] = slot;
                 if (slot >= 0) src_of[slot] = i;
             }

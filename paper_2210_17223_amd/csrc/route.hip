@@ -621,10 +621,7 @@ moe_status launch_route_t(const moe_shape &s, const XT *x, const float *Wgp,
     if (cpw == CPW_) {                                                                        \
         auto kern = route_chain_kernel<XT, CPW_>;                                             \
         static PerDeviceOnce once;                                                            \
-        if (once.first()) {                                                                   \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                   \
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024); \
-        }                                                                                     \
+        once.raise_lds(reinterpret_cast<const void *>(kern), 72 * 1024);                              \
         hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, x, Wgp, bias, bias_stride, \
                            expert_idx, gate, seg_cnt, s.T, s.d_model, dP, s.E, EP, rs.tb,     \
                            s.k, s.renorm_topk);                                               \
@@ -642,10 +639,7 @@ moe_status launch_route_t(const moe_shape &s, const XT *x, const float *Wgp,
     if (rs.tpl == TPL_ && rs.epl == EPL_) {                                                   \
         auto kern = route_kernel<XT, TPL_, EPL_>;                                             \
         static PerDeviceOnce once;                                                            \
-        if (once.first()) {                                                                   \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                   \
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024); \
-        }                                                                                     \
+        once.raise_lds(reinterpret_cast<const void *>(kern), 72 * 1024);                              \
         hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, x, Wgp, bias, bias_stride, \
                            expert_idx, gate, seg_cnt, s.T, s.d_model, dP, s.E, EP, rs.tb,     \
                            s.k, s.renorm_topk);                                               \

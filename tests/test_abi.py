@@ -34,12 +34,25 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), f"{name} is declared under include/ but not exported"
 
 
-def test_capacity_matches_generator_formula():
-    for c in wl.CONFIGS.values():
-        want = wl.capacity(c["T"], c["E"], c["k"], c["cf"])
-        assert moe.moe_capacity(c["T"], c["E"], c["k"], c["cf"] or 0.0) == want
+def test_capacity_literals_and_rounding():
+    want = {"tiny_fp32": 128, "gpt2s_moe": 640, "skewed": 1280, "large_chunked": 1024,
+            "infer_stack": 256}
+    for name, c in wl.CONFIGS.items():
+        assert moe.moe_capacity(c["T"], c["E"], c["k"], c["cf"] or 0.0) == want[name] == c["C"]
     assert moe.moe_capacity(10, 4, 1, 1.0) == 3
     assert moe.moe_capacity(8, 4, 1, 1.0) == 2
+    assert moe.moe_capacity(3, 1, 1, 1.1) == 4                       # 3.3000000000000003 rounds up
+    assert moe.moe_capacity(1 << 20, 1 << 20, 1, 1.0 + 2.0 ** -52) == 2
+    assert moe.moe_capacity(100, 8, 2, 1.1) == 28
+
+
+def test_capacity_agrees_with_the_oracle_on_a_grid():
+    import oracle
+    for T in (1, 7, 96, 1000, 4096, 32768):
+        for E in (1, 3, 8, 64):
+            for k in (1, 2, 4):
+                for cf in (0.5, 1.0, 1.1, 1.2, 1.25, 2.0, 1.0 / 3.0):
+                    assert moe.moe_capacity(T, E, k, cf) == max(1, oracle.capacity(T, E, k, cf)), (T, E, k, cf)
 
 
 def test_sizes():

@@ -1,8 +1,8 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times.
 Integers (expert choice, counts, offsets, slots, sources) are compared in full and
-bit-exactly; packed rows in full and bit-exactly; layer outputs on sampled tokens the
-oracle computes one by one (random tokens plus the tokens with the largest gate weights,
-where the error bound is tightest), plus properties that hold at any size."""
+bit-exactly; packed rows in full and bit-exactly; layer outputs element by element for
+EVERY token (the oracle's fp64 FFN over all kept rows takes seconds to tens of seconds on
+the machine's host cores), plus properties that hold at any size."""
 import numpy as np
 import pytest
 import torch
@@ -24,23 +24,16 @@ def oracle_routing(li):
     return idx, gate, count, off, slot_of, src_of
 
 
-def sample_tokens(li, gate, n_random=768, n_top=256, seed=123):
-    rng = np.random.default_rng(seed)
-    rnd = rng.choice(li.T, size=min(n_random, li.T), replace=False)
-    top = np.argsort(-gate.max(1))[:n_top]
-    return np.unique(np.concatenate([rnd, top])).astype(np.int32)
-
-
 @pytest.mark.parametrize("name,chunk_list", [("gpt2s_moe", (1,)), ("skewed", (1,)),
                                              ("large_chunked", (1, 4, 8))])
 def test_full_size_layer(name, chunk_list):
     li = wl.make_layer(wl.CONFIGS[name], seed=0, threads=16)
     idx, gate, count, off, slot_of, src_of = oracle_routing(li)
     A = int(off[-1])
-    toks = sample_tokens(li, gate)
+    print(f"{name}: oracle over all {li.T} tokens ({A} rows) ...", flush=True)
     o = oracle.moe_layer(li.x, li.Wg, li.W1, li.W2, k=li.k, capacity=li.C, bias=li.gate_bias,
-                         bias_stride=li.bias_token_stride, tokens=toks)
-    assert np.array_equal(o.slot_of, slot_of)
+                         bias_stride=li.bias_token_stride)
+    assert np.array_equal(o.slot_of, slot_of) and o.y.shape == (li.T, li.d)
     rms = float(np.sqrt(np.mean(np.square(o.y.astype(np.float64)))))
     fully_dropped = (slot_of.reshape(li.T, li.k) < 0).all(1)
 
@@ -58,7 +51,8 @@ def test_full_size_layer(name, chunk_list):
         assert np.array_equal(xe[:A].view(np.uint32), li.x[src_of // li.k].view(np.uint32))
         y = L.b["y"].cpu().numpy().reshape(li.T, li.d)
         assert np.isfinite(y).all()
-        err = float(np.abs(y[toks].astype(np.float64) - o.y).max() / rms)
+        err = float(np.abs(y - o.y).max() / rms)          # every element of every token
+        print(f"{name} n_chunks={n_chunks}: max-abs err / RMS = {err:.3e}", flush=True)
         assert err <= TOL_BF16, f"{name} n_chunks={n_chunks}: max-abs err / RMS = {err}"
         assert not y[fully_dropped].any()                 # dropped tokens give zeros
         if ref_bits is None:
@@ -127,12 +121,17 @@ def test_inference_stack():
         # the two chains' inputs differ by accumulated rounding, and a gate weight is a
         # softmax of logits: compare it absolutely
         np.testing.assert_allclose(gg, wg, rtol=0, atol=3e-2)
-        # There is no normalisation between the layers, so the activations double per layer
-        # and the gate's sensitivity to an input ulp grows with them; the output is linear in
-        # the gate weights, and a single element's deviation follows the gate's.  (a) above
-        # is the parity gate; here the drift of the whole output is bounded in the mean.
+        # Layer 0 reads the same input on both sides: it meets the layer tolerance, max-abs,
+        # exactly as in (a).  From layer 1 on the two chains' inputs differ by accumulated
+        # rounding; there is no normalisation between the layers, so the activations double
+        # per layer and the gate's sensitivity to an input ulp doubles with them, and the
+        # output is linear in the gate weights: the max-abs bound doubles per layer, and the
+        # drift of the whole output stays within the layer tolerance in the mean.
         y = L.b["y"].cpu().numpy().reshape(T, d).astype(np.float64)
+        err = rel_rms_err(y, o.y)
         drift = np.linalg.norm(y - o.y) / np.linalg.norm(o.y)
+        print(f"free-running layer {l}: max-abs err / RMS = {err:.3e}, Frobenius drift = {drift:.3e}", flush=True)
+        assert err <= TOL_BF16 * 2 ** l, f"layer {l}: max-abs err / RMS = {err}"
         assert drift <= TOL_BF16, f"layer {l}: relative Frobenius drift {drift}"
         x_dev = L.b["y_act"].view(T, d)
 

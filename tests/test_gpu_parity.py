@@ -82,6 +82,39 @@ def test_entry_points_one_by_one(name):
     assert not y[dropped].any()
 
 
+@pytest.mark.parametrize("name", ["gpt2s_small", "tiny_fp32_ragged", "skewed_small"])
+def test_dispatch_skips_indices_that_name_no_expert(name):
+    """moe_dispatch with padding markers (-1, E, a large value) in expert_idx: those
+    assignments are in no count and take no slot; everything else as the oracle plans it."""
+    li = wl.make_layer(SMALL[name], seed=6)
+    z = oracle.gate_logits(li.x, li.Wg, li.gate_bias, li.bias_token_stride)
+    idx, _ = oracle.topk_softmax(z, li.k)
+    prng = np.random.Generator(np.random.PCG64(99))
+    flat = idx.reshape(-1).copy()
+    hit = prng.random(flat.size) < 0.15
+    flat[hit] = prng.choice(np.array([-1, li.E, li.E + 5, -7, 2 ** 30], np.int32), size=int(hit.sum()))
+    flat[:3] = (-1, li.E, -1)                             # a whole wavefront's first lanes
+    idx = flat.reshape(li.T, li.k)
+    count, off, slot_of, src_of = oracle.plan(idx, li.E, li.C)
+    A = int(off[-1])
+    xe_ref = oracle.scatter(li.x, slot_of, li.k, A)
+    s = shape_of(li)
+    L = DeviceLayer(li, s)
+    b = L.b
+    b["xe"].zero_()
+    b["slot_of"].fill_(12345)
+    moe.moe_dispatch(s, L.x, torch.from_numpy(flat).to(DEV), b["counts"], b["offsets"], b["slot_of"],
+                     b["src_of"], b["xe"], b["workspace"])
+    torch.cuda.synchronize()
+    assert np.array_equal(b["counts"].cpu().numpy(), count)
+    assert np.array_equal(b["offsets"].cpu().numpy(), off)
+    assert np.array_equal(b["slot_of"].cpu().numpy(), slot_of)
+    assert np.array_equal(b["src_of"].cpu().numpy()[:A], src_of)
+    xe = download(b["xe"]).reshape(-1, li.d)
+    assert np.array_equal(xe[:A].view(np.uint32), xe_ref.view(np.uint32))
+    assert not xe[A:].any()
+
+
 @pytest.mark.parametrize("name", list(SMALL))
 def test_whole_layer_and_chunk_invariance(name):
     li = wl.make_layer(SMALL[name], seed=1)

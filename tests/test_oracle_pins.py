@@ -39,7 +39,20 @@ def test_capacity_closed_forms():
     want = {"tiny_fp32": 128, "gpt2s_moe": 640, "skewed": 1280,
             "large_chunked": 1024, "infer_stack": 256}
     for name, c in wl.CONFIGS.items():
-        assert wl.capacity(c["T"], c["E"], c["k"], c["cf"]) == want[name]
+        assert oracle.capacity(c["T"], c["E"], c["k"], c["cf"]) == want[name]
+        assert c["C"] == want[name]                  # the literal the generator hands to both sides
+    # exact quotients stay, anything above an integer rounds up -- also by one part in 2^52
+    assert oracle.capacity(8, 4, 1, 1.0) == 2
+    assert oracle.capacity(10, 4, 1, 1.0) == 3
+    assert oracle.capacity(10, 4, 1, 1.2) == 3       # 1.2*10 is exactly 12.0 in double
+    assert oracle.capacity(100, 8, 2, 1.1) == 28     # 27.5...
+    assert oracle.capacity(3, 1, 1, 1.1) == 4        # 3.3000000000000003
+    assert oracle.capacity(1 << 20, 1 << 20, 1, 1.0 + 2.0 ** -52) == 2
+    assert oracle.capacity(7, 7, 1, 1.0) == 1
+    assert oracle.capacity(256, 8, 2, None) == 256
+    # integer cross-check where cf is a ratio of small integers: ceil(p*k*T / (q*E))
+    for T, E, k, p, q in [(4096, 16, 2, 5, 4), (1000, 7, 2, 3, 2), (333, 5, 1, 1, 1), (96, 4, 2, 1, 1)]:
+        assert oracle.capacity(T, E, k, p / q) == -((-p * k * T) // (q * E))
 
 
 # ---------------------------------------------------------------- gate logits
@@ -150,7 +163,9 @@ def plan_by_definition(idx, E, C):
     slot_of, src_of = [], {}
     for i in range(n):
         pos = sum(1 for ii in range(i) if flat[ii] == flat[i])
-        if pos < C:
+        if not 0 <= flat[i] < E:              # names no expert: dispatched nowhere
+            slot_of.append(-1)
+        elif pos < C:
             slot_of.append(off[flat[i]] + pos)
             src_of[off[flat[i]] + pos] = i
         else:
@@ -168,6 +183,32 @@ def test_plan_brute_force_every_assignment(T, E, k):
             want = plan_by_definition(idx, E, C)
             assert got[0].tolist() == want[0] and got[1].tolist() == want[1]
             assert got[2].tolist() == want[2] and got[3].tolist() == want[3]
+
+
+def test_plan_skips_indices_that_name_no_expert():
+    """Every assignment vector of 5 entries over {-1, 0, 1, 2 (= E, out of range)} with E = 2:
+    entries outside [0, E) are in no count and take no slot; the rest are planned as if the
+    others were absent."""
+    E = 2
+    for assign in itertools.product((-1, 0, 1, 2), repeat=5):
+        idx = np.array(assign, np.int32).reshape(5, 1)
+        for C in (1, 2, 5):
+            count, off, slot_of, src_of = oracle.plan(idx, E, C)
+            want = plan_by_definition(idx, E, C)
+            assert count.tolist() == want[0] and off.tolist() == want[1]
+            assert slot_of.tolist() == want[2] and src_of.tolist() == want[3]
+            # the same plan as for the valid entries alone
+            keep = [i for i, v in enumerate(assign) if 0 <= v < E]
+            sub = oracle.plan(idx[keep], E, C) if keep else None
+            if sub is not None:
+                assert count.tolist() == sub[0].tolist() and off.tolist() == sub[1].tolist()
+                assert slot_of[keep].tolist() == sub[2].tolist()
+                assert [keep.index(i) for i in src_of.tolist()] == sub[3].tolist()
+            assert all(slot_of[i] == -1 for i, v in enumerate(assign) if not 0 <= v < E)
+    # a hand-worked case: E = 3, C = 1
+    count, off, slot_of, src_of = oracle.plan(np.array([[2], [-1], [2], [0], [7]], np.int32), 3, 1)
+    assert count.tolist() == [1, 0, 2] and off.tolist() == [0, 1, 1, 2]
+    assert slot_of.tolist() == [1, -1, -1, 0, -1] and src_of.tolist() == [3, 0]
 
 
 def test_plan_brute_force_through_the_gate():

@@ -109,6 +109,24 @@ def test_oversubscription_wraps():
     assert hosted == [[0, 1], [0, 2], [0, 3]]
 
 
+def test_replication_is_capped_at_the_device_count():
+    """Sec. 5.2 replicates a popular expert on more devices; it cannot sit on more devices
+    than exist.  Hand-worked: w = 25, W = 10 asks for round(2.5) = 3 devices, N = 2 gives 2."""
+    replicas, hosted, used = so.schedule([25], 10, [True], N=2, max_pack=4)
+    assert replicas == [2] and hosted == [[0], [0]] and used == 2
+    # one device short: 3.4 -> 3 wanted, 3 exist -> 3; 3.5 -> 4 wanted, 3 exist -> 3
+    assert so.schedule([34], 10, [True], N=3, max_pack=4)[0] == [3]
+    assert so.schedule([35], 10, [True], N=3, max_pack=4)[0] == [3]
+    # the cap is per expert: a second expert still gets its own (wrapped) device, and every
+    # device hosts each expert at most once
+    replicas, hosted, used = so.schedule([90, 10, 4], 10, [True] * 3, N=2, max_pack=4)
+    assert replicas == [2, 1, 1] and used == 2
+    assert hosted == [[0, 1], [0, 2]]
+    # Eq. (1) side of the same case: all N_t tokens expect expert 0 with probability 1 on N = 2
+    # devices -> n_0 = N = 2 exactly, never more
+    assert so.devices_for_expert(5 << so.FIX, 5, 2) == 2.0
+
+
 def test_top_lists():
     assert so.top_list([5, 9, 9, 1], 3) == [1, 2, 0]
     assert so.lists_identical([5, 9, 9, 1], [50, 90, 91, 10], 1) is False      # order matters

@@ -20,31 +20,42 @@ import numpy as np
 # uses top-2 and inference top-1/2 gates (Sec. 7.1).  The sizes below are the
 # benchmark's own synthetic shapes.
 CONFIGS: Dict[str, dict] = {
-    "tiny_fp32": dict(T=512, d=128, E=4, h=256, k=1, cf=1.0, dtype="f32",
+    "tiny_fp32": dict(T=512, d=128, E=4, h=256, k=1, cf=1.0, C=128, dtype="f32",
                       skew=None, layers=1),
-    "gpt2s_moe": dict(T=4096, d=768, E=16, h=3072, k=2, cf=1.25, dtype="bf16",
+    "gpt2s_moe": dict(T=4096, d=768, E=16, h=3072, k=2, cf=1.25, C=640, dtype="bf16",
                       skew=None, layers=1),
-    "skewed": dict(T=16384, d=1024, E=32, h=4096, k=2, cf=1.25, dtype="bf16",
+    "skewed": dict(T=16384, d=1024, E=32, h=4096, k=2, cf=1.25, C=1280, dtype="bf16",
                    skew=("zipf_bias", 1.2), layers=1),
-    "large_chunked": dict(T=32768, d=2048, E=64, h=8192, k=2, cf=1.0,
+    "large_chunked": dict(T=32768, d=2048, E=64, h=8192, k=2, cf=1.0, C=1024,
                           dtype="bf16", skew=None, layers=1),
-    "infer_stack": dict(T=256, d=4096, E=8, h=14336, k=2, cf=None, dtype="bf16",
+    "infer_stack": dict(T=256, d=4096, E=8, h=14336, k=2, cf=None, C=256, dtype="bf16",
                         skew=("markov", 1.0, 0.7), layers=4),
 }
+# `C`, the slots per expert, is an INPUT of both the library and the oracle (each also has a
+# capacity function of its own, tested against these literals and against each other).
 
 
 def scaled(name: str, **over) -> dict:
-    """A copy of a named configuration with some sizes overridden (test sizes)."""
+    """A copy of a named configuration with some sizes overridden (test sizes).  Unless the
+    caller passes `C`, the copy's slot count is re-sized for its new shape."""
     cfg = dict(CONFIGS[name])
     cfg.update(over)
+    if "C" not in over:
+        cfg["C"] = test_slots(cfg["T"], cfg["E"], cfg["k"], cfg.get("cf"))
     return cfg
 
 
-def capacity(T: int, E: int, k: int, cf: Optional[float]) -> int:
-    """Slots per expert: ceil(cf*k*T/E); cf=None means no dropping (C = T)."""
+def test_slots(T: int, E: int, k: int, cf: Optional[float]) -> int:
+    """Sizes the slot count of a scaled-down test input: about cf times an even share of
+    the T*k assignments per expert, rounded up; cf=None gives every expert room for all
+    tokens.  This only picks an input; what a capacity factor MEANS is stated, and pinned,
+    by the oracle's and the library's own capacity functions."""
     if cf is None:
         return int(T)
-    return int(math.ceil(cf * k * T / E - 1e-9))
+    return int(math.ceil(cf * k * T / E))
+
+
+test_slots.__test__ = False     # not a pytest case, whatever module imports it
 
 
 def bf16_bits(a: np.ndarray) -> np.ndarray:
@@ -159,7 +170,7 @@ def make_layer(cfg: dict, seed: int = 0, threads: int = 8,
     else:
         W1 = np.zeros((E, 0, 0), np.float32)
         W2 = np.zeros((E, 0, 0), np.float32)
-    C = capacity(T, E, k, cfg.get("cf"))
+    C = int(cfg["C"]) if "C" in cfg else test_slots(T, E, k, cfg.get("cf"))
     li = LayerInputs(cfg=cfg, T=T, d=d, E=E, h=h, k=k, C=C, dtype=dtype,
                      x=x, Wg=Wg, W1=W1, W2=W2)
     skew = cfg.get("skew")
