@@ -51,6 +51,9 @@ def main() -> int:
                     help="one of workloads.CONFIGS (default: the largest single-GPU configuration), "
                          "or 'popularity': the inference scheduler's estimate + two-phase decision")
     ap.add_argument("--chunks", type=int, default=1, help="n_chunks of moe_layer_chunked")
+    ap.add_argument("--group-rows", type=int, default=0,
+                    help="with --chunks > 1: rows per expert an FFN launch must hold on average "
+                         "(moe_tune_ffn_group_rows; 0 = the library's default, 1 = one FFN launch per chunk)")
     ap.add_argument("--comm", action="store_true",
                     help="the workload's layer in the padded equal-split layout with both all-to-alls "
                          "on the stand-in link (moe_layer_padded), alone and while a gradient "
@@ -106,6 +109,8 @@ def main() -> int:
         return bench_popularity(args, moe, np, torch, dev)
     if args.comm:
         return bench_comm(args, moe, wl, np, torch, dev)
+    if args.group_rows > 0:
+        moe.moe_tune_ffn_group_rows(args.group_rows)
     cfg = wl.CONFIGS[args.workload]
     n_layers = cfg["layers"]
     host = wl.make_stack(cfg, seed=0, threads=16) if n_layers > 1 else [wl.make_layer(cfg, seed=0, threads=16)]
@@ -278,7 +283,7 @@ def main() -> int:
         "config": {"workload": f"{args.workload}: T={l0.T} d_model={l0.d} E={l0.E} d_ff={l0.h} "
                                f"k={l0.k} capacity={l0.C} {l0.dtype}, seed 0"
                                + (f", {n_layers} layers back to back (value counts layer-tokens)" if n_layers > 1 else ""),
-                   "n_chunks": args.chunks, "kept_rows_A": A,
+                   "n_chunks": args.chunks, "ffn_group_rows": moe.moe_tune_ffn_group_rows(0), "kept_rows_A": A,
                    "dropped_assignments": float(l0.T * l0.k - A),
                    "count_min": int(min(c.min() for c in cnts)), "count_max": int(max(c.max() for c in cnts))},
         "roofline": roof,
@@ -383,7 +388,7 @@ def main() -> int:
             out["stages_us"] = st
             out["stages_us_median"] = med
             out["stages_us_min"] = mn
-        if args.chunks > 1:
+        if args.chunks > 1 and st["scatter"] is not None:
             # How much of the pack and unpack time the chunk pipeline hides behind the expert
             # FFN (Sec. 4.2's pipelining efficiency, with the pack kernel in the all-to-all's
             # place): 1 - (t_pipelined - t_ffn) / (t_pack + t_unpack), stage times summed over
@@ -521,7 +526,8 @@ def bench_comm(args, moe, wl, np, torch, dev) -> int:
              slot_of=i32(li.T * li.k), src_of=i32(slots),
              xs=torch.empty(slots * li.d, dtype=s.torch_dtype, device=dev),
              xr=torch.empty(slots * li.d, dtype=s.torch_dtype, device=dev),
-             ys=torch.zeros(slots * li.d, device=dev), yr=torch.zeros(slots * li.d, device=dev),
+             ys=torch.zeros(slots * li.d, dtype=s.ye_dtype, device=dev),
+             yr=torch.zeros(slots * li.d, dtype=s.ye_dtype, device=dev),
              y=torch.empty(li.T * li.d, device=dev))
     ws = {n: torch.empty(moe.moe_padded_workspace_bytes(s, n), dtype=torch.uint8, device=dev) for n in (1, 2, 4, 8)}
 
@@ -545,7 +551,8 @@ def bench_comm(args, moe, wl, np, torch, dev) -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
-    a2a_bytes = slots * li.d * (esz + 4)                      # both all-to-alls of one layer
+    ysz = p["ys"].element_size()
+    a2a_bytes = slots * li.d * (esz + ysz)                    # both all-to-alls of one layer
     res = {"compact_layer_ms": timed(compact, args.steps, args.warmup)}
     for n in (1, 2, 4, 8):
         res[f"padded_own_link_n{n}_ms"] = timed(lambda: padded(n), args.steps, args.warmup)
@@ -555,11 +562,11 @@ def bench_comm(args, moe, wl, np, torch, dev) -> int:
     c = comm.moe_comm_create(comm.PRIORITY, args.link_blocks, 2)
     link_ms = []
     for i in range(6):
-        op = comm.moe_comm_submit(c, comm.ALL_TO_ALL, p["ys"], p["yr"], li.E, li.C, li.d * 4, 1)
+        op = comm.moe_comm_submit(c, comm.ALL_TO_ALL, p["ys"], p["yr"], li.E, li.C, li.d * ysz, 1)
         comm.moe_comm_post(c, op, 0, 1)
         link_ms.append(comm.moe_comm_finish(c, op))
     comm.moe_comm_destroy(c)
-    link_gbps = slots * li.d * 4 / (min(link_ms[1:]) * 1e-3) / 1e9
+    link_gbps = slots * li.d * ysz / (min(link_ms[1:]) * 1e-3) / 1e9
     res["link_GBps"] = link_gbps
 
     # (b) contention: the layer through a scheduler that also carries a gradient allreduce
@@ -613,7 +620,7 @@ def bench_comm(args, moe, wl, np, torch, dev) -> int:
            "roofline": {"bound": "hbm", "kernel": "link_copy_kernel (the stand-in link, one all-to-all's bytes)",
                         "achieved": 2 * link_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                         "frac": 2 * link_gbps / PEAK_HBM_GBPS, "traffic": None,
-                        "avg_launch_us": min(link_ms[1:]) * 1e3, "algorithmic_bytes": 2 * slots * li.d * 4,
+                        "avg_launch_us": min(link_ms[1:]) * 1e3, "algorithmic_bytes": 2 * slots * li.d * ysz,
                         "note": "read + write of every byte; the kernel is confined to link_blocks workgroups "
                                 "on purpose (it stands for a network link), so the fraction is a setting, "
                                 "not an achievement"},

@@ -40,9 +40,12 @@
  *   - Inputs are assumed finite.
  *
  * Element types.  `dtype` is the storage type of x, Wg, W1, W2, xe.  Gate logits,
- * softmax and gate weights are fp32.  The expert outputs ye and the layer output y
- * are fp32 for both dtypes: an expert's output stays in the accumulator's
- * precision until the weighted sum over the selected experts is complete.
+ * softmax and gate weights are fp32.  MOE_BF16 layers: the hidden activations and
+ * the expert outputs ye are stored in fp16 (the payload of the second all-to-all is
+ * then two bytes per element, as the first one's); the weighted sum over the selected
+ * experts is accumulated in fp32 and the layer output y is fp32 (a 16-bit y would
+ * spend the whole error budget on its own rounding of the largest elements).
+ * MOE_F32 layers: everything fp32.
  */
 #ifndef MOE_H
 #define MOE_H
@@ -157,18 +160,19 @@ moe_status moe_dispatch(const moe_shape *s, const void *x, const int32_t *expert
 /* Expert FFN (Sec. 2.1): for slot r of expert e,
  *   ye[r,:] = act(xe[r,:] W1[e] + b1[e]) W2[e] + b2[e].
  *   W1p, W2p from moe_pack_weights; b1 fp32 [E,d_ff] and b2 fp32 [E,d_model] may
- *   be NULL; ye fp32 [moe_max_rows, d_model].  Experts with no rows read no
- *   weights.  Rows at or beyond offsets[E] are left untouched. */
+ *   be NULL; ye [moe_max_rows, d_model], fp16 for MOE_BF16 layers and fp32 for MOE_F32
+ *   layers.  Experts with no rows read no weights.  Rows at or beyond offsets[E] are
+ *   left untouched. */
 moe_status moe_expert_ffn(const moe_shape *s, const void *xe, const int32_t *offsets,
                           const void *W1p, const float *b1, const void *W2p,
-                          const float *b2, float *ye, void *workspace, void *stream);
+                          const float *b2, void *ye, void *workspace, void *stream);
 
 /* Combine = unpack after the second all-to-all (Sec. 2.2, forward-pass timeline):
  *   y[t,:] = sum over kept j of gate[t,j] * ye[slot_of[t*k+j],:]  (fp32, ascending j),
  * zero for a token with no kept assignment.
- *   y fp32 [T, d_model].  y_act: NULL, or [T, d_model] in `dtype` receiving y
+ *   ye as moe_expert_ffn writes it (fp16 / fp32 by dtype); y fp32 [T, d_model].  y_act: NULL, or [T, d_model] in `dtype` receiving y
  *   rounded to nearest-even (the next layer's input in a stack). */
-moe_status moe_combine(const moe_shape *s, const float *ye, const int32_t *slot_of,
+moe_status moe_combine(const moe_shape *s, const void *ye, const int32_t *slot_of,
                        const float *gate, float *y, void *y_act, void *stream);
 
 /* The whole layer with the token stream cut into n_chunks contiguous parts
@@ -176,7 +180,15 @@ moe_status moe_combine(const moe_shape *s, const float *ye, const int32_t *slot_
  * Routing and the dispatch plan are computed once over all T tokens, so every
  * output is identical for every n_chunks (Sec. 7.1: the scheduling does not change
  * what is computed).  Packing of chunk c+1 and unpacking of chunk c-1 run on side
- * streams concurrently with the expert FFN of chunk c (Sec. 4.2).
+ * streams concurrently with the expert FFN of chunk c (Sec. 4.2).  In MOE_BF16 layers
+ * the first expert GEMM reads its rows straight from x through src_of (the tokens are
+ * already in this GPU's memory), so no FFN launch waits for the pack: xe, the payload
+ * the first all-to-all would carry, is written beside it -- also when n_chunks = 1.
+ * The expert FFN runs once per GROUP of consecutive chunks: every FFN launch streams
+ * all experts' weights from HBM once, so a launch is given at least
+ * moe_tune_ffn_group_rows() (default 2048) rows per expert on average --
+ * groups = min(n_chunks, (moe_max_rows / E) / that), at least 1; packing and unpacking
+ * keep n_chunks.  With one group the call runs as n_chunks = 1.
  * Arguments as in the calls above; all outputs are written.  The side streams
  * and events are created on the first chunked call on a device and kept. */
 moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x,
@@ -185,8 +197,13 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
                              const float *b1, const void *W2p, const float *b2,
                              int32_t *expert_idx, float *gate, int32_t *counts,
                              int32_t *offsets, int32_t *slot_of, int32_t *src_of,
-                             void *xe, float *ye, float *y, void *y_act,
+                             void *xe, void *ye, float *y, void *y_act,
                              void *workspace, void *stream);
+
+/* Tuning knob, process-wide: the average rows per expert an FFN launch of a chunked
+ * layer must hold (see moe_layer_chunked).  rows >= 1 sets it; any other value only
+ * reads.  Returns the value before the call.  1 gives one FFN launch per chunk. */
+int32_t moe_tune_ffn_group_rows(int32_t rows);
 
 /* Measurement aid, off by default (not part of the layer).  Stage numbers:
  * 0 gate, 1 dispatch plan, 2 row-tile table, 3 pack (scatter), 4 first expert GEMM

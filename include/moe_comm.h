@@ -151,7 +151,8 @@ size_t moe_padded_workspace_bytes(const moe_shape *s, int32_t n_micro);
  * blocks while it waits for micro-ops to be launched, and link_blocks is ignored.
  *   expert_idx, gate [T*k], counts [E]: as in moe_layer_chunked
  *   slot_of [T*k]: e*C + rank, -1 if dropped;  src_of [E*C]: written for kept slots only
- *   xs, xr [E*C, d_model] in `dtype`;  ys, yr [E*C, d_model] fp32;  y [T, d_model] fp32
+ *   xs, xr [E*C, d_model] in `dtype`;  ys, yr [E*C, d_model] as moe_expert_ffn's ye (fp16 for
+ *   MOE_BF16 layers, fp32 for MOE_F32);  y [T, d_model] fp32
  * Rows of ys / yr at or beyond an expert's min(count, C) are left untouched in ys and
  * copied as they are.  y equals moe_layer_chunked's y bit for bit.
  */
@@ -161,7 +162,7 @@ moe_status moe_layer_padded(const moe_shape *s, int32_t n_micro, moe_comm *link,
                             const void *W1p, const float *b1, const void *W2p,
                             const float *b2, int32_t *expert_idx, float *gate,
                             int32_t *counts, int32_t *slot_of, int32_t *src_of, void *xs,
-                            void *xr, float *ys, float *yr, float *y, void *workspace,
+                            void *xr, void *ys, void *yr, float *y, void *workspace,
                             void *stream);
 
 #ifdef __cplusplus

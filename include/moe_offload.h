@@ -44,7 +44,7 @@ size_t moe_offload_workspace_bytes(const moe_shape *s);
  */
 moe_status moe_expert_ffn_offloaded(const moe_shape *s, const void *xe, const int32_t *offsets,
                                     const void *W1p_host, const void *W2p_host, const float *b1,
-                                    const float *b2, float *ye, void *staging, int32_t resident,
+                                    const float *b2, void *ye, void *staging, int32_t resident,
                                     void *workspace, void *stream);
 
 #ifdef __cplusplus

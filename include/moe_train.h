@@ -51,7 +51,7 @@ moe_status moe_layer_forward_keep(const moe_shape *s, const void *x, const float
                                   const void *W1p, const float *b1, const void *W2p,
                                   const float *b2, int32_t *expert_idx, float *gate,
                                   int32_t *counts, int32_t *offsets, int32_t *slot_of,
-                                  int32_t *src_of, void *xe, float *ye, void *pre, void *hid,
+                                  int32_t *src_of, void *xe, void *ye, void *pre, void *hid,
                                   float *y, void *workspace, void *stream);
 
 /* Bytes of workspace moe_layer_backward needs for this shape (0 if unsupported). */
@@ -75,7 +75,7 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
                               const void *W1, const void *W2, const void *W1p,
                               const int32_t *expert_idx, const float *gate,
                               const int32_t *offsets, const int32_t *slot_of,
-                              const int32_t *src_of, const void *xe, const float *ye,
+                              const int32_t *src_of, const void *xe, const void *ye,
                               const void *pre, const void *hid, const float *dy, float *dx,
                               float *dWg, float *dW1, float *dW2, float *dgate, void *workspace,
                               void *stream);

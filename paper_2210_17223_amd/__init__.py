@@ -8,7 +8,8 @@ from .binding import (ACT, DTYPE, MoeError, Shape, alloc_buffers, lib, lib_path,
                       moe_calib_copy, moe_calib_mfma, moe_capacity, moe_combine, moe_dispatch, moe_expert_ffn,
                       moe_last_error, moe_layer_chunked, moe_max_rows, moe_pack_gate,
                       moe_pack_weights, moe_packed_gate_bytes, moe_packed_weight_bytes,
-                      moe_profile_enable, moe_profile_read, moe_route, moe_workspace_bytes,
+                      moe_profile_enable, moe_profile_read, moe_route, moe_tune_ffn_group_rows,
+                      moe_workspace_bytes,
                       STAGES)
 
 from .sched_binding import (PathShape, moe_devices_for_expert, moe_path_count, moe_path_finalize,
@@ -30,5 +31,6 @@ __all__ = ["comm", "moe_layer_padded", "moe_padded_workspace_bytes", "moe_expert
            "moe_calib_copy", "moe_calib_mfma", "moe_capacity", "moe_combine", "moe_dispatch", "moe_expert_ffn",
            "moe_last_error", "moe_layer_chunked", "moe_max_rows", "moe_pack_gate",
            "moe_pack_weights", "moe_packed_gate_bytes", "moe_packed_weight_bytes",
-           "moe_profile_enable", "moe_profile_read", "moe_route", "moe_workspace_bytes",
+           "moe_profile_enable", "moe_profile_read", "moe_route", "moe_tune_ffn_group_rows",
+           "moe_workspace_bytes",
            "STAGES"]

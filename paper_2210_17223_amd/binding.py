@@ -38,6 +38,11 @@ class Shape(C.Structure):
     def torch_dtype(self):
         return torch.bfloat16 if self.dtype == DTYPE["bf16"] else torch.float32
 
+    @property
+    def ye_dtype(self):
+        """Stored type of the expert outputs ye: fp16 for bf16 layers, fp32 for fp32 layers."""
+        return torch.float16 if self.dtype == DTYPE["bf16"] else torch.float32
+
 
 _lib = None
 
@@ -81,6 +86,8 @@ def lib() -> C.CDLL:
         L.moe_calib_mfma.restype = C.c_int
         L.moe_calib_mfma_flops.argtypes = [i32, i32]
         L.moe_calib_mfma_flops.restype = C.c_double
+        L.moe_tune_ffn_group_rows.argtypes = [i32]
+        L.moe_tune_ffn_group_rows.restype = i32
         L.moe_profile_enable.restype = C.c_int
         L.moe_profile_enable.argtypes = [C.c_uint32, i32]
         L.moe_profile_read.restype = i32
@@ -190,18 +197,24 @@ def moe_calib_mfma(sink, waves_per_simd: int, iters: int, random_operands: bool,
     return float(lib().moe_calib_mfma_flops(waves_per_simd, iters))
 
 
+def moe_tune_ffn_group_rows(rows: int = 0) -> int:
+    """Sets (rows >= 1) or reads the rows per expert an FFN launch of a chunked layer must
+    hold on average; returns the previous value."""
+    return int(lib().moe_tune_ffn_group_rows(int(rows)))
+
+
 def moe_expert_ffn(s: Shape, xe, offsets, W1p, b1, W2p, b2, ye, workspace, stream=None) -> None:
     rows = moe_max_rows(s)
     _need(xe, s.torch_dtype, rows * s.d_model, "xe")
     _need(offsets, torch.int32, s.E + 1, "offsets")
-    _need(ye, torch.float32, rows * s.d_model, "ye")
+    _need(ye, s.ye_dtype, rows * s.d_model, "ye")
     _need(workspace, torch.uint8, moe_workspace_bytes(s, 1), "workspace")
     _check(lib().moe_expert_ffn(C.byref(s), _ptr(xe), _ptr(offsets), _ptr(W1p), _ptr(b1),
                                 _ptr(W2p), _ptr(b2), _ptr(ye), _ptr(workspace), _stream(stream)))
 
 
 def moe_combine(s: Shape, ye, slot_of, gate, y, y_act=None, stream=None) -> None:
-    _need(ye, torch.float32, moe_max_rows(s) * s.d_model, "ye")
+    _need(ye, s.ye_dtype, moe_max_rows(s) * s.d_model, "ye")
     _need(slot_of, torch.int32, s.T * s.k, "slot_of")
     _need(gate, torch.float32, s.T * s.k, "gate")
     _need(y, torch.float32, s.T * s.d_model, "y")
@@ -223,7 +236,7 @@ def moe_layer_chunked(s: Shape, n_chunks: int, x, Wgp, gate_bias, bias_token_str
     _need(slot_of, torch.int32, s.T * s.k, "slot_of")
     _need(src_of, torch.int32, rows, "src_of")
     _need(xe, s.torch_dtype, rows * s.d_model, "xe")
-    _need(ye, torch.float32, rows * s.d_model, "ye")
+    _need(ye, s.ye_dtype, rows * s.d_model, "ye")
     _need(y, torch.float32, s.T * s.d_model, "y")
     _need(workspace, torch.uint8, moe_workspace_bytes(s, max(1, n_chunks)), "workspace")
     if gate_bias is not None:
@@ -266,7 +279,7 @@ def alloc_buffers(s: Shape, n_chunks: int = 1, device="cuda:0", y_act: bool = Fa
         slot_of=torch.empty(s.T * s.k, dtype=torch.int32, device=dev),
         src_of=torch.empty(rows, dtype=torch.int32, device=dev),
         xe=torch.empty(rows * s.d_model, dtype=s.torch_dtype, device=dev),
-        ye=torch.empty(rows * s.d_model, dtype=torch.float32, device=dev),
+        ye=torch.empty(rows * s.d_model, dtype=s.ye_dtype, device=dev),
         y=torch.empty(s.T * s.d_model, dtype=torch.float32, device=dev),
         workspace=torch.empty(moe_workspace_bytes(s, n_chunks), dtype=torch.uint8, device=dev),
     )

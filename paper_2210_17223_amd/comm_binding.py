@@ -131,8 +131,8 @@ def moe_layer_padded(s: Shape, n_micro: int, link: Optional[C.c_void_p], link_bl
     _need(src_of, torch.int32, slots, "src_of")
     _need(xs, s.torch_dtype, slots * s.d_model, "xs")
     _need(xr, s.torch_dtype, slots * s.d_model, "xr")
-    _need(ys, torch.float32, slots * s.d_model, "ys")
-    _need(yr, torch.float32, slots * s.d_model, "yr")
+    _need(ys, s.ye_dtype, slots * s.d_model, "ys")
+    _need(yr, s.ye_dtype, slots * s.d_model, "yr")
     _need(y, torch.float32, s.T * s.d_model, "y")
     _need(workspace, torch.uint8, moe_padded_workspace_bytes(s, n_micro), "workspace")
     _check(_lib().moe_layer_padded(C.byref(s), n_micro, link, link_blocks, _ptr(x), _ptr(Wgp),

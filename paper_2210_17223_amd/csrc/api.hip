@@ -225,6 +225,23 @@ moe_status chunk_resources(ChunkResources **out)
 
 }  // namespace
 
+// The expert FFN of a chunked layer runs once per GROUP of consecutive chunks.  A launch
+// reads every expert's two weight matrices from HBM once whatever its row count, and is bound
+// by the matrix cores only with several hundred rows per expert (2*rows flops per 2-byte
+// weight against ~1 PFLOP/s over ~3.5 TB/s of HBM put the break-even near 300 rows; measured
+// at 512 rows per expert and launch the two GEMMs still take 16 % longer than in one launch):
+// groups are sized to hold at least 2048 rows per expert on average.  Packing and unpacking
+// keep the caller's n_chunks.
+std::atomic<int32_t> g_group_rows{2048};
+
+int ffn_groups(const moe_shape &s, int n_chunks)
+{
+    const int64_t rows_per_expert = moe_max_rows(&s) / s.E;
+    int64_t g = rows_per_expert / g_group_rows.load(std::memory_order_relaxed);
+    if (g < 1) g = 1;
+    return static_cast<int>(g < n_chunks ? g : n_chunks);
+}
+
 bool layout_workspace(const moe_shape &s, int n_chunks, void *base, Workspace *w)
 {
     if (n_chunks < 1 || n_chunks > kMaxChunks) return false;
@@ -279,12 +296,19 @@ int64_t moe_max_rows(const moe_shape *s)
 size_t moe_workspace_bytes(const moe_shape *s, int32_t n_chunks)
 {
     if (check_common(s) != MOE_OK) return 0;
-    Workspace w;
-    if (!layout_workspace(*s, n_chunks, nullptr, &w)) {
+    if (n_chunks < 1 || n_chunks > kMaxChunks) {
         set_error("n_chunks must be in 1..%d, got %d", kMaxChunks, n_chunks);
         return 0;
     }
-    return w.bytes;
+    // the same buffer serves every call with up to n_chunks chunks (a chunked layer lays its
+    // work lists out for its number of FFN groups, which is at most n_chunks)
+    size_t bytes = 0;
+    for (int c = 1; c <= n_chunks; ++c) {
+        Workspace w;
+        layout_workspace(*s, c, nullptr, &w);
+        if (w.bytes > bytes) bytes = w.bytes;
+    }
+    return bytes;
 }
 
 const char *moe_last_error(void) { return g_error; }
@@ -398,9 +422,16 @@ moe_status moe_dispatch(const moe_shape *s, const void *x, const int32_t *expert
     return MOE_OK;
 }
 
+int32_t moe_tune_ffn_group_rows(int32_t rows)
+{
+    const int32_t before = g_group_rows.load(std::memory_order_relaxed);
+    if (rows >= 1) g_group_rows.store(rows, std::memory_order_relaxed);
+    return before;
+}
+
 moe_status moe_expert_ffn(const moe_shape *s, const void *xe, const int32_t *offsets,
                           const void *W1p, const float *b1, const void *W2p, const float *b2,
-                          float *ye, void *workspace, void *stream)
+                          void *ye, void *workspace, void *stream)
 {
     MOE_TRY(check_common(s));
     MOE_REQUIRE_PTR(xe);
@@ -414,11 +445,11 @@ moe_status moe_expert_ffn(const moe_shape *s, const void *xe, const int32_t *off
     Workspace w;
     layout_workspace(*s, 1, workspace, &w);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    MOE_TIMED(kStageTiles, st, launch_items(*s, 1, offsets, nullptr, w, st));
+    MOE_TIMED(kStageTiles, st, launch_items(*s, 1, 1, offsets, nullptr, w, st));
     return launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, 0, st);
 }
 
-moe_status moe_combine(const moe_shape *s, const float *ye, const int32_t *slot_of,
+moe_status moe_combine(const moe_shape *s, const void *ye, const int32_t *slot_of,
                        const float *gate, float *y, void *y_act, void *stream)
 {
     MOE_TRY(check_common(s));
@@ -442,7 +473,7 @@ moe_status layer_forward(const moe_shape *s, int32_t n_chunks, const void *x,
                          int32_t bias_token_stride, const void *W1p, const float *b1,
                          const void *W2p, const float *b2, int32_t *expert_idx, float *gate,
                          int32_t *counts, int32_t *offsets, int32_t *slot_of,
-                         int32_t *src_of, void *xe, float *ye, void *pre, void *hid, float *y,
+                         int32_t *src_of, void *xe, void *ye, void *pre, void *hid, float *y,
                          void *y_act, void *workspace, void *stream)
 {
     MOE_TRY(check_common(s));
@@ -469,9 +500,13 @@ moe_status layer_forward(const moe_shape *s, int32_t n_chunks, const void *x,
     MOE_REQUIRE_PTR(workspace);
     MOE_TRY(check_bias(*s, gate_bias, bias_token_stride));
     if (n_chunks > s->T) n_chunks = s->T;
+    // FFN launches: one per group of consecutive chunks; a layer whose FFN would run as one
+    // group anyway is run unchunked (same outputs, one launch less per chunk)
+    const int n_groups = ffn_groups(*s, n_chunks);
+    if (n_groups == 1) n_chunks = 1;
 
     Workspace w;
-    layout_workspace(*s, n_chunks, workspace, &w);
+    layout_workspace(*s, n_groups, workspace, &w);
     if (hid != nullptr) w.hidden = hid;       // the hidden activations go where the caller keeps them
     hipStream_t st = static_cast<hipStream_t>(stream);
 
@@ -483,19 +518,28 @@ moe_status layer_forward(const moe_shape *s, int32_t n_chunks, const void *x,
               launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w, true, n_chunks, st,
                           false, n_chunks == 1 ? x : nullptr, xe, &packed));
     if (n_chunks > 1)
-        MOE_TIMED(kStageTiles, st, launch_items(*s, n_chunks, offsets, src_of, w, st));
+        MOE_TIMED(kStageTiles, st, launch_items(*s, n_chunks, n_groups, offsets, src_of, w, st));
 
-    if (n_chunks == 1) {
+    // bf16 layers: the first expert GEMM gathers its rows from the token matrix through
+    // src_of, so it does not wait for the pack; xe (the first all-to-all's payload) is then
+    // written beside it on a side stream.  fp32 layers multiply the packed buffer.
+    const bool gather = s->dtype == MOE_BF16;
+    const void *ffn_in = gather ? x : xe;
+    const int32_t *row_src = gather ? src_of : nullptr;
+
+    if (n_chunks == 1 && (packed || !gather)) {
         if (!packed)
             MOE_TIMED(kStageScatter, st, launch_scatter(*s, x, slot_of, xe, 0, s->T, st));
-        MOE_TRY(launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, 0, st, pre));
+        MOE_TRY(launch_ffn(*s, ffn_in, W1p, b1, W2p, b2, ye, w, 0, st, pre, row_src));
         MOE_TIMED(kStageCombine, st,
                   launch_combine(*s, ye, slot_of, gate, y, y_act, 0, s->T, st));
         return MOE_OK;
     }
 
-    // pack stream: chunk after chunk; caller's stream: expert FFN of a chunk once it
-    // is packed; unpack stream: combine of a chunk once its FFN is done.
+    // pack stream: chunk after chunk; caller's stream: expert FFN of a group of chunks (fp32
+    // layers: once the group is packed); unpack stream: combine of a chunk once its group's FFN
+    // is done.  An unchunked bf16 layer takes this path with one chunk and one group: its pack
+    // runs beside the FFN.
     ChunkResources *r = nullptr;
     MOE_TRY(chunk_resources(&r));
     // One call at a time enqueues on this device's side streams: two threads' records and
@@ -503,33 +547,41 @@ moe_status layer_forward(const moe_shape *s, int32_t n_chunks, const void *x,
     std::lock_guard<std::mutex> enqueue(r->enqueue);
     MOE_TRY_HIP(hipEventRecord(r->planned, st));
     MOE_TRY_HIP(hipStreamWaitEvent(r->pack, r->planned, 0));
-    MOE_TRY_HIP(hipStreamWaitEvent(r->unpack, r->planned, 0));
+    if (n_chunks > 1) MOE_TRY_HIP(hipStreamWaitEvent(r->unpack, r->planned, 0));
+    auto bound = [&](int c) { return static_cast<int>(static_cast<int64_t>(c) * s->T / n_chunks); };
     auto enqueue_chunks = [&]() -> moe_status {
         for (int c = 0; c < n_chunks; ++c) {
-            const int t0 = static_cast<int>(static_cast<int64_t>(c) * s->T / n_chunks);
-            const int t1 = static_cast<int>(static_cast<int64_t>(c + 1) * s->T / n_chunks);
-            MOE_TIMED(kStageScatter, r->pack, launch_scatter(*s, x, slot_of, xe, t0, t1, r->pack));
-            MOE_TRY_HIP(hipEventRecord(r->packed[c], r->pack));
+            MOE_TIMED(kStageScatter, r->pack,
+                      launch_scatter(*s, x, slot_of, xe, bound(c), bound(c + 1), r->pack));
+            if (!gather) MOE_TRY_HIP(hipEventRecord(r->packed[c], r->pack));
         }
-        for (int c = 0; c < n_chunks; ++c) {
-            const int t0 = static_cast<int>(static_cast<int64_t>(c) * s->T / n_chunks);
-            const int t1 = static_cast<int>(static_cast<int64_t>(c + 1) * s->T / n_chunks);
-            MOE_TRY_HIP(hipStreamWaitEvent(st, r->packed[c], 0));
-            MOE_TRY(launch_ffn(*s, xe, W1p, b1, W2p, b2, ye, w, c, st));
-            MOE_TRY_HIP(hipEventRecord(r->computed[c], st));
-            MOE_TRY_HIP(hipStreamWaitEvent(r->unpack, r->computed[c], 0));
-            MOE_TIMED(kStageCombine, r->unpack,
-                      launch_combine(*s, ye, slot_of, gate, y, y_act, t0, t1, r->unpack));
+        for (int f = 0; f < n_groups; ++f) {
+            // group f = chunks [c0, c1)
+            const int c0 = static_cast<int>(static_cast<int64_t>(f) * n_chunks / n_groups);
+            const int c1 = static_cast<int>(static_cast<int64_t>(f + 1) * n_chunks / n_groups);
+            if (!gather) MOE_TRY_HIP(hipStreamWaitEvent(st, r->packed[c1 - 1], 0));
+            MOE_TRY(launch_ffn(*s, ffn_in, W1p, b1, W2p, b2, ye, w, f, st, pre, row_src));
+            if (n_chunks == 1) {
+                MOE_TIMED(kStageCombine, st,
+                          launch_combine(*s, ye, slot_of, gate, y, y_act, 0, s->T, st));
+                continue;
+            }
+            MOE_TRY_HIP(hipEventRecord(r->computed[f], st));
+            MOE_TRY_HIP(hipStreamWaitEvent(r->unpack, r->computed[f], 0));
+            for (int c = c0; c < c1; ++c)
+                MOE_TIMED(kStageCombine, r->unpack,
+                          launch_combine(*s, ye, slot_of, gate, y, y_act, bound(c), bound(c + 1),
+                                         r->unpack));
         }
         return MOE_OK;
     };
     const moe_status rc = enqueue_chunks();
-    // Join both side streams back into the caller's stream, also after a failure part-way:
+    // Join the side streams back into the caller's stream, also after a failure part-way:
     // whatever was enqueued there must not outlive the call unobserved.
-    hipError_t je = hipEventRecord(r->unpacked, r->unpack);
-    if (je == hipSuccess) je = hipStreamWaitEvent(st, r->unpacked, 0);
-    if (je == hipSuccess) je = hipEventRecord(r->planned, r->pack);
-    if (je == hipSuccess) je = hipStreamWaitEvent(st, r->planned, 0);
+    hipError_t je = hipEventRecord(r->packed[0], r->pack);
+    if (je == hipSuccess) je = hipStreamWaitEvent(st, r->packed[0], 0);
+    if (je == hipSuccess && n_chunks > 1) je = hipEventRecord(r->unpacked, r->unpack);
+    if (je == hipSuccess && n_chunks > 1) je = hipStreamWaitEvent(st, r->unpacked, 0);
     if (rc != MOE_OK) return rc;
     if (je != hipSuccess) return hip_fail(je, "joining the side streams");
     return MOE_OK;
@@ -544,7 +596,7 @@ moe_status moe_layer_chunked(const moe_shape *s, int32_t n_chunks, const void *x
                              int32_t bias_token_stride, const void *W1p, const float *b1,
                              const void *W2p, const float *b2, int32_t *expert_idx, float *gate,
                              int32_t *counts, int32_t *offsets, int32_t *slot_of,
-                             int32_t *src_of, void *xe, float *ye, float *y, void *y_act,
+                             int32_t *src_of, void *xe, void *ye, float *y, void *y_act,
                              void *workspace, void *stream)
 {
     return layer_forward(s, n_chunks, x, Wgp, gate_bias, bias_token_stride, W1p, b1, W2p, b2,
@@ -557,7 +609,7 @@ moe_status moe_layer_forward_keep(const moe_shape *s, const void *x, const float
                                   const void *W1p, const float *b1, const void *W2p,
                                   const float *b2, int32_t *expert_idx, float *gate,
                                   int32_t *counts, int32_t *offsets, int32_t *slot_of,
-                                  int32_t *src_of, void *xe, float *ye, void *pre, void *hid,
+                                  int32_t *src_of, void *xe, void *ye, void *pre, void *hid,
                                   float *y, void *workspace, void *stream)
 {
     MOE_TRY(check_common(s));

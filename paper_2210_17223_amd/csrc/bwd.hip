@@ -89,7 +89,7 @@ __device__ __forceinline__ void store_bf16x4(uint16_t *p, const float (&v)[4])
 // ---------------------------------------------------------------- combine backward
 // One wavefront per token.
 __global__ __launch_bounds__(256) void combine_bwd_kernel(
-    const float *__restrict__ dy, const float *__restrict__ ye, const int32_t *__restrict__ slot_of,
+    const float *__restrict__ dy, const _Float16 *__restrict__ ye, const int32_t *__restrict__ slot_of,
     const float *__restrict__ gate, uint16_t *__restrict__ dye, float *__restrict__ dgate, int T,
     int d, int k, int max_rows)
 {
@@ -104,16 +104,17 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(
             continue;
         }
         const float g = gate[static_cast<size_t>(t) * k + j];
-        const float *yerow = ye + static_cast<size_t>(slot) * d;
+        const _Float16 *yerow = ye + static_cast<size_t>(slot) * d;
         uint16_t *out = dye + static_cast<size_t>(slot) * d;
         float dot = 0.0f;
         for (int c = lane * 4; c < d; c += kWave * 4) {
             const float4 a = *reinterpret_cast<const float4 *>(dyrow + c);
-            const float4 b = *reinterpret_cast<const float4 *>(yerow + c);
-            dot = __builtin_fmaf(a.x, b.x, dot);
-            dot = __builtin_fmaf(a.y, b.y, dot);
-            dot = __builtin_fmaf(a.z, b.z, dot);
-            dot = __builtin_fmaf(a.w, b.w, dot);
+            typedef __attribute__((ext_vector_type(4))) _Float16 half4;
+            const half4 b = *reinterpret_cast<const half4 *>(yerow + c);
+            dot = __builtin_fmaf(a.x, static_cast<float>(b[0]), dot);
+            dot = __builtin_fmaf(a.y, static_cast<float>(b[1]), dot);
+            dot = __builtin_fmaf(a.z, static_cast<float>(b[2]), dot);
+            dot = __builtin_fmaf(a.w, static_cast<float>(b[3]), dot);
             const float v[4] = {g * a.x, g * a.y, g * a.z, g * a.w};
             store_bf16x4(out + c, v);
         }
@@ -811,14 +812,14 @@ moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, c
                       int bias_stride, const uint16_t *W1, const uint16_t *W2, const uint16_t *W1p,
                       const int32_t *expert_idx, const float *gate, const int32_t *offsets,
                       const int32_t *slot_of, const int32_t *src_of, const uint16_t *xe,
-                      const float *ye, const _Float16 *pre, const _Float16 *hid, const float *dy,
+                      const _Float16 *ye, const _Float16 *pre, const _Float16 *hid, const float *dy,
                       float *dx, float *dWg,
                       float *dW1, float *dW2, float *dgate, const BwdWorkspace &w, hipStream_t st)
 {
     const int T = s.T, d = s.d_model, h = s.d_ff, E = s.E, k = s.k;
     const int R = static_cast<int>(moe_max_rows(&s));
     // work lists of the row-grouped GEMMs (one chunk)
-    moe_status rc = launch_items(s, 1, offsets, src_of, w.lists, st);
+    moe_status rc = launch_items(s, 1, 1, offsets, src_of, w.lists, st);
     if (rc != MOE_OK) return rc;
     hipLaunchKernelGGL(combine_bwd_kernel, dim3(ceil_div(T, 4)), dim3(256), 0, st, dy, ye, slot_of,
                        gate, w.dye, dgate, T, d, k, R);
@@ -892,7 +893,7 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
                               const void *W1, const void *W2, const void *W1p,
                               const int32_t *expert_idx, const float *gate,
                               const int32_t *offsets, const int32_t *slot_of,
-                              const int32_t *src_of, const void *xe, const float *ye,
+                              const int32_t *src_of, const void *xe, const void *ye,
                               const void *pre, const void *hid, const float *dy, float *dx,
                               float *dWg, float *dW1, float *dW2, float *dgate, void *workspace,
                               void *stream)
@@ -931,7 +932,8 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
 #define MOE_BWD_CASE(ACT)                                                                         \
     case ACT:                                                                                     \
         return backward_t<ACT>(*s, xb, Wgf, gate_bias, bias_token_stride, W1b, W2b, W1pb,         \
-                               expert_idx, gate, offsets, slot_of, src_of, xeb, ye, preh, hidh,   \
+                               expert_idx, gate, offsets, slot_of, src_of, xeb,                   \
+                               static_cast<const _Float16 *>(ye), preh, hidh,                     \
                                dy, dx, dWg, dW1, dW2, dgate, w, st);
     switch (s->act) {
         MOE_BWD_CASE(MOE_ACT_GELU_ERF)

@@ -675,7 +675,7 @@ moe_status moe_layer_padded(const moe_shape *s, int32_t n_micro, moe_comm *link,
                             const float *gate_bias, int32_t bias_token_stride, const void *W1p,
                             const float *b1, const void *W2p, const float *b2,
                             int32_t *expert_idx, float *gate, int32_t *counts, int32_t *slot_of,
-                            int32_t *src_of, void *xs, void *xr, float *ys, float *yr, float *y,
+                            int32_t *src_of, void *xs, void *xr, void *ys, void *yr, float *y,
                             void *workspace, void *stream)
 {
     if (s == nullptr || !padded_shape_ok(s, n_micro)) return s == nullptr ? MOE_EINVAL : MOE_EUNSUPPORTED;
@@ -723,7 +723,7 @@ moe_status moe_layer_padded(const moe_shape *s, int32_t n_micro, moe_comm *link,
         MOE_TRY(moe_comm_submit(link, MOE_COMM_ALL_TO_ALL, xs, xr, E, C, static_cast<int64_t>(d) * elem,
                                 n_micro, &first));
         moe_status rc = moe_comm_submit(link, MOE_COMM_ALL_TO_ALL, ys, yr, E, C,
-                                        static_cast<int64_t>(d) * 4, n_micro, &second);
+                                        static_cast<int64_t>(d) * ye_elem_bytes(*s), n_micro, &second);
         const int timeout_ms = 20000;
         int posted1 = 0, posted2 = 0;
         for (int m = 0; rc == MOE_OK && m < n_micro; ++m) {
@@ -780,7 +780,7 @@ moe_status moe_layer_padded(const moe_shape *s, int32_t n_micro, moe_comm *link,
         int64_t r0, r1;
         range(m, &r0, &r1);
         MOE_TRY_HIP(hipStreamWaitEvent(r->link, r->computed[m], 0));
-        launch_link_copy(ys, yr, E, C, static_cast<int64_t>(d) * 4, r0, r1, link_blocks, r->link);
+        launch_link_copy(ys, yr, E, C, static_cast<int64_t>(d) * ye_elem_bytes(*s), r0, r1, link_blocks, r->link);
     }
     MOE_TRY_HIP(hipEventRecord(r->returned, r->link));
     MOE_TRY_HIP(hipStreamWaitEvent(st, r->returned, 0));

@@ -119,21 +119,31 @@ moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *c
 // work lists of the padded layout, one per micro-op (slot positions [m*C/n, (m+1)*C/n))
 moe_status launch_items_padded(const moe_shape &s, int n_micro, const int32_t *counts,
                                const Workspace &w, hipStream_t st);
-moe_status launch_items(const moe_shape &s, int n_chunks, const int32_t *offsets,
+// one pair of work lists per FFN group (a run of consecutive chunks, ffn_groups() of them)
+moe_status launch_items(const moe_shape &s, int n_chunks, int n_groups, const int32_t *offsets,
                         const int32_t *src_of, const Workspace &w, hipStream_t st);
+// How many expert-FFN launches a layer cut into n_chunks gets.  Every FFN launch streams the
+// weights of all experts once, so a launch needs enough rows per expert to pay for that.
+int ffn_groups(const moe_shape &s, int n_chunks);
 // w.items[g] / w.nitems[g] sized for E lists: list e = the output tiles of expert e alone
 moe_status launch_items_per_expert(const moe_shape &s, const int32_t *offsets, const Workspace &w,
                                    hipStream_t st);
 moe_status launch_scatter(const moe_shape &s, const void *x, const int32_t *slot_of,
                           void *xe, int t0, int t1, hipStream_t st);
 // rows: rows of ye (slots at or beyond it are never followed); < 0 = moe_max_rows
-moe_status launch_combine(const moe_shape &s, const float *ye, const int32_t *slot_of,
+// ye: the expert outputs in their stored type (fp16 for bf16 layers, fp32 for fp32 layers)
+moe_status launch_combine(const moe_shape &s, const void *ye, const int32_t *slot_of,
                           const float *gate, float *y, void *y_act, int t0, int t1,
                           hipStream_t st, int64_t rows = -1);
 // pre: NULL, or fp16 [rows, d_ff] receiving the pre-activations of the first GEMM (bf16 layers)
+// row_src: NULL, or the dispatch plan's src_of: `xe` is then the token matrix x itself and the
+// first GEMM gathers slot i's row from token src_of[i] / k (bf16 layers)
 moe_status launch_ffn(const moe_shape &s, const void *xe, const void *W1p,
-                      const float *b1, const void *W2p, const float *b2, float *ye,
-                      const Workspace &w, int chunk, hipStream_t st, void *pre = nullptr);
+                      const float *b1, const void *W2p, const float *b2, void *ye,
+                      const Workspace &w, int chunk, hipStream_t st, void *pre = nullptr,
+                      const int32_t *row_src = nullptr);
+// bytes per element of the expert outputs ye
+inline int ye_elem_bytes(const moe_shape &s) { return s.dtype == MOE_BF16 ? 2 : 4; }
 moe_status launch_pack(const moe_shape &s, const void *W1, const void *W2, void *W1p,
                        void *W2p, hipStream_t st);
 

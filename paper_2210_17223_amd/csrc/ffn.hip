@@ -10,7 +10,7 @@
 // index contiguous (activations by nature, weights after moe_pack_weights), staged
 // through LDS in 128 x 64 tiles, and the weight tile is fed as the MFMA "A" operand
 // so that each lane ends up with four consecutive output columns of one row.
-// H is kept in fp16, ye in fp32.
+// H and ye are kept in fp16.
 // fp32 layers: a plain LDS-tiled vector-ALU GEMM (correctness configuration).
 #include "common.h"
 
@@ -174,12 +174,16 @@ __device__ __forceinline__ void store4(_Float16 *p, const float (&v)[4])
 // XCD's L2.  32-row sub-tiles past the end of a ragged row tile are skipped.
 // KEEP: the pre-activation values (accumulator + bias) also go to Pre [rows, N] as fp16, for
 // the backward pass.
+// row_src != NULL: A is not the expert-major buffer but the token matrix itself, and the row
+// operand of slot i is token row_src[i] / row_div (the dispatch plan's src_of and k): the
+// loader gathers the tokens where they lie, so the multiply does not wait for the pack.
 template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN, bool KTAIL, bool KEEP>
 // (two wavefronts per SIMD in every shape: two 4-wavefront blocks or one 8-wavefront block)
 __global__ __launch_bounds__(64 * WM * WN, 2) void grouped_gemm_mfma_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W,
     const float *__restrict__ bias, TOut *__restrict__ C, _Float16 *__restrict__ Pre,
-    const WorkItem *__restrict__ items, const int32_t *__restrict__ nitems, int N, int K)
+    const WorkItem *__restrict__ items, const int32_t *__restrict__ nitems, int N, int K,
+    const int32_t *__restrict__ row_src, int row_div)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64, LD = BK + 8;
     constexpr int NT = 64 * WM * WN;
@@ -213,7 +217,11 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void grouped_gemm_mfma_kernel(
     for (int q = 0; q < AV; ++q) {
         const int r = (tid + NT * q) >> 3;
         a_off[q] = r * LD + ld_col;
-        a_src[q] = A + static_cast<size_t>(min(item.row0 + r, item.row1 - 1)) * K + ld_col;
+        // row_src: the operand rows are gathered -- row i of the expert-major order is row
+        // row_src[i] / row_div of A (the token that holds assignment row_src[i])
+        int arow = min(item.row0 + r, item.row1 - 1);
+        if (row_src != nullptr) arow = row_src[arow] / row_div;
+        a_src[q] = A + static_cast<size_t>(arow) * K + ld_col;
     }
 #pragma unroll
     for (int q = 0; q < WV; ++q) {
@@ -420,7 +428,7 @@ void launch_f32_pair(const moe_shape &s, const float *xe, const float *W1, const
 template <bool F16, typename TOut, int ACT, int WM, int WN, int TM, int TN, bool KTAIL, bool KEEP>
 void launch_mfma_cfg_k(const uint16_t *A, const uint16_t *W, const float *bias, TOut *C,
                      _Float16 *pre, const WorkItem *items, const int32_t *nitems, int max_items,
-                     int N, int K, int stage, hipStream_t st)
+                     int N, int K, int stage, hipStream_t st, const int32_t *row_src, int row_div)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t lds = 2 * (BM + BN) * (64 + 8) * sizeof(uint16_t);
@@ -431,7 +439,7 @@ void launch_mfma_cfg_k(const uint16_t *A, const uint16_t *W, const float *bias, 
     hipEvent_t t0, t1;
     prof_kernel_events(stage, &t0, &t1);
     hipExtLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, st, t0, t1, 0, A, W, bias, C,
-                          pre, items, nitems, N, K);
+                          pre, items, nitems, N, K, row_src, row_div);
 }
 
 // The contraction depth is a multiple of the 64-deep stage in every benchmark shape;
@@ -439,24 +447,25 @@ void launch_mfma_cfg_k(const uint16_t *A, const uint16_t *W, const float *bias, 
 template <bool F16, typename TOut, int ACT, bool KEEP, int WM, int WN, int TM, int TN>
 void launch_mfma_cfg(const uint16_t *A, const uint16_t *W, const float *bias, TOut *C,
                      _Float16 *pre, const WorkItem *items, const int32_t *nitems, int max_items,
-                     int N, int K, int stage, hipStream_t st)
+                     int N, int K, int stage, hipStream_t st, const int32_t *row_src, int row_div)
 {
     if (K % 64 == 0)
         launch_mfma_cfg_k<F16, TOut, ACT, WM, WN, TM, TN, false, KEEP>(
-            A, W, bias, C, pre, items, nitems, max_items, N, K, stage, st);
+            A, W, bias, C, pre, items, nitems, max_items, N, K, stage, st, row_src, row_div);
     else
         launch_mfma_cfg_k<F16, TOut, ACT, WM, WN, TM, TN, true, KEEP>(
-            A, W, bias, C, pre, items, nitems, max_items, N, K, stage, st);
+            A, W, bias, C, pre, items, nitems, max_items, N, K, stage, st, row_src, row_div);
 }
 
 template <bool F16, typename TOut, int ACT, bool KEEP>
 void launch_mfma(const GemmPlan &gp, const uint16_t *A, const uint16_t *W, const float *bias,
                  TOut *C, _Float16 *pre, const WorkItem *items, const int32_t *nitems, int N, int K,
-                 int stage, hipStream_t st)
+                 int stage, hipStream_t st, const int32_t *row_src = nullptr, int row_div = 1)
 {
 #define MOE_MFMA_SHAPE(WM_, WN_, TM_, TN_)                                                        \
     launch_mfma_cfg<F16, TOut, ACT, KEEP, WM_, WN_, TM_, TN_>(A, W, bias, C, pre, items, nitems,    \
-                                                              gp.max_items, N, K, stage, st)
+                                                              gp.max_items, N, K, stage, st,       \
+                                                              row_src, row_div)
     if (gp.bm == 256)
         MOE_MFMA_SHAPE(2, 4, 4, 2);
     else if (gp.bm == 64)
@@ -470,8 +479,9 @@ void launch_mfma(const GemmPlan &gp, const uint16_t *A, const uint16_t *W, const
 
 template <int ACT>
 void launch_mfma_pair(const moe_shape &s, const uint16_t *xe, const uint16_t *W1p,
-                      const float *b1, const uint16_t *W2p, const float *b2, float *ye,
-                      _Float16 *pre, const Workspace &w, int chunk, hipStream_t st)
+                      const float *b1, const uint16_t *W2p, const float *b2, _Float16 *ye,
+                      _Float16 *pre, const Workspace &w, int chunk, hipStream_t st,
+                      const int32_t *row_src, int row_div)
 {
     _Float16 *H = static_cast<_Float16 *>(w.hidden);
     const WorkItem *it1 = w.items[0] + static_cast<size_t>(chunk) * w.gp[0].max_items;
@@ -479,12 +489,12 @@ void launch_mfma_pair(const moe_shape &s, const uint16_t *xe, const uint16_t *W1
     if (pre != nullptr)
         launch_mfma<false, _Float16, ACT, true>(w.gp[0], xe, W1p, b1, H, pre, it1,
                                                 w.nitems[0] + chunk, s.d_ff, s.d_model,
-                                                kStageGemm1, st);
+                                                kStageGemm1, st, row_src, row_div);
     else
         launch_mfma<false, _Float16, ACT, false>(w.gp[0], xe, W1p, b1, H, nullptr, it1,
                                                  w.nitems[0] + chunk, s.d_ff, s.d_model,
-                                                 kStageGemm1, st);
-    launch_mfma<true, float, MOE_ACT_IDENTITY, false>(w.gp[1], reinterpret_cast<const uint16_t *>(H),
+                                                 kStageGemm1, st, row_src, row_div);
+    launch_mfma<true, _Float16, MOE_ACT_IDENTITY, false>(w.gp[1], reinterpret_cast<const uint16_t *>(H),
                                                       W2p, b2, ye, nullptr, it2, w.nitems[1] + chunk,
                                                       s.d_model, s.d_ff, kStageGemm2, st);
 }
@@ -528,9 +538,13 @@ GemmPlan choose_gemm_plan(const moe_shape &s, int which, int n_chunks)
 }
 
 moe_status launch_ffn(const moe_shape &s, const void *xe, const void *W1p, const float *b1,
-                      const void *W2p, const float *b2, float *ye, const Workspace &w,
-                      int chunk, hipStream_t st, void *pre)
+                      const void *W2p, const float *b2, void *ye, const Workspace &w,
+                      int chunk, hipStream_t st, void *pre, const int32_t *row_src)
 {
+    if (row_src != nullptr && s.dtype != MOE_BF16) {
+        set_error("gathered token rows are for bf16 layers only");
+        return MOE_EUNSUPPORTED;
+    }
     if (pre != nullptr && s.dtype != MOE_BF16) {
         set_error("the pre-activations are kept for bf16 layers only");
         return MOE_EUNSUPPORTED;
@@ -540,12 +554,14 @@ moe_status launch_ffn(const moe_shape &s, const void *xe, const void *W1p, const
         if (s.dtype == MOE_BF16)                                                               \
             launch_mfma_pair<ACT>(s, static_cast<const uint16_t *>(xe),                         \
                                   static_cast<const uint16_t *>(W1p), b1,                       \
-                                  static_cast<const uint16_t *>(W2p), b2, ye,                   \
-                                  static_cast<_Float16 *>(pre), w, chunk, st);                  \
+                                  static_cast<const uint16_t *>(W2p), b2,                       \
+                                  static_cast<_Float16 *>(ye), static_cast<_Float16 *>(pre), w, \
+                                  chunk, st, row_src, s.k);                                     \
         else                                                                                   \
             launch_f32_pair<ACT>(s, static_cast<const float *>(xe),                             \
                                  static_cast<const float *>(W1p), b1,                           \
-                                 static_cast<const float *>(W2p), b2, ye, w, chunk, st);        \
+                                 static_cast<const float *>(W2p), b2, static_cast<float *>(ye), \
+                                 w, chunk, st);                                                 \
         break;
     switch (s.act) {
         MOE_FFN_CASE(MOE_ACT_GELU_ERF)

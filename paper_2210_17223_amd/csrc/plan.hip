@@ -392,14 +392,16 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rank_prefix_kernel(
     }
 }
 
-// Work lists for chunk c (blockIdx.x) and GEMM g (blockIdx.y).  Expert e's rows of the chunk
-// are the slots whose source assignment lies in [t0*k, t1*k); src_of ascends inside an
-// expert, so both ends are binary searches (lane e of the first wavefront owns expert e).
+// Work lists for FFN group f (blockIdx.x) and GEMM g (blockIdx.y).  Group f of n_groups is the
+// run of chunks [f*n_chunks/n_groups, (f+1)*n_chunks/n_groups), i.e. the tokens [t0, t1) between
+// those chunks' bounds.  Expert e's rows of the group are the slots whose source assignment
+// lies in [t0*k, t1*k); src_of ascends inside an expert, so both ends are binary searches
+// (lane e of the first wavefront owns expert e).
 __global__ __launch_bounds__(256) void plan_items_kernel(
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ src_of,
     WorkItem *__restrict__ items0, int32_t *__restrict__ nitems0, GemmPlan gp0,
     WorkItem *__restrict__ items1, int32_t *__restrict__ nitems1, GemmPlan gp1, int T, int k,
-    int E, int n_chunks)
+    int E, int n_chunks, int n_groups)
 {
     __shared__ int32_t lo_s[kMaxExperts], hi_s[kMaxExperts], mt_s[kMaxExperts];
     __shared__ int32_t cum_s[kMaxExperts + 1];
@@ -410,12 +412,14 @@ __global__ __launch_bounds__(256) void plan_items_kernel(
 
     if (threadIdx.x < kWave) {
         const int e = threadIdx.x;
-        const long t0 = static_cast<long>(c) * T / n_chunks;
-        const long t1 = static_cast<long>(c + 1) * T / n_chunks;
+        const long c0 = static_cast<long>(c) * n_chunks / n_groups;
+        const long c1 = static_cast<long>(c + 1) * n_chunks / n_groups;
+        const long t0 = c0 * T / n_chunks;
+        const long t1 = c1 * T / n_chunks;
         int lo = 0, hi = 0;
         if (e < E) {
             const int b = offsets[e], end = offsets[e + 1];
-            if (n_chunks == 1) {
+            if (n_groups == 1) {
                 lo = b;
                 hi = end;
             } else {
@@ -561,12 +565,12 @@ moe_status launch_plan(const moe_shape &s, const int32_t *expert_idx, int32_t *c
     return MOE_OK;
 }
 
-moe_status launch_items(const moe_shape &s, int n_chunks, const int32_t *offsets,
+moe_status launch_items(const moe_shape &s, int n_chunks, int n_groups, const int32_t *offsets,
                         const int32_t *src_of, const Workspace &w, hipStream_t st)
 {
-    hipLaunchKernelGGL(plan_items_kernel, dim3(n_chunks, 2, 8), dim3(256), 0, st, offsets, src_of,
+    hipLaunchKernelGGL(plan_items_kernel, dim3(n_groups, 2, 8), dim3(256), 0, st, offsets, src_of,
                        w.items[0], w.nitems[0], w.gp[0], w.items[1], w.nitems[1], w.gp[1], s.T,
-                       s.k, s.E, n_chunks);
+                       s.k, s.E, n_chunks, n_groups);
     MOE_TRY_HIP(hipGetLastError());
     return MOE_OK;
 }

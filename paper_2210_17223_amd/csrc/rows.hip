@@ -3,7 +3,8 @@
 // Sec. 2.2 forward-pass timeline).  Both are bound by HBM bandwidth: one wavefront
 // owns one token, every lane moves 16 bytes per step, a token's row is read once
 // and written to each of its kept slots (pack) or its kept expert rows are read
-// once and the weighted sum written once (unpack).
+// once and the weighted sum written once (unpack).  Expert outputs are stored in fp16 for
+// bf16 layers (fp32 for fp32 layers); the weighted sum and y are fp32.
 #include "common.h"
 
 namespace moe {
@@ -36,14 +37,17 @@ __global__ __launch_bounds__(kRowThreads) void scatter_rows_kernel(
     }
 }
 
-// y[t,:] = sum_j gate[t,j] * ye[slot_of[t*k+j],:] over kept j, ascending j.
+// y[t,:] = sum_j gate[t,j] * ye[slot_of[t*k+j],:] over kept j, ascending j, in fp32.
+// TIn: stored type of the expert outputs (fp16 for bf16 layers, fp32 for fp32 layers); a lane
+// takes 16 bytes of every kept row per step (NV = 8 or 4 elements) and writes NV fp32 values.
 // ACT_BYTES: element size of the optional copy in the activation dtype (0 = none).
-template <int ACT_BYTES>
+template <typename TIn, int ACT_BYTES>
 __global__ __launch_bounds__(kRowThreads) void combine_rows_kernel(
-    const float4 *__restrict__ ye, const int32_t *__restrict__ slot_of,
-    const float *__restrict__ gate, float4 *__restrict__ y, void *__restrict__ y_act,
+    const uint4 *__restrict__ ye, const int32_t *__restrict__ slot_of,
+    const float *__restrict__ gate, float *__restrict__ y, void *__restrict__ y_act,
     int t0, int t1, int k, int vec, int max_rows)
 {
+    constexpr int NV = 16 / static_cast<int>(sizeof(TIn));
     const int lane = lane_id();
     const int t = t0 + blockIdx.x * kRowWaves + threadIdx.x / kWave;
     if (t >= t1) return;
@@ -58,31 +62,52 @@ __global__ __launch_bounds__(kRowThreads) void combine_rows_kernel(
         g[j] = __shfl(my_gate, j);
     }
     for (int c = lane; c < vec; c += kWave) {
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        float acc[NV];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) acc[i] = 0.0f;
         bool first = true;
 #pragma unroll
         for (int j = 0; j < kMaxTopK; ++j) {
             if (j < k && slots[j] >= 0) {
-                const float4 v = ye[static_cast<size_t>(slots[j]) * vec + c];
+                const uint4 raw = ye[static_cast<size_t>(slots[j]) * vec + c];
+                float v[NV];
+                if constexpr (NV == 8) {
+                    typedef __attribute__((ext_vector_type(8))) _Float16 half8;
+                    const half8 hv = __builtin_bit_cast(half8, raw);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[i] = static_cast<float>(hv[i]);
+                } else {
+                    v[0] = __uint_as_float(raw.x); v[1] = __uint_as_float(raw.y);
+                    v[2] = __uint_as_float(raw.z); v[3] = __uint_as_float(raw.w);
+                }
                 if (first) {
-                    acc = make_float4(g[j] * v.x, g[j] * v.y, g[j] * v.z, g[j] * v.w);
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) acc[i] = g[j] * v[i];
                     first = false;
                 } else {
-                    acc.x = __builtin_fmaf(g[j], v.x, acc.x);
-                    acc.y = __builtin_fmaf(g[j], v.y, acc.y);
-                    acc.z = __builtin_fmaf(g[j], v.z, acc.z);
-                    acc.w = __builtin_fmaf(g[j], v.w, acc.w);
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) acc[i] = __builtin_fmaf(g[j], v[i], acc[i]);
                 }
             }
         }
-        y[static_cast<size_t>(t) * vec + c] = acc;
+        const size_t at = (static_cast<size_t>(t) * vec + c) * NV;       // element index in the row-major output
+#pragma unroll
+        for (int i = 0; i < NV; i += 4)
+            *reinterpret_cast<float4 *>(y + at + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
         if constexpr (ACT_BYTES == 4) {
-            static_cast<float4 *>(y_act)[static_cast<size_t>(t) * vec + c] = acc;
+#pragma unroll
+            for (int i = 0; i < NV; i += 4)
+                *reinterpret_cast<float4 *>(static_cast<float *>(y_act) + at + i) =
+                    make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
         } else if constexpr (ACT_BYTES == 2) {
-            uint2 p;
-            p.x = f32_to_bf16(acc.x) | (static_cast<uint32_t>(f32_to_bf16(acc.y)) << 16);
-            p.y = f32_to_bf16(acc.z) | (static_cast<uint32_t>(f32_to_bf16(acc.w)) << 16);
-            static_cast<uint2 *>(y_act)[static_cast<size_t>(t) * vec + c] = p;
+            uint32_t p[NV / 2];
+#pragma unroll
+            for (int i = 0; i < NV; i += 2)
+                p[i / 2] = f32_to_bf16(acc[i]) | (static_cast<uint32_t>(f32_to_bf16(acc[i + 1])) << 16);
+            if constexpr (NV == 8)
+                *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(y_act) + at) = make_uint4(p[0], p[1], p[2], p[3]);
+            else
+                *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(y_act) + at) = make_uint2(p[0], p[1]);
         }
     }
 }
@@ -103,25 +128,24 @@ moe_status launch_scatter(const moe_shape &s, const void *x, const int32_t *slot
     return MOE_OK;
 }
 
-moe_status launch_combine(const moe_shape &s, const float *ye, const int32_t *slot_of,
+moe_status launch_combine(const moe_shape &s, const void *ye, const int32_t *slot_of,
                           const float *gate, float *y, void *y_act, int t0, int t1,
                           hipStream_t st, int64_t rows)
 {
     if (t1 <= t0) return MOE_OK;
-    const int vec = s.d_model / 4;   // 16-byte vectors of fp32
+    const int vec = s.d_model * ye_elem_bytes(s) / 16;   // 16-byte vectors per row of ye
     const int max_rows = static_cast<int>(rows < 0 ? moe_max_rows(&s) : rows);
     const dim3 grid(ceil_div(t1 - t0, kRowWaves)), block(kRowThreads);
-    const float4 *ye4 = reinterpret_cast<const float4 *>(ye);
-    float4 *y4 = reinterpret_cast<float4 *>(y);
-    if (y_act == nullptr)
-        hipLaunchKernelGGL(combine_rows_kernel<0>, grid, block, 0, st, ye4, slot_of, gate, y4,
-                           y_act, t0, t1, s.k, vec, max_rows);
-    else if (s.dtype == MOE_BF16)
-        hipLaunchKernelGGL(combine_rows_kernel<2>, grid, block, 0, st, ye4, slot_of, gate, y4,
-                           y_act, t0, t1, s.k, vec, max_rows);
-    else
-        hipLaunchKernelGGL(combine_rows_kernel<4>, grid, block, 0, st, ye4, slot_of, gate, y4,
-                           y_act, t0, t1, s.k, vec, max_rows);
+    const uint4 *ye4 = static_cast<const uint4 *>(ye);
+#define MOE_COMBINE(TIN, AB)                                                                      \
+    hipLaunchKernelGGL((combine_rows_kernel<TIN, AB>), grid, block, 0, st, ye4, slot_of, gate, y,  \
+                       y_act, t0, t1, s.k, vec, max_rows)
+    if (s.dtype == MOE_BF16) {
+        if (y_act == nullptr) MOE_COMBINE(_Float16, 0); else MOE_COMBINE(_Float16, 2);
+    } else {
+        if (y_act == nullptr) MOE_COMBINE(float, 0); else MOE_COMBINE(float, 4);
+    }
+#undef MOE_COMBINE
     MOE_TRY_HIP(hipGetLastError());
     return MOE_OK;
 }

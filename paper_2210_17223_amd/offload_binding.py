@@ -43,8 +43,8 @@ def moe_expert_ffn_offloaded(s: Shape, xe, offsets, W1p_host, W2p_host, b1, b2, 
                              resident: int, workspace, stream=None) -> None:
     rows = moe_max_rows(s)
     wb = moe_packed_weight_bytes(s)
-    if xe.numel() < rows * s.d_model or ye.numel() < rows * s.d_model or ye.dtype != torch.float32:
-        raise MoeError("xe / ye: need max_rows x d_model elements (ye fp32)")
+    if xe.numel() < rows * s.d_model or ye.numel() < rows * s.d_model or ye.dtype != s.ye_dtype:
+        raise MoeError("xe / ye: need max_rows x d_model elements (ye fp16)")
     if staging.numel() * staging.element_size() < moe_offload_staging_bytes(s, resident):
         raise MoeError("staging is smaller than moe_offload_staging_bytes")
     if workspace.numel() * workspace.element_size() < moe_offload_workspace_bytes(s):

@@ -48,7 +48,7 @@ def moe_layer_forward_keep(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1p, 
     _need(slot_of, torch.int32, T * k, "slot_of")
     _need(src_of, torch.int32, rows, "src_of")
     _need(xe, torch.bfloat16, rows * d, "xe")
-    _need(ye, torch.float32, rows * d, "ye")
+    _need(ye, s.ye_dtype, rows * d, "ye")
     _need(pre, torch.float16, rows * h, "pre")
     _need(hid, torch.float16, rows * h, "hid")
     _need(y, torch.float32, T * d, "y")
@@ -74,7 +74,7 @@ def moe_layer_backward(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1, W2, W
     _need(slot_of, torch.int32, T * k, "slot_of")
     _need(src_of, torch.int32, rows, "src_of")
     _need(xe, torch.bfloat16, rows * d, "xe")
-    _need(ye, torch.float32, rows * d, "ye")
+    _need(ye, s.ye_dtype, rows * d, "ye")
     if pre is not None:
         _need(pre, torch.float16, rows * h, "pre")
     if hid is not None:

@@ -34,8 +34,8 @@ def padded_buffers(s, n_micro):
                 slot_of=i32(s.T * s.k), src_of=i32(slots),
                 xs=torch.full((slots * s.d_model,), 3.0, dtype=s.torch_dtype, device=DEV),
                 xr=torch.full((slots * s.d_model,), 5.0, dtype=s.torch_dtype, device=DEV),
-                ys=torch.full((slots * s.d_model,), 11.0, device=DEV),
-                yr=torch.full((slots * s.d_model,), 13.0, device=DEV),
+                ys=torch.full((slots * s.d_model,), 11.0, dtype=s.ye_dtype, device=DEV),
+                yr=torch.full((slots * s.d_model,), 13.0, dtype=s.ye_dtype, device=DEV),
                 y=torch.full((s.T * s.d_model,), 17.0, device=DEV),
                 ws=torch.empty(moe.moe_padded_workspace_bytes(s, n_micro), dtype=torch.uint8, device=DEV))
 
@@ -68,8 +68,8 @@ def check_padded(li, L, s, p):
     assert torch.equal(p["xr"].view(torch.int16 if li.dtype == "bf16" else torch.int32),
                        p["xs"].view(torch.int16 if li.dtype == "bf16" else torch.int32))
     # the second all-to-all carried every slot row as it was
-    assert torch.equal(p["yr"].view(torch.int32), p["ys"].view(torch.int32))
-    ys = p["ys"].cpu().numpy().reshape(E * C, d)
+    assert torch.equal(p["yr"].view(torch.int16), p["ys"].view(torch.int16))
+    ys = p["ys"].float().cpu().numpy().reshape(E * C, d)
     assert (ys[~held] == 11.0).all()                          # rows without a token: not computed
     tol = TOL_BF16 if li.dtype == "bf16" else 1e-5
     assert rel_rms_err(p["y"].cpu().numpy().reshape(T, d), o.y) <= tol

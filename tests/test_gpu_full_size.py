@@ -24,7 +24,7 @@ def oracle_routing(li):
     return idx, gate, count, off, slot_of, src_of
 
 
-@pytest.mark.parametrize("name,chunk_list", [("gpt2s_moe", (1,)), ("skewed", (1,)),
+@pytest.mark.parametrize("name,chunk_list", [("gpt2s_moe", (1,)), ("skewed", (1, 4)),
                                              ("large_chunked", (1, 4, 8))])
 def test_full_size_layer(name, chunk_list):
     li = wl.make_layer(wl.CONFIGS[name], seed=0, threads=16)
@@ -40,28 +40,38 @@ def test_full_size_layer(name, chunk_list):
     s = shape_of(li)
     L = DeviceLayer(li, s, n_chunks=max(chunk_list))
     li.W1 = li.W2 = None                     # the device holds the packed copies now
-    ref_bits = None
+    ref = []
     for n_chunks in chunk_list:
-        L.b["y"].fill_(float("nan"))
-        L.b["xe"].zero_()
-        L.layer(n_chunks)
-        assert_ints_equal(L.ints(), o)
-        np.testing.assert_allclose(L.b["gate"].cpu().numpy().reshape(li.T, li.k), gate, rtol=1e-6)
-        xe = download(L.b["xe"]).reshape(-1, li.d)
-        assert np.array_equal(xe[:A].view(np.uint32), li.x[src_of // li.k].view(np.uint32))
-        y = L.b["y"].cpu().numpy().reshape(li.T, li.d)
-        assert np.isfinite(y).all()
-        err = float(np.abs(y - o.y).max() / rms)          # every element of every token
-        print(f"{name} n_chunks={n_chunks}: max-abs err / RMS = {err:.3e}", flush=True)
-        assert err <= TOL_BF16, f"{name} n_chunks={n_chunks}: max-abs err / RMS = {err}"
-        assert not y[fully_dropped].any()                 # dropped tokens give zeros
-        if ref_bits is None:
-            ref_bits = y.view(np.uint32).copy()
-        else:                                              # chunking changes no output bit
-            assert np.array_equal(y.view(np.uint32), ref_bits), f"n_chunks={n_chunks}"
+        # the first chunked run of the large layer with one FFN launch per chunk, the others
+        # with the default grouping (two FFN launches at this size)
+        before = moe.moe_tune_ffn_group_rows(1 if n_chunks == 4 else 0)
+        try:
+            _run_and_check(L, li, o, name, n_chunks, A, gate, src_of, rms, fully_dropped, ref)
+        finally:
+            moe.moe_tune_ffn_group_rows(before)
     if name == "skewed":
         assert (slot_of < 0).mean() > 0.4                  # the Zipf bias really overflows
         assert count.max() > li.C > count.min()
+
+
+def _run_and_check(L, li, o, name, n_chunks, A, gate, src_of, rms, fully_dropped, ref):
+    L.b["y"].fill_(float("nan"))
+    L.b["xe"].zero_()
+    L.layer(n_chunks)
+    assert_ints_equal(L.ints(), o)
+    np.testing.assert_allclose(L.b["gate"].cpu().numpy().reshape(li.T, li.k), gate, rtol=1e-6)
+    xe = download(L.b["xe"]).reshape(-1, li.d)
+    assert np.array_equal(xe[:A].view(np.uint32), li.x[src_of // li.k].view(np.uint32))
+    y = L.b["y"].cpu().numpy().reshape(li.T, li.d)
+    assert np.isfinite(y).all()
+    err = float(np.abs(y - o.y).max() / rms)          # every element of every token
+    print(f"{name} n_chunks={n_chunks}: max-abs err / RMS = {err:.3e}", flush=True)
+    assert err <= TOL_BF16, f"{name} n_chunks={n_chunks}: max-abs err / RMS = {err}"
+    assert not y[fully_dropped].any()                 # dropped tokens give zeros
+    if not ref:
+        ref.append(y.view(np.uint32).copy())
+    else:                                              # chunking changes no output bit
+        assert np.array_equal(y.view(np.uint32), ref[0]), f"n_chunks={n_chunks}"
 
 
 def canon(expert_idx, slot_of, gate, T, k):

@@ -66,18 +66,21 @@ def test_entry_points_one_by_one(name):
     moe.moe_expert_ffn(s, b["xe"], b["offsets"], b["W1p"], None, b["W2p"], None, b["ye"],
                        b["workspace"])
     torch.cuda.synchronize()
-    ye = b["ye"].cpu().numpy().reshape(-1, li.d)
+    ye = b["ye"].float().cpu().numpy().reshape(-1, li.d)
     assert rel_rms_err(ye[:o.A], ye_ref) <= TOL[li.dtype]
     assert not ye[o.A:].any()
-    # --- combine on the oracle's expert outputs (rounded to fp32)
+    # --- combine: both sides are handed the same expert outputs, the oracle's rounded to the
+    # type the library stores them in (fp16 for bf16 layers, fp32 for fp32 layers)
+    ye_in = ye_ref.astype(np.float16 if li.dtype == "bf16" else np.float32)
     ye_dev = torch.zeros_like(b["ye"])
-    ye_dev[:o.A * li.d] = torch.from_numpy(ye_ref.astype(np.float32).reshape(-1)).to(DEV)
+    ye_dev[:o.A * li.d] = torch.from_numpy(ye_in.reshape(-1)).to(DEV)
     slot = torch.from_numpy(o.slot_of).to(DEV)
     gate = torch.from_numpy(o.gate.reshape(-1)).to(DEV)
     moe.moe_combine(s, ye_dev, slot, gate, b["y"])
     torch.cuda.synchronize()
     y = b["y"].cpu().numpy().reshape(li.T, li.d)
-    assert rel_rms_err(y, o.y) <= 1e-5
+    y_ref = oracle.combine(ye_in.astype(np.float64), o.slot_of, o.gate, li.T, li.k)
+    assert rel_rms_err(y, y_ref) <= 1e-5
     dropped = (o.slot_of.reshape(li.T, li.k) < 0).all(1)
     assert not y[dropped].any()
 
@@ -115,28 +118,37 @@ def test_dispatch_skips_indices_that_name_no_expert(name):
     assert not xe[A:].any()
 
 
+@pytest.mark.parametrize("group_rows", [1, 16, 512], ids=["ffn_per_chunk", "ffn_groups_of_16_rows", "default_groups"])
 @pytest.mark.parametrize("name", list(SMALL))
-def test_whole_layer_and_chunk_invariance(name):
+def test_whole_layer_and_chunk_invariance(name, group_rows):
+    """Every n_chunks gives the oracle's integers and the same output bits.  group_rows sets how
+    many rows per expert an FFN launch must hold: 1 = one FFN launch per chunk (every side
+    stream and event in use), 16 = a few chunks per FFN launch, 512 = the default (these small
+    layers then run their FFN in one launch)."""
     li = wl.make_layer(SMALL[name], seed=1)
     o = run_oracle(li)
     s = shape_of(li)
     L = DeviceLayer(li, s, n_chunks=64, y_act=True)
     ref_bits = None
-    for n_chunks in (1, 2, 3, 4, 8, 64):
-        for key in ("y", "ye", "xe"):
-            L.b[key].zero_()
-        L.layer(n_chunks)
-        assert_ints_equal(L.ints(), o)
-        np.testing.assert_allclose(L.b["gate"].cpu().numpy().reshape(li.T, li.k), o.gate, rtol=1e-6)
-        y = L.b["y"].cpu().numpy().reshape(li.T, li.d)
-        assert rel_rms_err(y, o.y) <= TOL[li.dtype], f"n_chunks={n_chunks}"
-        if ref_bits is None:
-            ref_bits = y.view(np.uint32).copy()
-        else:                                          # chunking changes no bit of the output
-            assert np.array_equal(y.view(np.uint32), ref_bits), f"n_chunks={n_chunks}"
-        y_act = download(L.b["y_act"]).reshape(li.T, li.d)
-        want = wl.bf16_round(y) if li.dtype == "bf16" else y
-        assert np.array_equal(y_act.view(np.uint32), want.view(np.uint32))
+    before = moe.moe_tune_ffn_group_rows(group_rows)
+    try:
+        for n_chunks in (1, 2, 3, 4, 8, 64):
+            for key in ("y", "ye", "xe"):
+                L.b[key].zero_()
+            L.layer(n_chunks)
+            assert_ints_equal(L.ints(), o)
+            np.testing.assert_allclose(L.b["gate"].cpu().numpy().reshape(li.T, li.k), o.gate, rtol=1e-6)
+            y = L.b["y"].cpu().numpy().reshape(li.T, li.d)
+            assert rel_rms_err(y, o.y) <= TOL[li.dtype], f"n_chunks={n_chunks}"
+            if ref_bits is None:
+                ref_bits = y.view(np.uint32).copy()
+            else:                                          # chunking changes no bit of the output
+                assert np.array_equal(y.view(np.uint32), ref_bits), f"n_chunks={n_chunks}"
+            y_act = download(L.b["y_act"]).reshape(li.T, li.d)
+            want = wl.bf16_round(y) if li.dtype == "bf16" else y
+            assert np.array_equal(y_act.view(np.uint32), want.view(np.uint32))
+    finally:
+        moe.moe_tune_ffn_group_rows(before)
 
 
 @pytest.mark.parametrize("T,d,E,k", [(600, 128, 16, 2), (9000, 64, 32, 2), (700, 72, 5, 3)],
