@@ -157,6 +157,26 @@ moe_status moe_dispatch(const moe_shape *s, const void *x, const int32_t *expert
                         int32_t *counts, int32_t *offsets, int32_t *slot_of,
                         int32_t *src_of, void *xe, void *workspace, void *stream);
 
+/* moe_dispatch for callers that cannot allocate device memory or have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments and results as moe_dispatch
+ * minus `workspace`; the plan's scratch (256 bytes per plan segment; a segment
+ * is 4 to 64 tokens by shape) lives in an array of
+ * moe_dispatch_static_limit() = 4 MiB inside the library's device image, which
+ * every GPU the library runs on holds until the process ends.  The call
+ * allocates and frees nothing (its first call on a device looks the array's
+ * address up once).  A shape whose plan needs more scratch than the array holds
+ * is refused with MOE_EUNSUPPORTED before anything is enqueued.  All calls on
+ * one GPU share that GPU's array, whatever their stream or thread: two calls
+ * whose work overlaps in time on one GPU race on it; serialise them (one
+ * stream, or events).  Nothing in the array has to start at zero: every call
+ * overwrites the part it reads. */
+size_t moe_dispatch_static_limit(void);
+moe_status moe_dispatch_static(const moe_shape *s, const void *x,
+                               const int32_t *expert_idx, int32_t *counts,
+                               int32_t *offsets, int32_t *slot_of, int32_t *src_of,
+                               void *xe, void *stream);
+
 /* Expert FFN (Sec. 2.1): for slot r of expert e,
  *   ye[r,:] = act(xe[r,:] W1[e] + b1[e]) W2[e] + b2[e].
  *   W1p, W2p from moe_pack_weights; b1 fp32 [E,d_ff] and b2 fp32 [E,d_model] may

@@ -77,6 +77,10 @@ def lib() -> C.CDLL:
         L.moe_pack_gate.argtypes = [sp, vp, vp, vp]
         L.moe_route.argtypes = [sp, vp, vp, vp, i32, vp, vp, vp]
         L.moe_dispatch.argtypes = [sp] + [vp] * 9
+        L.moe_dispatch_static.argtypes = [sp] + [vp] * 8
+        L.moe_dispatch_static.restype = C.c_int
+        L.moe_dispatch_static_limit.restype = sz
+        L.moe_dispatch_static_limit.argtypes = []
         L.moe_expert_ffn.argtypes = [sp] + [vp] * 9
         L.moe_combine.argtypes = [sp] + [vp] * 6
         L.moe_layer_chunked.argtypes = [sp, i32, vp, vp, vp, i32] + [vp] * 16
@@ -201,6 +205,25 @@ def moe_tune_ffn_group_rows(rows: int = 0) -> int:
     """Sets (rows >= 1) or reads the rows per expert an FFN launch of a chunked layer must
     hold on average; returns the previous value."""
     return int(lib().moe_tune_ffn_group_rows(int(rows)))
+
+
+def moe_dispatch_static_limit() -> int:
+    return int(lib().moe_dispatch_static_limit())
+
+
+def moe_dispatch_static(s: Shape, x, expert_idx, counts, offsets, slot_of, src_of, xe,
+                        stream=None) -> None:
+    rows = moe_max_rows(s)
+    _need(x, s.torch_dtype, s.T * s.d_model, "x")
+    _need(expert_idx, torch.int32, s.T * s.k, "expert_idx")
+    _need(counts, torch.int32, s.E, "counts")
+    _need(offsets, torch.int32, s.E + 1, "offsets")
+    _need(slot_of, torch.int32, s.T * s.k, "slot_of")
+    _need(src_of, torch.int32, rows, "src_of")
+    _need(xe, s.torch_dtype, rows * s.d_model, "xe")
+    _check(lib().moe_dispatch_static(C.byref(s), _ptr(x), _ptr(expert_idx), _ptr(counts),
+                                     _ptr(offsets), _ptr(slot_of), _ptr(src_of), _ptr(xe),
+                                     _stream(stream)))
 
 
 def moe_expert_ffn(s: Shape, xe, offsets, W1p, b1, W2p, b2, ye, workspace, stream=None) -> None:

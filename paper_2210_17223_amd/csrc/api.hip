@@ -223,6 +223,38 @@ moe_status chunk_resources(ChunkResources **out)
     return MOE_OK;
 }
 
+// ---- scratch of the entry point that allocates nothing ---------------------------
+// moe_dispatch_static keeps the dispatch plan's per-segment expert counts here instead of in
+// a caller's workspace.  In host code the array's NAME is only a stand-in for the symbol: the
+// memory is reached through the address hipGetSymbolAddress returns, looked up once per
+// device (every GPU holds its own copy of the array at its own address).
+constexpr size_t kScratchBytes = size_t(4) << 20;
+__device__ __align__(256) unsigned char scratch[kScratchBytes];
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[16] = {};
+
+moe_status scratch_address(void **out)
+{
+    int dev = 0;
+    MOE_TRY_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 16) {
+        set_error("device index %d out of range", dev);
+        return MOE_EUNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        MOE_TRY_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (ptr == nullptr) {
+            set_error("hipGetSymbolAddress returned a null address for the scratch array");
+            return MOE_EHIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MOE_OK;
+}
+
 }  // namespace
 
 // The expert FFN of a chunked layer runs once per GROUP of consecutive chunks.  A launch
@@ -427,6 +459,42 @@ int32_t moe_tune_ffn_group_rows(int32_t rows)
     const int32_t before = g_group_rows.load(std::memory_order_relaxed);
     if (rows >= 1) g_group_rows.store(rows, std::memory_order_relaxed);
     return before;
+}
+
+size_t moe_dispatch_static_limit(void) { return kScratchBytes; }
+
+moe_status moe_dispatch_static(const moe_shape *s, const void *x, const int32_t *expert_idx,
+                               int32_t *counts, int32_t *offsets, int32_t *slot_of,
+                               int32_t *src_of, void *xe, void *stream)
+{
+    MOE_TRY(check_common(s));
+    MOE_REQUIRE_PTR(x);
+    MOE_REQUIRE_PTR(expert_idx);
+    MOE_REQUIRE_PTR(counts);
+    MOE_REQUIRE_PTR(offsets);
+    MOE_REQUIRE_PTR(slot_of);
+    MOE_REQUIRE_PTR(src_of);
+    MOE_REQUIRE_PTR(xe);
+    Workspace w = {};
+    w.seg_tok = route_segment_tokens(*s);
+    w.nseg = (s->T + w.seg_tok - 1) / w.seg_tok;
+    const size_t need = static_cast<size_t>(w.nseg) * kMaxExperts * sizeof(int32_t);
+    if (need > kScratchBytes) {
+        set_error("moe_dispatch_static: this shape's plan needs %zu bytes of scratch (%d segments "
+                  "of %d tokens), the static array holds %zu; use moe_dispatch with a workspace",
+                  need, w.nseg, w.seg_tok, kScratchBytes);
+        return MOE_EUNSUPPORTED;
+    }
+    void *ptr = nullptr;
+    MOE_TRY(scratch_address(&ptr));
+    w.seg_cnt = static_cast<int32_t *>(ptr);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    bool packed = false;
+    // n_chunks = 0: no work lists (they are the expert FFN's, which builds its own)
+    MOE_TIMED(kStagePlan, st, launch_plan(*s, expert_idx, counts, offsets, slot_of, src_of, w,
+                                          false, 0, st, false, x, xe, &packed));
+    if (!packed) MOE_TIMED(kStageScatter, st, launch_scatter(*s, x, slot_of, xe, 0, s->T, st));
+    return MOE_OK;
 }
 
 moe_status moe_expert_ffn(const moe_shape *s, const void *xe, const int32_t *offsets,

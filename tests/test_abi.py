@@ -102,3 +102,17 @@ def test_null_and_misaligned_pointers_are_refused_before_any_launch():
     assert "n_chunks" in moe.moe_last_error()
     assert L.moe_layer_chunked(C.byref(s), 65, ok, ok, z, 0, *args) == 1
     assert L.moe_route(None, ok, ok, z, 0, ok, ok, z) == 1
+
+
+def test_static_dispatch_refuses_what_does_not_fit_its_array():
+    """The entry point that allocates nothing rejects a plan larger than its static scratch
+    array before anything is enqueued (so this needs no GPU)."""
+    L = moe.lib()
+    assert moe.moe_dispatch_static_limit() == 4 << 20
+    s = moe.Shape.make(1 << 21, 64, 4, 64, 1, 1 << 21, dtype="bf16")   # 32768 segments of 256 bytes
+    buf = (C.c_char * 64)()
+    p = C.c_void_p((C.addressof(buf) + 15) // 16 * 16)
+    rc = L.moe_dispatch_static(C.byref(s), p, p, p, p, p, p, p, None)
+    assert rc == 2 and "static array holds" in moe.moe_last_error()
+    rc = L.moe_dispatch_static(C.byref(s), None, p, p, p, p, p, p, None)
+    assert rc == 1
