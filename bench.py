@@ -33,7 +33,8 @@ INFINITY_CACHE_BYTES = 256 << 20
 # The counters cannot be read from inside the process, so the figure is a stored
 # measurement, reported only for the workload and launch configuration it was taken on
 # (null for any other): {(workload, n_chunks): (FETCH_SIZE KiB, WRITE_SIZE KiB)} per launch.
-GEMM1_TRAFFIC_KIB = {}
+GEMM1_TRAFFIC_KIB = {("large_chunked", 1): (1563240.7, 1406581.4),     # profiles/layer_hbm_traffic_pmc.txt
+                     ("gpt2s_moe", 1): (70064.8, 50061.3)}
 FETCH_UNIT, WRITE_UNIT = 2.0, 1.0     # what the plain-copy calibration reads per counted KiB
 
 
@@ -54,6 +55,10 @@ def main() -> int:
     ap.add_argument("--group-rows", type=int, default=0,
                     help="with --chunks > 1: rows per expert an FFN launch must hold on average "
                          "(moe_tune_ffn_group_rows; 0 = the library's default, 1 = one FFN launch per chunk)")
+    ap.add_argument("--four-calls", action="store_true",
+                    help="a step is the four entry points one after the other on one stream "
+                         "(moe_route, moe_dispatch, moe_expert_ffn, moe_combine) instead of moe_layer_chunked: "
+                         "the expert FFN then reads the packed buffer and nothing overlaps")
     ap.add_argument("--comm", action="store_true",
                     help="the workload's layer in the padded equal-split layout with both all-to-alls "
                          "on the stand-in link (moe_layer_padded), alone and while a gradient "
@@ -174,6 +179,14 @@ def main() -> int:
                                  b["src_of"], b["xe"], b["workspace"])
                 moe.moe_expert_ffn_offloaded(s, b["xe"], b["offsets"], self.W1h, self.W2h, None, None,
                                              b["ye"], self.staging, args.offload, self.ows)
+                moe.moe_combine(s, b["ye"], b["slot_of"], b["gate"], b["y"], b["y_act"])
+                return
+            if args.four_calls:
+                moe.moe_route(s, x, b["Wgp"], self.bias, self.stride, b["expert_idx"], b["gate"])
+                moe.moe_dispatch(s, x, b["expert_idx"], b["counts"], b["offsets"], b["slot_of"],
+                                 b["src_of"], b["xe"], b["workspace"])
+                moe.moe_expert_ffn(s, b["xe"], b["offsets"], b["W1p"], None, b["W2p"], None, b["ye"],
+                                   b["workspace"])
                 moe.moe_combine(s, b["ye"], b["slot_of"], b["gate"], b["y"], b["y_act"])
                 return
             if args.backward and self.pre is not None:
@@ -340,8 +353,29 @@ def main() -> int:
         moe.moe_profile_enable(0, 0)
         return mean, med, mn
 
+    def row_mover_times():
+        """Pack and combine alone (moe_dispatch, moe_combine on the layer's own routing): their
+        stage times with nothing else running beside them, us per layer."""
+        n = min(args.steps, 50)
+        i_plan, i_sc, i_cb = (moe.STAGES.index(k) for k in ("plan", "scatter", "combine"))
+        moe.moe_profile_enable((1 << i_plan) | (1 << i_sc) | (1 << i_cb), n * n_layers)
+        for _ in range(n):
+            x = sets[0][0].x
+            for L in sets[0]:
+                b = L.b
+                moe.moe_dispatch(s, x, b["expert_idx"], b["counts"], b["offsets"], b["slot_of"], b["src_of"],
+                                 b["xe"], b["workspace"])
+                moe.moe_combine(s, b["ye"], b["slot_of"], b["gate"], b["y"], b["y_act"])
+                x = b["y_act"]
+        torch.cuda.synchronize()
+        t = {k: np.array(moe.moe_profile_read(i, n * n_layers)) for k, i in (("plan", i_plan), ("scatter", i_sc), ("combine", i_cb))}
+        moe.moe_profile_enable(0, 0)
+        per = lambda v: None if v.size == 0 else float(v.reshape(n, -1).sum(1).mean() * 1e3)
+        return per(t["plan"]), per(t["scatter"]), per(t["combine"])
+
     if not args.offload:
         st, med, mn = stage_times()
+        alone_plan_us, alone_pack_us, alone_combine_us = row_mover_times()
         kept_tokens = float(np.mean([(L.b["slot_of"].view(l0.T, l0.k) >= 0).any(1).sum().item() for L in sets[0]]))
         ye_sz = sets[0][0].b["ye"].element_size()
         # The method's bytes (what the two all-to-all payloads carry, in the storage type):
@@ -353,19 +387,23 @@ def main() -> int:
         comb_moved = (A * ye_sz + l0.T * 4 + (l0.T * esz if n_layers > 1 else 0)) * l0.d * n_layers + 8.0 * l0.T * l0.k * n_layers
         # (an unchunked layer of up to 64 MiB of token rows packs them in its plan launch: then
         # there is no pack stage and the bytes are set against the plan stage's time)
-        pack_in_plan = st["scatter"] is None
-        pack_us = st["plan"] if pack_in_plan else st["scatter"]
-        dc_us = (pack_us + st["combine"]) * 1e-6
+        # (inside the layer call the pack of a large layer runs beside the first expert GEMM, so
+        # its own rate is taken from the stand-alone calls)
+        pack_in_plan = alone_pack_us is None
+        pack_us = alone_plan_us if pack_in_plan else alone_pack_us
+        comb_us = alone_combine_us
+        dc_us = (pack_us + comb_us) * 1e-6
         out["dispatch_combine"] = {
-            "pack_us": pack_us, "combine_us": st["combine"], "pack_in_plan_launch": pack_in_plan,
+            "pack_us": pack_us, "combine_us": comb_us, "pack_in_plan_launch": pack_in_plan,
+            "timed": "moe_dispatch and moe_combine alone on the layer's routing (stage brackets)",
             "algorithmic_bytes": disp_alg + comb_alg,
             "GBps": (disp_alg + comb_alg) / dc_us / 1e9,
             "frac_of_hbm_peak": (disp_alg + comb_alg) / dc_us / 1e9 / PEAK_HBM_GBPS,
             "pack_GBps": disp_alg / (pack_us * 1e-6) / 1e9,
-            "combine_GBps": comb_alg / (st["combine"] * 1e-6) / 1e9,
+            "combine_GBps": comb_alg / (comb_us * 1e-6) / 1e9,
             "moved_bytes": disp_alg + comb_moved,
             "moved_GBps": (disp_alg + comb_moved) / dc_us / 1e9,
-            "combine_moved_GBps": comb_moved / (st["combine"] * 1e-6) / 1e9,
+            "combine_moved_GBps": comb_moved / (comb_us * 1e-6) / 1e9,
             "note": "algorithmic = (T'+A)*d*s packed + (A+T)*d*s unpacked, s = storage element size (the "
                     "target figure); moved = what the kernels transfer: expert rows as stored "
                     f"({ye_sz} B/element), y in fp32"}
@@ -489,6 +527,24 @@ def calibrate() -> int:
             out["mfma"][f"{'random' if rnd else 'constant'}_operands_{wps}_wave_per_simd"] = {
                 "ms": t, "tflops": flops / (t * 1e-3) / 1e12,
                 "frac_of_nominal": flops / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    # a yardstick, not a roof: the vendor library's dense bf16 GEMM (through torch.matmul) on
+    # random data of the two sizes that bracket the layer's GEMMs
+    out["vendor_dense_gemm"] = {}
+    for m, n, k in ((8192, 8192, 8192), (65536, 8192, 2048), (65536, 2048, 8192)):
+        a = torch.randn(m, k, device=dev, dtype=torch.bfloat16)
+        b = torch.randn(k, n, device=dev, dtype=torch.bfloat16)
+        for _ in range(3):
+            torch.matmul(a, b)
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(10):
+            torch.matmul(a, b)
+        e1.record()
+        torch.cuda.synchronize()
+        t = e0.elapsed_time(e1) / 10
+        out["vendor_dense_gemm"][f"{m}x{n}x{k}"] = {"ms": t, "tflops": 2.0 * m * n * k / (t * 1e-3) / 1e12,
+                                                      "frac_of_nominal": 2.0 * m * n * k / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        del a, b
     print(json.dumps(out))
     return 0
 
