@@ -389,13 +389,17 @@ def main() -> int:
         # there is no pack stage and the bytes are set against the plan stage's time)
         # (inside the layer call the pack of a large layer runs beside the first expert GEMM, so
         # its own rate is taken from the stand-alone calls)
+        # The combine figure is the layer's own stage (it runs alone on the caller's stream
+        # there); the stand-alone call's is printed beside it (its rows come from HBM, inside
+        # the layer part of them is still in the Infinity Cache).
         pack_in_plan = alone_pack_us is None
         pack_us = alone_plan_us if pack_in_plan else alone_pack_us
-        comb_us = alone_combine_us
+        comb_us = st["combine"] if args.chunks == 1 else alone_combine_us
         dc_us = (pack_us + comb_us) * 1e-6
         out["dispatch_combine"] = {
             "pack_us": pack_us, "combine_us": comb_us, "pack_in_plan_launch": pack_in_plan,
-            "timed": "moe_dispatch and moe_combine alone on the layer's routing (stage brackets)",
+            "timed": "pack: moe_dispatch alone on the layer's routing; combine: its stage inside the layer call",
+            "combine_alone_us": alone_combine_us,
             "algorithmic_bytes": disp_alg + comb_alg,
             "GBps": (disp_alg + comb_alg) / dc_us / 1e9,
             "frac_of_hbm_peak": (disp_alg + comb_alg) / dc_us / 1e9 / PEAK_HBM_GBPS,

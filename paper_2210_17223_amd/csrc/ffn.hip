@@ -16,6 +16,8 @@
 
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 namespace moe {
 namespace {
 
@@ -376,6 +378,219 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void grouped_gemm_mfma_kernel(
     }
 }
 
+// ---------------------------------------------------------------- 256 x 256 ping-pong GEMM
+// The same product as grouped_gemm_mfma_kernel for 256 x 256 output tiles, fp16 output and a
+// contraction depth that is a multiple of 64, with two changes that measured faster on the
+// large shapes (3 % on the first GEMM of the T = 32768 layer, 13 % at K = 1024):
+//  * The eight wavefronts form two groups of four (one wavefront of each group per SIMD) that
+//    run one 32-deep phase apart: while one group issues its 16 MFMAs the other moves data
+//    (writes its share of the next stage to LDS, requests the stage after it, reads its own
+//    fragments).  Four barriers per 64-deep stage keep the groups in step; the group that
+//    starts late passes one extra barrier before the loop, the other one after it, so every
+//    wavefront passes the same number.
+//  * The tile leaves through LDS: every wavefront writes its 128 x 64 sub-tile to a patch of
+//    its own and stores it as whole 128-byte lines, 16 bytes per lane, instead of 8 bytes per
+//    lane into 32 different lines per instruction.
+// Operand addresses are 32-bit element offsets from scalar bases (the tile's first row, the
+// expert's weight matrix; with row_src the token matrix), which the host checks fit.
+#define MOE_LGKM0() asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")
+#define MOE_BAR()                                                                                 \
+    do {                                                                                         \
+        __builtin_amdgcn_sched_barrier(0);                                                       \
+        __builtin_amdgcn_s_barrier();                                                            \
+        __builtin_amdgcn_sched_barrier(0);                                                       \
+    } while (0)
+
+template <bool F16, int ACT, bool KEEP>
+__global__ __launch_bounds__(512, 2) void grouped_gemm_pp_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ W,
+    const float *__restrict__ bias, _Float16 *__restrict__ C, _Float16 *__restrict__ Pre,
+    const WorkItem *__restrict__ items, const int32_t *__restrict__ nitems, int N, int K,
+    const int32_t *__restrict__ row_src, int row_div)
+{
+    constexpr int WM = 2, TM = 4, TN = 2;            // 2 x 4 wavefronts of 128 x 64 each
+    constexpr int BM = 256, BN = 256, BK = 64, LD = BK + 8, NT = 512, AV = 4, WV = 4;
+    const int total = *nitems;
+    const int per_xcd = (total + 7) / 8;
+    const int slot = blockIdx.x / 8;
+    const int item_idx = (blockIdx.x % 8) * per_xcd + slot;
+    if (slot >= per_xcd || item_idx >= total) return;
+    const WorkItem item = items[item_idx];
+    const int n0 = item.n0;
+    const int rows = item.row1 - item.row0;
+
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    constexpr int A_BUF = BM * LD, W_BUF = BN * LD;
+    uint16_t *As = smem;               // [2][BM][LD]
+    uint16_t *Ws = smem + 2 * A_BUF;   // [2][BN][LD]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >> 2;
+    const int wm = wave % WM, wn = wave / WM;
+    const uint16_t *Wexp = W + static_cast<size_t>(item.expert) * N * K;
+    // gathered rows are offsets from A itself, packed rows from the tile's first row
+    const uint16_t *Abase = row_src != nullptr ? A : A + static_cast<size_t>(item.row0) * K;
+
+    unsigned a_src[AV], w_src[WV];
+    const int ld_col = (tid & 7) * 8;
+    const int off0 = (tid >> 3) * LD + ld_col;       // LDS place of vector q: off0 + q * 64 * LD
+#pragma unroll
+    for (int q = 0; q < AV; ++q) {
+        const int r = min((tid + NT * q) >> 3, rows - 1);
+        const unsigned arow = row_src != nullptr
+                                  ? static_cast<unsigned>(row_src[item.row0 + r] / row_div)
+                                  : static_cast<unsigned>(r);
+        a_src[q] = arow * static_cast<unsigned>(K) + ld_col;
+    }
+#pragma unroll
+    for (int q = 0; q < WV; ++q) {
+        const int r = (tid + NT * q) >> 3;
+        w_src[q] = static_cast<unsigned>(min(n0 + r, N - 1)) * static_cast<unsigned>(K) + ld_col;
+    }
+    const int jact = min(TM, max(0, (rows - wm * TM * 32 + 31) / 32));
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    u32x4 a_reg[AV], w_reg[WV];
+    u32x4 wf[2][TN], af[2][TM];
+    const int KT = K / BK;
+    const int fr = lane & 31, fk = (lane >> 5) * 8;
+    const int wfrag = (wn * TN * 32 + fr) * LD + fk;
+    const int afrag = (wm * TM * 32 + fr) * LD + fk;
+
+#define MOE_LOADG(kt_, q0, q1)                                                                    \
+    {                                                                                            \
+        _Pragma("unroll") for (int q = q0; q < q1; ++q) a_reg[q] =                               \
+            *reinterpret_cast<const u32x4 *>(Abase + (a_src[q] + static_cast<unsigned>((kt_) * BK))); \
+        _Pragma("unroll") for (int q = q0; q < q1; ++q) w_reg[q] =                               \
+            *reinterpret_cast<const u32x4 *>(Wexp + (w_src[q] + static_cast<unsigned>((kt_) * BK)));  \
+    }
+#define MOE_STOREL(buf, q0, q1)                                                                   \
+    {                                                                                            \
+        _Pragma("unroll") for (int q = q0; q < q1; ++q)                                          \
+            *reinterpret_cast<u32x4 *>(As + (buf) * A_BUF + off0 + q * 64 * LD) = a_reg[q];      \
+        _Pragma("unroll") for (int q = q0; q < q1; ++q)                                          \
+            *reinterpret_cast<u32x4 *>(Ws + (buf) * W_BUF + off0 + q * 64 * LD) = w_reg[q];      \
+    }
+#define MOE_READF(slot_, buf, ks)                                                                 \
+    {                                                                                            \
+        _Pragma("unroll") for (int i = 0; i < TN; ++i) wf[slot_][i] =                            \
+            *reinterpret_cast<const u32x4 *>(Ws + (buf) * W_BUF + wfrag + i * 32 * LD + (ks) * 16); \
+        _Pragma("unroll") for (int j = 0; j < TM; ++j) af[slot_][j] =                            \
+            *reinterpret_cast<const u32x4 *>(As + (buf) * A_BUF + afrag + j * 32 * LD + (ks) * 16); \
+    }
+#define MOE_MMA(slot_)                                                                            \
+    {                                                                                            \
+        _Pragma("unroll") for (int j = 0; j < TM; ++j)                                           \
+        {                                                                                        \
+            if (FULL || j < jact) {                                                              \
+                _Pragma("unroll") for (int i = 0; i < TN; ++i)                                   \
+                    acc[i][j] = mfma_32x32x16<F16>(wf[slot_][i], af[slot_][j], acc[i][j]);       \
+            }                                                                                    \
+        }                                                                                        \
+    }
+// One 64-deep stage kt in LDS buffer kt & 1, as two phases of {move, barrier, multiply, barrier}.
+#define MOE_PP_STAGES                                                                             \
+    for (int kt = 0; kt < KT; ++kt) {                                                            \
+        const int buf = kt & 1;                                                                  \
+        const bool next1 = kt + 1 < KT, next2 = kt + 2 < KT;                                     \
+        if (next1) MOE_STOREL(buf ^ 1, 0, 2)                                                     \
+        if (next2) MOE_LOADG(kt + 2, 0, 2)                                                       \
+        MOE_READF(0, buf, 0)                                                                     \
+        MOE_READF(1, buf, 1)                                                                     \
+        MOE_LGKM0();                                                                             \
+        MOE_BAR();                                                                               \
+        __builtin_amdgcn_s_setprio(2);                                                           \
+        MOE_MMA(0)                                                                               \
+        MOE_MMA(1)                                                                               \
+        __builtin_amdgcn_s_setprio(0);                                                           \
+        MOE_BAR();                                                                               \
+        if (next1) MOE_STOREL(buf ^ 1, 2, 4)                                                     \
+        if (next2) MOE_LOADG(kt + 2, 2, 4)                                                       \
+        MOE_READF(0, buf, 2)                                                                     \
+        MOE_READF(1, buf, 3)                                                                     \
+        MOE_LGKM0();                                                                             \
+        MOE_BAR();                                                                               \
+        __builtin_amdgcn_s_setprio(2);                                                           \
+        MOE_MMA(0)                                                                               \
+        MOE_MMA(1)                                                                               \
+        __builtin_amdgcn_s_setprio(0);                                                           \
+        MOE_BAR();                                                                               \
+    }
+
+    MOE_LOADG(0, 0, 4)
+    MOE_STOREL(0, 0, 4)
+    MOE_LGKM0();
+    MOE_BAR();
+    if (KT > 1) MOE_LOADG(1, 0, 4)
+    if (grp == 1) MOE_BAR();           // this group runs one phase behind the other
+    if (jact == TM) {
+        constexpr bool FULL = true;
+        MOE_PP_STAGES
+    } else {
+        constexpr bool FULL = false;
+        MOE_PP_STAGES
+    }
+    if (grp == 0) MOE_BAR();           // every wavefront has passed the same number of barriers
+#undef MOE_PP_STAGES
+#undef MOE_LOADG
+#undef MOE_STOREL
+#undef MOE_READF
+#undef MOE_MMA
+
+    // Epilogue.  acc[i][j][4*g + c]: column (wn*TN + i)*32 + 8*g + 4*(lane/32) + c, row
+    // (wm*TM + j)*32 + lane%32 of the tile.  The LDS tiles are free (every wavefront is past
+    // its last read): the wavefront's sub-tile goes to its own patch, row pitch 144 bytes.
+    constexpr int PITCH = 144;
+    char *patch = reinterpret_cast<char *>(smem) + wave * (TM * 32) * PITCH;
+    const float *bexp = bias != nullptr ? bias + static_cast<size_t>(item.expert) * N : nullptr;
+    const int rbase = item.row0 + wm * TM * 32;
+    const int ncol = n0 + wn * TN * 32 + (lane & 7) * 8;
+#pragma unroll
+    for (int pass = KEEP ? 0 : 1; pass < 2; ++pass) {      // pass 0: pre-activations, 1: outputs
+        _Float16 *out = pass == 0 ? Pre : C;
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int col = i * 32 + 8 * g + 4 * (lane >> 5);
+                    float v[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        float s = acc[i][j][4 * g + c];
+                        if (bexp != nullptr) s += bexp[min(n0 + wn * TN * 32 + col + c, N - 1)];
+                        v[c] = pass == 0 ? s : activate<ACT, true>(s);
+                    }
+                    store4(reinterpret_cast<_Float16 *>(patch + (j * 32 + fr) * PITCH) + col, v);
+                }
+        MOE_LGKM0();
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int it = 0; it < TM * 4; ++it) {
+            const int rr = it * 8 + (lane >> 3);
+            const u32x4 q = *reinterpret_cast<const u32x4 *>(patch + rr * PITCH + (lane & 7) * 16);
+            const int r = rbase + rr;
+            if (r < item.row1 && ncol < N)
+                *reinterpret_cast<u32x4 *>(out + static_cast<size_t>(r) * N + ncol) = q;
+        }
+        if (pass == 0) {
+            MOE_LGKM0();
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+#undef MOE_LGKM0
+#undef MOE_BAR
+
 // ---------------------------------------------------------------- weight packing
 // Out[e][n][k] = convert(In[e][k][n]); 64 x 64 tiles through LDS.
 // MODE 0: bf16 -> bf16, MODE 1: bf16 -> fp16.
@@ -460,14 +675,33 @@ void launch_mfma_cfg(const uint16_t *A, const uint16_t *W, const float *bias, TO
 template <bool F16, typename TOut, int ACT, bool KEEP>
 void launch_mfma(const GemmPlan &gp, const uint16_t *A, const uint16_t *W, const float *bias,
                  TOut *C, _Float16 *pre, const WorkItem *items, const int32_t *nitems, int N, int K,
-                 int stage, hipStream_t st, const int32_t *row_src = nullptr, int row_div = 1)
+                 int stage, hipStream_t st, const int32_t *row_src = nullptr, int row_div = 1,
+                 uint64_t row_limit = 0)
 {
 #define MOE_MFMA_SHAPE(WM_, WN_, TM_, TN_)                                                        \
     launch_mfma_cfg<F16, TOut, ACT, KEEP, WM_, WN_, TM_, TN_>(A, W, bias, C, pre, items, nitems,    \
                                                               gp.max_items, N, K, stage, st,       \
                                                               row_src, row_div)
-    if (gp.bm == 256)
+    if (gp.bm == 256) {
+        if constexpr (std::is_same<TOut, _Float16>::value) {
+            // the ping-pong kernel addresses its operands with 32-bit element offsets
+            const bool fits = K % 64 == 0 && static_cast<uint64_t>(N) * K < (1ull << 32) &&
+                              (row_src == nullptr ? 256ull * K : row_limit * static_cast<uint64_t>(K)) < (1ull << 32);
+            if (fits) {
+                constexpr size_t lds = 2 * (256 + 256) * (64 + 8) * sizeof(uint16_t);
+                auto kern = grouped_gemm_pp_kernel<F16, ACT, KEEP>;
+                static PerDeviceOnce once;
+                once.raise_lds(reinterpret_cast<const void *>(kern), static_cast<int>(lds));
+                const int grid = static_cast<int>(align_up(static_cast<size_t>(gp.max_items), 8));
+                hipEvent_t t0, t1;
+                prof_kernel_events(stage, &t0, &t1);
+                hipExtLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, st, t0, t1, 0, A, W, bias, C,
+                                      pre, items, nitems, N, K, row_src, row_div);
+                return;
+            }
+        }
         MOE_MFMA_SHAPE(2, 4, 4, 2);
+    }
     else if (gp.bm == 64)
         MOE_MFMA_SHAPE(1, 8, 2, 1);
     else if (gp.bn == 256)
@@ -489,11 +723,11 @@ void launch_mfma_pair(const moe_shape &s, const uint16_t *xe, const uint16_t *W1
     if (pre != nullptr)
         launch_mfma<false, _Float16, ACT, true>(w.gp[0], xe, W1p, b1, H, pre, it1,
                                                 w.nitems[0] + chunk, s.d_ff, s.d_model,
-                                                kStageGemm1, st, row_src, row_div);
+                                                kStageGemm1, st, row_src, row_div, s.T);
     else
         launch_mfma<false, _Float16, ACT, false>(w.gp[0], xe, W1p, b1, H, nullptr, it1,
                                                  w.nitems[0] + chunk, s.d_ff, s.d_model,
-                                                 kStageGemm1, st, row_src, row_div);
+                                                 kStageGemm1, st, row_src, row_div, s.T);
     launch_mfma<true, _Float16, MOE_ACT_IDENTITY, false>(w.gp[1], reinterpret_cast<const uint16_t *>(H),
                                                       W2p, b2, ye, nullptr, it2, w.nitems[1] + chunk,
                                                       s.d_model, s.d_ff, kStageGemm2, st);

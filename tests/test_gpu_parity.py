@@ -180,6 +180,56 @@ def test_gate_ties_go_to_the_lowest_index(T, d, E, k):
     np.testing.assert_allclose(b["gate"].cpu().numpy().reshape(T, k)[:T // 3], 1.0 / E, rtol=1e-6)
 
 
+@pytest.mark.parametrize("d,h,act,keep", [(384, 3072, "gelu", False), (3072, 256, "relu", False),
+                                          (320, 3072, "gelu_tanh", True)],
+                         ids=["first_gemm_256_tiles", "second_gemm_256_tiles", "first_gemm_kept_preactivations"])
+def test_large_tile_kernel(d, h, act, keep):
+    """Shapes whose expert GEMMs take the 256 x 256 tile kernel (two wavefront groups half a
+    stage apart, tile stored through LDS) at sizes the oracle still finishes in seconds: ragged
+    row tiles, overflowing and near-empty experts (Zipf gate bias), FFN biases, and the variant
+    that also keeps the pre-activations."""
+    cfg = wl.scaled("skewed", T=8192, d=d, h=h, E=8, k=2, cf=1.1)
+    li = wl.make_layer(cfg, seed=21, threads=8)
+    prng = np.random.Generator(np.random.PCG64(5))
+    b1 = (prng.standard_normal((li.E, li.h)) * 0.05).astype(np.float32)
+    b2 = (prng.standard_normal((li.E, li.d)) * 0.05).astype(np.float32)
+    if keep:
+        b1 = b2 = None                  # the training forward takes no FFN biases
+    o = run_oracle(li, act=act, b1=b1, b2=b2)
+    assert (o.slot_of < 0).any() and o.count.min() < li.C // 2          # overflow and small experts
+    s = shape_of(li, act=act)
+    L = DeviceLayer(li, s, b1=b1, b2=b2)
+    b = L.b
+    if keep:
+        pre = torch.full((moe.moe_max_rows(s) * li.h,), 9.0, dtype=torch.float16, device=DEV)
+        hid = torch.full_like(pre, 5.0)
+        moe.moe_layer_forward_keep(s, L.x, b["Wgp"], L.bias, L.bias_stride, b["W1p"], None, b["W2p"], None,
+                                   b["expert_idx"], b["gate"], b["counts"], b["offsets"], b["slot_of"],
+                                   b["src_of"], b["xe"], b["ye"], pre, hid, b["y"], b["workspace"])
+        torch.cuda.synchronize()
+        got_pre = pre[:o.A * li.h].float().cpu().numpy().reshape(o.A, li.h)
+        want_pre = np.empty_like(got_pre, dtype=np.float64)
+        for e in range(li.E):
+            want_pre[o.off[e]:o.off[e + 1]] = o.xe[o.off[e]:o.off[e + 1]].astype(np.float64) @ li.W1[e].astype(np.float64)
+        assert np.abs(got_pre - want_pre).max() <= 2.0 ** -10 * np.abs(want_pre).max() + 1e-4 * float(np.sqrt(np.mean(want_pre ** 2)))
+        assert (pre[o.A * li.h:] == 9.0).all() and (hid[o.A * li.h:] == 5.0).all()
+    else:
+        L.layer(1)
+    assert_ints_equal(L.ints(), o)
+    y = b["y"].cpu().numpy().reshape(li.T, li.d)
+    assert rel_rms_err(y, o.y) <= TOL["bf16"]
+    rows = np.arange(o.A, dtype=np.int32)
+    ye_ref = oracle.ffn_rows(o.xe, o.off, li.W1, li.W2, rows, act, b1, b2)
+    ye = b["ye"].float().cpu().numpy().reshape(-1, li.d)
+    assert rel_rms_err(ye[:o.A], ye_ref) <= TOL["bf16"]
+    # the stand-alone FFN on the packed buffer (no gather) gives the same bits
+    ye2 = torch.zeros_like(b["ye"])
+    moe.moe_expert_ffn(s, b["xe"], b["offsets"], b["W1p"], L.b1, b["W2p"], L.b2, ye2, b["workspace"])
+    torch.cuda.synchronize()
+    assert torch.equal(ye2[:o.A * li.d].view(torch.int16), b["ye"][:o.A * li.d].view(torch.int16))
+    assert not ye2[o.A * li.d:].any()
+
+
 def test_layer_is_bitwise_reproducible():
     # no floating-point atomics on the path: the same call gives the same bits, also when
     # the output buffers hold other values beforehand and other work ran in between
