@@ -92,6 +92,10 @@ def main() -> int:
                          "(HBM GB/s, read + write; under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE its "
                          "reading fixes the counters' unit) and its register-resident MFMA loop with "
                          "constant and with random operands (TFLOP/s)")
+    ap.add_argument("--gemm-ablation", action="store_true",
+                    help="time the 256 x 256 expert-GEMM kernel alone on the large layer's two GEMM shapes "
+                         "(64 experts of 1024 rows), whole and with parts left out (moe_calib_gemm), on random "
+                         "and on all-ones operands, and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -99,6 +103,8 @@ def main() -> int:
         return 2
     if args.calibrate:
         return calibrate()
+    if args.gemm_ablation:
+        return gemm_ablation()
     import numpy as np
     import torch
 
@@ -549,6 +555,76 @@ def calibrate() -> int:
         out["vendor_dense_gemm"][f"{m}x{n}x{k}"] = {"ms": t, "tflops": 2.0 * m * n * k / (t * 1e-3) / 1e12,
                                                       "frac_of_nominal": 2.0 * m * n * k / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
         del a, b
+    print(json.dumps(out))
+    return 0
+
+
+def gemm_ablation() -> int:
+    """What each part of the 256 x 256 expert-GEMM kernel costs: the kernel the layer runs,
+    alone, with parts left out (their outputs are wrong by construction; only variant 0's is
+    checked, on sampled elements against an fp64 dot product)."""
+    import numpy as np
+    import torch
+
+    import paper_2210_17223_amd as moe
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    E, rows_e, BM = 64, 1024, 256
+    variants = [(0, "whole kernel"), (16, "whole, both wavefront groups in phase"), (8, "no output stores"),
+                (6, "MFMAs + barriers only (one stage of operands)"), (4, "MFMAs + LDS fragment reads"),
+                (2, "MFMAs + global loads + LDS writes"), (1, "everything but the MFMAs"),
+                (7, "barriers, prologue and epilogue only")]
+    out = {"gemm_ablation": True, "shape": f"{E} experts x {rows_e} rows, 256 x 256 tiles", "problems": {}}
+    for tag, N, K, gelu in (("first GEMM  (N=8192, K=2048, GeLU)", 8192, 2048, True),
+                            ("second GEMM (N=2048, K=8192)", 2048, 8192, False)):
+        rows = E * rows_e
+        mt, nt = rows_e // BM, N // 256
+        gn = max(1, 32 // mt)
+        items = []
+        for e in range(E):
+            for pn in range(0, nt, gn):
+                for m in range(mt):
+                    for n in range(pn, min(nt, pn + gn)):
+                        items.append((e, e * rows_e + m * BM, e * rows_e + (m + 1) * BM, n * 256))
+        items_d = torch.tensor(items, dtype=torch.int32, device=dev).reshape(-1)
+        n_items = torch.tensor([len(items)], dtype=torch.int32, device=dev)
+        flops = 2.0 * rows * N * K
+        res = {}
+        for data in ("random", "ones"):
+            if data == "random":
+                g = torch.Generator(device=dev).manual_seed(1)
+                A = torch.randn(rows, K, device=dev, dtype=torch.float32, generator=g).to(torch.bfloat16)
+                W = (torch.randn(E * N, K, device=dev, dtype=torch.float32, generator=g) * 0.02).to(torch.bfloat16)
+            else:
+                A = torch.ones(rows, K, device=dev, dtype=torch.bfloat16)
+                W = torch.full((E * N, K), 0.0078125, device=dev, dtype=torch.bfloat16)
+            Cout = torch.zeros(rows, N, device=dev, dtype=torch.float16)
+            for var, name in (variants if data == "random" else variants[:1]):
+                for _ in range(2):
+                    moe.moe_calib_gemm(A, W, Cout, items_d, n_items, N, K, var, gelu)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(5):
+                    moe.moe_calib_gemm(A, W, Cout, items_d, n_items, N, K, var, gelu)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) / 5 * 1e3
+                res[f"{name} [{data} operands]"] = {"variant": var, "us": us, "tflops_if_whole": flops / (us * 1e-6) / 1e12}
+                if var == 0 and data == "random":
+                    prng = np.random.Generator(np.random.PCG64(3))
+                    rr, cc = prng.integers(0, rows, 256), prng.integers(0, N, 256)
+                    a = A[torch.from_numpy(rr).to(dev)].double().cpu().numpy()
+                    w = W.view(E, N, K)[torch.from_numpy(rr // rows_e).to(dev), torch.from_numpy(cc).to(dev)].double().cpu().numpy()
+                    want = (a * w).sum(1)
+                    if gelu:
+                        import math
+                        want = np.array([0.5 * v * (1.0 + math.erf(v / math.sqrt(2.0))) for v in want])
+                    got = Cout[torch.from_numpy(rr).to(dev), torch.from_numpy(cc).to(dev)].double().cpu().numpy()
+                    err = float(np.abs(got - want).max() / (np.abs(want).max() + 1e-30))
+                    assert err < 5e-3, err
+                    res["check_max_err_rel_to_max"] = err
+            del A, W, Cout
+        out["problems"][tag] = res
     print(json.dumps(out))
     return 0
 

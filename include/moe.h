@@ -254,8 +254,20 @@ int32_t moe_profile_read(int32_t stage, float *ms, int32_t cap);
  *   issuing iters x 8 independent 32x32x16 bf16 matrix instructions on register
  *   operands (random_operands != 0: operand bits differ per lane; 0: all ones, which
  *   draws less power and holds a higher clock).  sink: fp32 [256*waves_per_simd*256].
- *   moe_calib_mfma_flops gives the launch's floating-point operations. */
+ *   moe_calib_mfma_flops gives the launch's floating-point operations.
+ * moe_calib_gemm: the 256 x 256 expert-GEMM kernel alone, on operands and a work list
+ *   the caller makes: A bf16 [rows, K], W bf16 [E, N, K], C fp16 [rows, N] (written),
+ *   items int32 [max_items][4] = {expert, row0, row1, first column} with row1 - row0 in
+ *   1..256 and the first column a multiple of 256, *n_items <= max_items (device).
+ *   variant 0 is the kernel as the layer runs it; other variants leave parts of it out to
+ *   show what each costs (bit 0: no matrix instructions; bit 1: no LDS fragment reads
+ *   after the first stage; bit 2: no global loads and LDS writes in the loop; bit 3: no
+ *   output stores; bit 4: no phase offset between the two wavefront groups; built: 0, 1,
+ *   2, 4, 6, 7, 8, 16) -- their outputs are wrong by construction.  K a multiple of 64. */
 moe_status moe_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
+moe_status moe_calib_gemm(const void *A, const void *W, void *C, const int32_t *items,
+                          const int32_t *n_items, int32_t max_items, int32_t N, int32_t K,
+                          int32_t variant, int32_t gelu, void *stream);
 moe_status moe_calib_mfma(float *sink, int32_t waves_per_simd, int32_t iters,
                           int32_t random_operands, void *stream);
 double moe_calib_mfma_flops(int32_t waves_per_simd, int32_t iters);

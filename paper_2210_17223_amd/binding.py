@@ -86,6 +86,8 @@ def lib() -> C.CDLL:
         L.moe_layer_chunked.argtypes = [sp, i32, vp, vp, vp, i32] + [vp] * 16
         L.moe_calib_copy.argtypes = [vp, vp, sz, vp]
         L.moe_calib_copy.restype = C.c_int
+        L.moe_calib_gemm.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
+        L.moe_calib_gemm.restype = C.c_int
         L.moe_calib_mfma.argtypes = [vp, i32, i32, i32, vp]
         L.moe_calib_mfma.restype = C.c_int
         L.moe_calib_mfma_flops.argtypes = [i32, i32]
@@ -192,6 +194,11 @@ def moe_dispatch(s: Shape, x, expert_idx, counts, offsets, slot_of, src_of, xe, 
 
 def moe_calib_copy(dst, src, nbytes: int, stream=None) -> None:
     _check(lib().moe_calib_copy(_ptr(dst), _ptr(src), int(nbytes), _stream(stream)))
+
+
+def moe_calib_gemm(A, W, Cout, items, n_items, N: int, K: int, variant: int, gelu: bool, stream=None) -> None:
+    _check(lib().moe_calib_gemm(_ptr(A), _ptr(W), _ptr(Cout), _ptr(items), _ptr(n_items), items.numel() // 4,
+                                N, K, variant, int(gelu), _stream(stream)))
 
 
 def moe_calib_mfma(sink, waves_per_simd: int, iters: int, random_operands: bool, stream=None) -> float:

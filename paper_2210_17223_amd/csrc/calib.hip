@@ -64,6 +64,10 @@ __global__ __launch_bounds__(256) void calib_mfma_kernel(float *__restrict__ sin
 }
 
 }  // namespace
+
+moe_status launch_calib_gemm(const uint16_t *A, const uint16_t *W, _Float16 *C, const WorkItem *items,
+                             const int32_t *nitems, int max_items, int N, int K, int abl, int gelu,
+                             hipStream_t st);
 }  // namespace moe
 
 using namespace moe;
@@ -106,6 +110,21 @@ moe_status moe_calib_mfma(float *sink, int32_t waves_per_simd, int32_t iters, in
         hipLaunchKernelGGL(calib_mfma_kernel<false>, grid, block, 0, st, sink, iters);
     MOE_TRY_HIP(hipGetLastError());
     return MOE_OK;
+}
+
+moe_status moe_calib_gemm(const void *A, const void *W, void *C, const int32_t *items,
+                          const int32_t *n_items, int32_t max_items, int32_t N, int32_t K,
+                          int32_t variant, int32_t gelu, void *stream)
+{
+    if (A == nullptr || W == nullptr || C == nullptr || items == nullptr || n_items == nullptr ||
+        max_items < 1 || N < 8 || K < 64 || K % 64 != 0 || N % 8 != 0 ||
+        static_cast<uint64_t>(N) * K >= (1ull << 32)) {
+        set_error("moe_calib_gemm: NULL pointer, or N not a multiple of 8, or K not a multiple of 64");
+        return MOE_EINVAL;
+    }
+    return launch_calib_gemm(static_cast<const uint16_t *>(A), static_cast<const uint16_t *>(W),
+                             static_cast<_Float16 *>(C), reinterpret_cast<const WorkItem *>(items),
+                             n_items, max_items, N, K, variant, gelu, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -401,7 +401,11 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void grouped_gemm_mfma_kernel(
         __builtin_amdgcn_sched_barrier(0);                                                       \
     } while (0)
 
-template <bool F16, int ACT, bool KEEP>
+// ABL (measurement only, 0 in the layer): bit 0 leaves out the MFMAs, bit 1 the LDS fragment
+// reads after the first stage, bit 2 the global loads and LDS writes inside the loop, bit 3 the
+// output stores, bit 4 the phase offset between the two groups.  Results are then wrong by
+// construction; every access stays inside the buffers.
+template <bool F16, int ACT, bool KEEP, int ABL = 0>
 __global__ __launch_bounds__(512, 2) void grouped_gemm_pp_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W,
     const float *__restrict__ bias, _Float16 *__restrict__ C, _Float16 *__restrict__ Pre,
@@ -500,27 +504,36 @@ __global__ __launch_bounds__(512, 2) void grouped_gemm_pp_kernel(
 #define MOE_PP_STAGES                                                                             \
     for (int kt = 0; kt < KT; ++kt) {                                                            \
         const int buf = kt & 1;                                                                  \
-        const bool next1 = kt + 1 < KT, next2 = kt + 2 < KT;                                     \
+        const bool next1 = !(ABL & 4) && kt + 1 < KT, next2 = !(ABL & 4) && kt + 2 < KT;         \
+        const bool reads = !(ABL & 2) || kt == 0;                                                \
         if (next1) MOE_STOREL(buf ^ 1, 0, 2)                                                     \
         if (next2) MOE_LOADG(kt + 2, 0, 2)                                                       \
-        MOE_READF(0, buf, 0)                                                                     \
-        MOE_READF(1, buf, 1)                                                                     \
+        if (reads) {                                                                             \
+            MOE_READF(0, buf, 0)                                                                 \
+            MOE_READF(1, buf, 1)                                                                 \
+        }                                                                                        \
         MOE_LGKM0();                                                                             \
         MOE_BAR();                                                                               \
         __builtin_amdgcn_s_setprio(2);                                                           \
-        MOE_MMA(0)                                                                               \
-        MOE_MMA(1)                                                                               \
+        if constexpr (!(ABL & 1)) {                                                              \
+            MOE_MMA(0)                                                                           \
+            MOE_MMA(1)                                                                           \
+        }                                                                                        \
         __builtin_amdgcn_s_setprio(0);                                                           \
         MOE_BAR();                                                                               \
         if (next1) MOE_STOREL(buf ^ 1, 2, 4)                                                     \
         if (next2) MOE_LOADG(kt + 2, 2, 4)                                                       \
-        MOE_READF(0, buf, 2)                                                                     \
-        MOE_READF(1, buf, 3)                                                                     \
+        if (reads) {                                                                             \
+            MOE_READF(0, buf, 2)                                                                 \
+            MOE_READF(1, buf, 3)                                                                 \
+        }                                                                                        \
         MOE_LGKM0();                                                                             \
         MOE_BAR();                                                                               \
         __builtin_amdgcn_s_setprio(2);                                                           \
-        MOE_MMA(0)                                                                               \
-        MOE_MMA(1)                                                                               \
+        if constexpr (!(ABL & 1)) {                                                              \
+            MOE_MMA(0)                                                                           \
+            MOE_MMA(1)                                                                           \
+        }                                                                                        \
         __builtin_amdgcn_s_setprio(0);                                                           \
         MOE_BAR();                                                                               \
     }
@@ -530,7 +543,7 @@ __global__ __launch_bounds__(512, 2) void grouped_gemm_pp_kernel(
     MOE_LGKM0();
     MOE_BAR();
     if (KT > 1) MOE_LOADG(1, 0, 4)
-    if (grp == 1) MOE_BAR();           // this group runs one phase behind the other
+    if (!(ABL & 16) && grp == 1) MOE_BAR();           // this group runs one phase behind the other
     if (jact == TM) {
         constexpr bool FULL = true;
         MOE_PP_STAGES
@@ -538,7 +551,7 @@ __global__ __launch_bounds__(512, 2) void grouped_gemm_pp_kernel(
         constexpr bool FULL = false;
         MOE_PP_STAGES
     }
-    if (grp == 0) MOE_BAR();           // every wavefront has passed the same number of barriers
+    if (!(ABL & 16) && grp == 0) MOE_BAR();           // every wavefront has passed the same number of barriers
 #undef MOE_PP_STAGES
 #undef MOE_LOADG
 #undef MOE_STOREL
@@ -579,7 +592,7 @@ __global__ __launch_bounds__(512, 2) void grouped_gemm_pp_kernel(
             const int rr = it * 8 + (lane >> 3);
             const u32x4 q = *reinterpret_cast<const u32x4 *>(patch + rr * PITCH + (lane & 7) * 16);
             const int r = rbase + rr;
-            if (r < item.row1 && ncol < N)
+            if (r < item.row1 && ncol < N && (!(ABL & 8) || q[0] == 0x7fc07fc1u))
                 *reinterpret_cast<u32x4 *>(out + static_cast<size_t>(r) * N + ncol) = q;
         }
         if (pass == 0) {
@@ -734,6 +747,43 @@ void launch_mfma_pair(const moe_shape &s, const uint16_t *xe, const uint16_t *W1
 }
 
 }  // namespace
+
+// Measurement aid: the 256 x 256 kernel alone on caller-made operands and work list, with
+// parts of it left out (see ABL above).  gelu != 0 applies the activation.
+moe_status launch_calib_gemm(const uint16_t *A, const uint16_t *W, _Float16 *C, const WorkItem *items,
+                             const int32_t *nitems, int max_items, int N, int K, int abl, int gelu,
+                             hipStream_t st)
+{
+    constexpr size_t lds = 2 * (256 + 256) * (64 + 8) * sizeof(uint16_t);
+    const int grid = static_cast<int>(align_up(static_cast<size_t>(max_items), 8));
+#define MOE_CALIB_CASE(ABL_)                                                                      \
+    case ABL_: {                                                                                  \
+        auto k1 = grouped_gemm_pp_kernel<false, MOE_ACT_GELU_ERF, false, ABL_>;                   \
+        auto k0 = grouped_gemm_pp_kernel<false, MOE_ACT_IDENTITY, false, ABL_>;                   \
+        static PerDeviceOnce once1, once0;                                                        \
+        once1.raise_lds(reinterpret_cast<const void *>(k1), static_cast<int>(lds));               \
+        once0.raise_lds(reinterpret_cast<const void *>(k0), static_cast<int>(lds));               \
+        hipLaunchKernelGGL(gelu ? k1 : k0, dim3(grid), dim3(512), lds, st, A, W, nullptr, C,      \
+                           nullptr, items, nitems, N, K, nullptr, 1);                             \
+        break;                                                                                    \
+    }
+    switch (abl) {
+        MOE_CALIB_CASE(0)
+        MOE_CALIB_CASE(1)
+        MOE_CALIB_CASE(2)
+        MOE_CALIB_CASE(4)
+        MOE_CALIB_CASE(6)
+        MOE_CALIB_CASE(7)
+        MOE_CALIB_CASE(8)
+        MOE_CALIB_CASE(16)
+    default:
+        set_error("moe_calib_gemm: variant %d is not built (0, 1, 2, 4, 6, 7, 8, 16)", abl);
+        return MOE_EINVAL;
+    }
+#undef MOE_CALIB_CASE
+    MOE_TRY_HIP(hipGetLastError());
+    return MOE_OK;
+}
 
 // Tile shape of expert GEMM `which` (0: xe.W1, 1: H.W2) for this layer shape.  Large
 // tiles cut the operand traffic per flop; they need enough output tiles to fill 256
