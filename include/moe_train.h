@@ -80,6 +80,27 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
                               float *dWg, float *dW1, float *dW2, float *dgate, void *workspace,
                               void *stream);
 
+/* moe_layer_backward with the token stream cut into n_chunks contiguous parts (1..64), the
+ * backward pass's counterpart of moe_layer_chunked (Sec. 2.2: the backward pass has two
+ * all-to-alls of its own; Sec. 4.2: they are cut into micro-ops along the token dimension).
+ * Gradient rows are dispatched to the expert-major order chunk by chunk on a side stream, the
+ * two input-gradient GEMMs run once per group of consecutive chunks (the same grouping rule as
+ * the forward's FFN launches, moe_tune_ffn_group_rows) as soon as the group's last chunk is
+ * there, and the rows that come back are folded into dx chunk by chunk on a second side
+ * stream while the caller's stream goes on with the next group and the weight gradients.
+ * Every gradient is the same bits for every n_chunks.  With one group the call runs as
+ * n_chunks = 1.  Side streams and events are created on the first chunked call on a device. */
+moe_status moe_layer_backward_chunked(const moe_shape *s, int32_t n_chunks, const void *x,
+                                      const void *Wgp, const float *gate_bias,
+                                      int32_t bias_token_stride, const void *W1, const void *W2,
+                                      const void *W1p, const int32_t *expert_idx,
+                                      const float *gate, const int32_t *offsets,
+                                      const int32_t *slot_of, const int32_t *src_of,
+                                      const void *xe, const void *ye, const void *pre,
+                                      const void *hid, const float *dy, float *dx, float *dWg,
+                                      float *dW1, float *dW2, float *dgate, void *workspace,
+                                      void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -90,11 +90,12 @@ __device__ __forceinline__ void store_bf16x4(uint16_t *p, const float (&v)[4])
 // One wavefront per token.
 __global__ __launch_bounds__(256) void combine_bwd_kernel(
     const float *__restrict__ dy, const _Float16 *__restrict__ ye, const int32_t *__restrict__ slot_of,
-    const float *__restrict__ gate, uint16_t *__restrict__ dye, float *__restrict__ dgate, int T,
-    int d, int k, int max_rows)
+    const float *__restrict__ gate, uint16_t *__restrict__ dye, float *__restrict__ dgate, int t0,
+    int T, int d, int k, int max_rows)
 {
+    // tokens [t0, T)
     const int lane = lane_id();
-    const int t = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    const int t = t0 + blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
     if (t >= T) return;
     const float *dyrow = dy + static_cast<size_t>(t) * d;
     for (int j = 0; j < k; ++j) {
@@ -539,8 +540,8 @@ __global__ __launch_bounds__(STAGED ? 1024 : 256) void gate_bwd_kernel(
     const uint16_t *__restrict__ x, const float *__restrict__ Wgp, const float *__restrict__ bias,
     int bias_stride, const int32_t *__restrict__ expert_idx, const int32_t *__restrict__ slot_of,
     const float *__restrict__ dgate, const float *__restrict__ dxe, float *__restrict__ dz,
-    float *__restrict__ dx, int T, int d, int dP, int E, int k, int max_rows)
-{
+    float *__restrict__ dx, int t0, int T, int d, int dP, int E, int k, int max_rows)
+{   // tokens [t0, T)
     constexpr int NW = STAGED ? 16 : 4;                              // wavefronts per block
     __shared__ float dzs[NW][kWave];
     extern __shared__ __attribute__((aligned(16))) float wlds[];     // STAGED: [EP][d]
@@ -559,7 +560,7 @@ __global__ __launch_bounds__(STAGED ? 1024 : 256) void gate_bwd_kernel(
         Wsrc = wlds;
         wpitch = d;
     }
-    const int t = blockIdx.x * NW + w;
+    const int t = t0 + blockIdx.x * NW + w;
     if (t >= T) return;
     const uint16_t *xrow = x + static_cast<size_t>(t) * d;
     float acc[EP];
@@ -734,9 +735,10 @@ void layout_bwd(const moe_shape &s, void *base, BwdWorkspace *w)
     w->lists = Workspace{};
     w->lists.gp[0] = plan128(s.d_ff, s.d_model, R, s.E);
     w->lists.gp[1] = plan128(s.d_model, s.d_ff, R, s.E);
-    for (int g = 0; g < 2; ++g) {
-        w->lists.items[g] = reinterpret_cast<WorkItem *>(take(sizeof(WorkItem) * w->lists.gp[g].max_items));
-        w->lists.nitems[g] = reinterpret_cast<int32_t *>(take(sizeof(int32_t)));
+    for (int g = 0; g < 2; ++g) {      // one list per FFN group of a chunked backward pass
+        w->lists.items[g] = reinterpret_cast<WorkItem *>(
+            take(sizeof(WorkItem) * w->lists.gp[g].max_items * kMaxChunks));
+        w->lists.nitems[g] = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * kMaxChunks));
     }
     const size_t Rh = static_cast<size_t>(R) * s.d_ff, Rd = static_cast<size_t>(R) * s.d_model;
     w->P = reinterpret_cast<_Float16 *>(take(Rh * 2));
@@ -807,68 +809,184 @@ void launch_wgrad(const uint16_t *A, const uint16_t *B, float *C, const int32_t 
                           tiles_m, tiles_n);
 }
 
+// Side streams and events of a chunked backward pass, per device, kept for the process.
+struct BwdResources {
+    bool ready = false;
+    std::mutex enqueue;                 // held while a call enqueues on the side streams
+    hipStream_t grad_in = nullptr, grad_out = nullptr;
+    hipEvent_t begun = nullptr, joined_in = nullptr, joined_out = nullptr;
+    hipEvent_t dispatched[kMaxChunks] = {}, computed[kMaxChunks] = {};
+};
+std::mutex g_bwd_mutex;
+BwdResources g_bwd[16];
+
+moe_status bwd_resources(BwdResources **out)
+{
+    int dev = 0;
+    MOE_TRY_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 16) {
+        set_error("device index %d out of range", dev);
+        return MOE_EUNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(g_bwd_mutex);
+    BwdResources &r = g_bwd[dev];
+    if (!r.ready) {
+        MOE_TRY_HIP(hipStreamCreateWithFlags(&r.grad_in, hipStreamNonBlocking));
+        MOE_TRY_HIP(hipStreamCreateWithFlags(&r.grad_out, hipStreamNonBlocking));
+        MOE_TRY_HIP(hipEventCreateWithFlags(&r.begun, hipEventDisableTiming));
+        MOE_TRY_HIP(hipEventCreateWithFlags(&r.joined_in, hipEventDisableTiming));
+        MOE_TRY_HIP(hipEventCreateWithFlags(&r.joined_out, hipEventDisableTiming));
+        for (int c = 0; c < kMaxChunks; ++c) {
+            MOE_TRY_HIP(hipEventCreateWithFlags(&r.dispatched[c], hipEventDisableTiming));
+            MOE_TRY_HIP(hipEventCreateWithFlags(&r.computed[c], hipEventDisableTiming));
+        }
+        r.ready = true;
+    }
+    *out = &r;
+    return MOE_OK;
+}
+
+// The backward pass, cut like the forward: tokens in n_chunks contiguous parts, the row-grouped
+// GEMMs once per group of consecutive chunks (ffn_groups).  Gradient rows are dispatched to the
+// expert-major order chunk by chunk on one side stream (the backward pass's first all-to-all
+// carries them, Sec. 2.2), the two input-gradient GEMMs of a group start when its last chunk is
+// there, and the rows that come back are folded into dx chunk by chunk on a second side stream
+// (the second all-to-all) while the caller's stream goes on with the next group and then with
+// the weight gradients.  Every result is the same bits for every n_chunks.
 template <int ACT>
-moe_status backward_t(const moe_shape &s, const uint16_t *x, const float *Wgp, const float *bias,
-                      int bias_stride, const uint16_t *W1, const uint16_t *W2, const uint16_t *W1p,
-                      const int32_t *expert_idx, const float *gate, const int32_t *offsets,
-                      const int32_t *slot_of, const int32_t *src_of, const uint16_t *xe,
-                      const _Float16 *ye, const _Float16 *pre, const _Float16 *hid, const float *dy,
-                      float *dx, float *dWg,
-                      float *dW1, float *dW2, float *dgate, const BwdWorkspace &w, hipStream_t st)
+moe_status backward_t(const moe_shape &s, int n_chunks, const uint16_t *x, const float *Wgp,
+                      const float *bias, int bias_stride, const uint16_t *W1, const uint16_t *W2,
+                      const uint16_t *W1p, const int32_t *expert_idx, const float *gate,
+                      const int32_t *offsets, const int32_t *slot_of, const int32_t *src_of,
+                      const uint16_t *xe, const _Float16 *ye, const _Float16 *pre,
+                      const _Float16 *hid, const float *dy, float *dx, float *dWg, float *dW1,
+                      float *dW2, float *dgate, const BwdWorkspace &w, hipStream_t st)
 {
     const int T = s.T, d = s.d_model, h = s.d_ff, E = s.E, k = s.k;
     const int R = static_cast<int>(moe_max_rows(&s));
-    // work lists of the row-grouped GEMMs (one chunk)
-    moe_status rc = launch_items(s, 1, 1, offsets, src_of, w.lists, st);
+    if (n_chunks > T) n_chunks = T;
+    const int n_groups = ffn_groups(s, n_chunks);
+    if (n_groups == 1) n_chunks = 1;
+    moe_status rc = launch_items(s, n_chunks, n_groups, offsets, src_of, w.lists, st);
     if (rc != MOE_OK) return rc;
-    hipLaunchKernelGGL(combine_bwd_kernel, dim3(ceil_div(T, 4)), dim3(256), 0, st, dy, ye, slot_of,
-                       gate, w.dye, dgate, T, d, k, R);
     const GemmPlan &g0 = w.lists.gp[0], &g1 = w.lists.gp[1];
-    // P = xe W1 (fp16), Hb = act(P) (bf16) -- unless the forward kept P and its hidden activations
     _Float16 *P = pre != nullptr ? const_cast<_Float16 *>(pre) : w.P;
-    if (pre == nullptr)
-        launch_gemm<1, ACT>(xe, W1p, w.Hb, w.P, w.lists.items[0], w.lists.nitems[0], h, d, g0.bn,
-                            g0.max_items, kStageBwdRecompute, st);
-    // dP = (dye W2^T) * act'(P): W2 [E][h][d] is already "rows n = h, contraction d contiguous"
-    launch_gemm<2, ACT>(w.dye, W2, w.dP, P, w.lists.items[0], w.lists.nitems[0], h, d, g0.bn,
-                        g0.max_items, kStageBwdDP, st);
-    // dxe = dP W1^T: W1 [E][d][h] is "rows n = d, contraction h contiguous"
-    launch_gemm<0, ACT>(w.dP, W1, w.dxe, nullptr, w.lists.items[1], w.lists.nitems[1], d, h, g1.bn,
-                        g1.max_items, kStageBwdDxe, st);
-    // dW2[e] [h][d] = act(P)^T dye ; dW1[e] [d][h] = xe^T dP, operands as they are
-    if (pre != nullptr)      // the forward's own hidden activations, fp16
-        launch_wgrad<true>(reinterpret_cast<const uint16_t *>(hid), w.dye, dW2, offsets, E, h, d,
-                           kStageBwdWgrad2, st);
-    else
-        launch_wgrad<false>(w.Hb, w.dye, dW2, offsets, E, h, d, kStageBwdWgrad2, st);
-    launch_wgrad<false>(xe, w.dP, dW1, offsets, E, d, h, kStageBwdWgrad1, st);
-    // gate: dz, dx, dWg
     int EP = 1;
     while (EP < E) EP <<= 1;
     const int dPad = (d + 127) / 128 * 128;            // the packed gate matrix's row length
+    auto bound = [&](int c) { return static_cast<int>(static_cast<int64_t>(c) * T / n_chunks); };
+
+    // dye = g dy (bf16) and dgate = <ye, dy> for the tokens [t0, t1)
+    auto grad_dispatch = [&](int t0, int t1, hipStream_t q) {
+        if (t1 > t0)
+            hipLaunchKernelGGL(combine_bwd_kernel, dim3(ceil_div(t1 - t0, 4)), dim3(256), 0, q, dy, ye,
+                               slot_of, gate, w.dye, dgate, t0, t1, d, k, R);
+    };
+    // the row-grouped GEMMs of FFN group f
+    auto group_gemms = [&](int f) {
+        const WorkItem *it0 = w.lists.items[0] + static_cast<size_t>(f) * g0.max_items;
+        const WorkItem *it1 = w.lists.items[1] + static_cast<size_t>(f) * g1.max_items;
+        // P = xe W1 (fp16), Hb = act(P) (bf16) -- unless the forward kept P and its hidden activations
+        if (pre == nullptr)
+            launch_gemm<1, ACT>(xe, W1p, w.Hb, w.P, it0, w.lists.nitems[0] + f, h, d, g0.bn, g0.max_items,
+                                kStageBwdRecompute, st);
+        // dP = (dye W2^T) * act'(P): W2 [E][h][d] is already "rows n = h, contraction d contiguous"
+        launch_gemm<2, ACT>(w.dye, W2, w.dP, P, it0, w.lists.nitems[0] + f, h, d, g0.bn, g0.max_items,
+                            kStageBwdDP, st);
+        // dxe = dP W1^T: W1 [E][d][h] is "rows n = d, contraction h contiguous"
+        launch_gemm<0, ACT>(w.dP, W1, w.dxe, nullptr, it1, w.lists.nitems[1] + f, d, h, g1.bn,
+                            g1.max_items, kStageBwdDxe, st);
+    };
+    // dW2[e] [h][d] = act(P)^T dye ; dW1[e] [d][h] = xe^T dP, operands as they are
+    auto weight_grads = [&]() {
+        if (pre != nullptr)      // the forward's own hidden activations, fp16
+            launch_wgrad<true>(reinterpret_cast<const uint16_t *>(hid), w.dye, dW2, offsets, E, h, d,
+                               kStageBwdWgrad2, st);
+        else
+            launch_wgrad<false>(w.Hb, w.dye, dW2, offsets, E, h, d, kStageBwdWgrad2, st);
+        launch_wgrad<false>(xe, w.dP, dW1, offsets, E, d, h, kStageBwdWgrad1, st);
+    };
+    // gate: dz and dx for the tokens [t0, t1)
+    auto grad_combine = [&](int t0, int t1, hipStream_t q) {
+        if (t1 <= t0) return;
+        const int n = t1 - t0;
 #define MOE_GATE_BWD_CASE(EP_)                                                                    \
     if (EP == EP_) {                                                                              \
         const size_t wbytes = static_cast<size_t>(EP_) * d * sizeof(float);                       \
         if (wbytes <= 64 * 1024 && T >= 16 * 256) {                                               \
             auto kern = gate_bwd_kernel<EP_, true>;                                               \
             static PerDeviceOnce once;                                                            \
-            once.raise_lds(reinterpret_cast<const void *>(kern), 64 * 1024);                              \
-            hipLaunchKernelGGL(kern, dim3(ceil_div(T, 16)), dim3(1024), wbytes,                   \
-                               st, x, Wgp, bias, bias_stride, expert_idx, slot_of, dgate, w.dxe,  \
-                               w.dz, dx, T, d, dPad, E, k, R);                                    \
+            once.raise_lds(reinterpret_cast<const void *>(kern), 64 * 1024);                      \
+            hipLaunchKernelGGL(kern, dim3(ceil_div(n, 16)), dim3(1024), wbytes, q, x, Wgp, bias,  \
+                               bias_stride, expert_idx, slot_of, dgate, w.dxe, w.dz, dx, t0, t1,  \
+                               d, dPad, E, k, R);                                                 \
         } else {                                                                                  \
-            hipLaunchKernelGGL((gate_bwd_kernel<EP_, false>), dim3(ceil_div(T, 4)), dim3(256), 0, \
-                               st, x, Wgp, bias, bias_stride, expert_idx, slot_of, dgate, w.dxe,  \
-                               w.dz, dx, T, d, dPad, E, k, R);                                    \
+            hipLaunchKernelGGL((gate_bwd_kernel<EP_, false>), dim3(ceil_div(n, 4)), dim3(256), 0, \
+                               q, x, Wgp, bias, bias_stride, expert_idx, slot_of, dgate, w.dxe,   \
+                               w.dz, dx, t0, t1, d, dPad, E, k, R);                               \
         }                                                                                         \
-        hipLaunchKernelGGL(dwg_partial_kernel<EP_>, dim3(ceil_div(d, 64), w.splits), dim3(256), 0, \
-                           st, x, w.dz, w.partial, T, d, E, w.per_split);                         \
     }
-    MOE_GATE_BWD_CASE(1) MOE_GATE_BWD_CASE(2) MOE_GATE_BWD_CASE(4) MOE_GATE_BWD_CASE(8)
-    MOE_GATE_BWD_CASE(16) MOE_GATE_BWD_CASE(32) MOE_GATE_BWD_CASE(64)
+        MOE_GATE_BWD_CASE(1) MOE_GATE_BWD_CASE(2) MOE_GATE_BWD_CASE(4) MOE_GATE_BWD_CASE(8)
+        MOE_GATE_BWD_CASE(16) MOE_GATE_BWD_CASE(32) MOE_GATE_BWD_CASE(64)
 #undef MOE_GATE_BWD_CASE
-    hipLaunchKernelGGL(dwg_reduce_kernel, dim3(ceil_div(d * E, 256)), dim3(256), 0, st, w.partial, dWg,
-                       d * E, w.splits);
+    };
+    // dWg = x^T dz: partial sums over fixed token ranges, then a fixed-order sum
+    auto gate_weight_grad = [&]() {
+#define MOE_DWG_CASE(EP_)                                                                         \
+    if (EP == EP_)                                                                                \
+        hipLaunchKernelGGL(dwg_partial_kernel<EP_>, dim3(ceil_div(d, 64), w.splits), dim3(256), 0, \
+                           st, x, w.dz, w.partial, T, d, E, w.per_split);
+        MOE_DWG_CASE(1) MOE_DWG_CASE(2) MOE_DWG_CASE(4) MOE_DWG_CASE(8)
+        MOE_DWG_CASE(16) MOE_DWG_CASE(32) MOE_DWG_CASE(64)
+#undef MOE_DWG_CASE
+        hipLaunchKernelGGL(dwg_reduce_kernel, dim3(ceil_div(d * E, 256)), dim3(256), 0, st, w.partial,
+                           dWg, d * E, w.splits);
+    };
+
+    if (n_chunks == 1) {
+        grad_dispatch(0, T, st);
+        group_gemms(0);
+        weight_grads();
+        grad_combine(0, T, st);
+        gate_weight_grad();
+        MOE_TRY_HIP(hipGetLastError());
+        return MOE_OK;
+    }
+
+    BwdResources *r = nullptr;
+    rc = bwd_resources(&r);
+    if (rc != MOE_OK) return rc;
+    std::lock_guard<std::mutex> enqueue(r->enqueue);
+    MOE_TRY_HIP(hipEventRecord(r->begun, st));
+    MOE_TRY_HIP(hipStreamWaitEvent(r->grad_in, r->begun, 0));
+    MOE_TRY_HIP(hipStreamWaitEvent(r->grad_out, r->begun, 0));
+    auto enqueue_chunks = [&]() -> moe_status {
+        for (int c = 0; c < n_chunks; ++c) {
+            grad_dispatch(bound(c), bound(c + 1), r->grad_in);
+            MOE_TRY_HIP(hipEventRecord(r->dispatched[c], r->grad_in));
+        }
+        for (int f = 0; f < n_groups; ++f) {
+            const int c0 = static_cast<int>(static_cast<int64_t>(f) * n_chunks / n_groups);
+            const int c1 = static_cast<int>(static_cast<int64_t>(f + 1) * n_chunks / n_groups);
+            MOE_TRY_HIP(hipStreamWaitEvent(st, r->dispatched[c1 - 1], 0));
+            group_gemms(f);
+            MOE_TRY_HIP(hipEventRecord(r->computed[f], st));
+            MOE_TRY_HIP(hipStreamWaitEvent(r->grad_out, r->computed[f], 0));
+            for (int c = c0; c < c1; ++c) grad_combine(bound(c), bound(c + 1), r->grad_out);
+        }
+        weight_grads();
+        return MOE_OK;
+    };
+    rc = enqueue_chunks();
+    // join both side streams (also after a failure part-way), then the gate matrix's gradient,
+    // which needs every token's dz
+    hipError_t je = hipEventRecord(r->joined_in, r->grad_in);
+    if (je == hipSuccess) je = hipStreamWaitEvent(st, r->joined_in, 0);
+    if (je == hipSuccess) je = hipEventRecord(r->joined_out, r->grad_out);
+    if (je == hipSuccess) je = hipStreamWaitEvent(st, r->joined_out, 0);
+    if (rc != MOE_OK) return rc;
+    if (je != hipSuccess) return hip_fail(je, "joining the side streams");
+    gate_weight_grad();
     MOE_TRY_HIP(hipGetLastError());
     return MOE_OK;
 }
@@ -898,6 +1016,21 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
                               float *dWg, float *dW1, float *dW2, float *dgate, void *workspace,
                               void *stream)
 {
+    return moe_layer_backward_chunked(s, 1, x, Wgp, gate_bias, bias_token_stride, W1, W2, W1p,
+                                      expert_idx, gate, offsets, slot_of, src_of, xe, ye, pre, hid, dy,
+                                      dx, dWg, dW1, dW2, dgate, workspace, stream);
+}
+
+moe_status moe_layer_backward_chunked(const moe_shape *s, int32_t n_chunks, const void *x,
+                                      const void *Wgp, const float *gate_bias,
+                                      int32_t bias_token_stride, const void *W1, const void *W2,
+                                      const void *W1p, const int32_t *expert_idx, const float *gate,
+                                      const int32_t *offsets, const int32_t *slot_of,
+                                      const int32_t *src_of, const void *xe, const void *ye,
+                                      const void *pre, const void *hid, const float *dy, float *dx,
+                                      float *dWg, float *dW1, float *dW2, float *dgate,
+                                      void *workspace, void *stream)
+{
     if (!supported(s)) {
         set_error("moe_layer_backward: bf16 layers without top-k renormalisation only, E <= %d, "
                   "k <= %d, d_model and d_ff multiples of 8", kMaxExperts, kMaxTopK);
@@ -905,6 +1038,10 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
     }
     if (gate_bias != nullptr && bias_token_stride != 0 && bias_token_stride != s->E) {
         set_error("bias_token_stride must be 0 or E");
+        return MOE_EINVAL;
+    }
+    if (n_chunks < 1 || n_chunks > kMaxChunks) {
+        set_error("n_chunks must be in 1..%d, got %d", kMaxChunks, n_chunks);
         return MOE_EINVAL;
     }
     const void *need[] = {x, Wgp, W1, W2, W1p, expert_idx, gate, offsets, slot_of, src_of, xe, ye, dy,
@@ -931,7 +1068,7 @@ moe_status moe_layer_backward(const moe_shape *s, const void *x, const void *Wgp
     const uint16_t *W1pb = static_cast<const uint16_t *>(W1p), *xeb = static_cast<const uint16_t *>(xe);
 #define MOE_BWD_CASE(ACT)                                                                         \
     case ACT:                                                                                     \
-        return backward_t<ACT>(*s, xb, Wgf, gate_bias, bias_token_stride, W1b, W2b, W1pb,         \
+        return backward_t<ACT>(*s, n_chunks, xb, Wgf, gate_bias, bias_token_stride, W1b, W2b, W1pb, \
                                expert_idx, gate, offsets, slot_of, src_of, xeb,                   \
                                static_cast<const _Float16 *>(ye), preh, hidh,                     \
                                dy, dx, dWg, dW1, dW2, dgate, w, st);

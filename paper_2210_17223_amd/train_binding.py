@@ -20,6 +20,8 @@ def _lib():
         L.moe_backward_workspace_bytes.argtypes = [sp]
         L.moe_layer_backward.restype = C.c_int
         L.moe_layer_backward.argtypes = [sp, vp, vp, vp, i32] + [vp] * 20
+        L.moe_layer_backward_chunked.restype = C.c_int
+        L.moe_layer_backward_chunked.argtypes = [sp, i32, vp, vp, vp, i32] + [vp] * 20
         L.moe_layer_forward_keep.restype = C.c_int
         L.moe_layer_forward_keep.argtypes = [sp, vp, vp, vp, i32] + [vp] * 17
         _ready = True
@@ -62,7 +64,8 @@ def moe_layer_forward_keep(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1p, 
 
 def moe_layer_backward(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1, W2, W1p, expert_idx, gate,
                        offsets, slot_of, src_of, xe, ye, pre, hid, dy, dx, dWg, dW1, dW2, dgate, workspace,
-                       stream=None) -> None:
+                       stream=None, n_chunks: int = 1) -> None:
+    """n_chunks = 1: moe_layer_backward; otherwise moe_layer_backward_chunked."""
     rows = moe_max_rows(s)
     T, d, E, h, k = s.T, s.d_model, s.E, s.d_ff, s.k
     _need(x, torch.bfloat16, T * d, "x")
@@ -86,8 +89,11 @@ def moe_layer_backward(s: Shape, x, Wgp, gate_bias, bias_token_stride, W1, W2, W
     _need(dW2, torch.float32, E * d * h, "dW2")
     _need(dgate, torch.float32, T * k, "dgate")
     _need(workspace, torch.uint8, moe_backward_workspace_bytes(s), "workspace")
-    _check(_lib().moe_layer_backward(C.byref(s), _ptr(x), _ptr(Wgp), _ptr(gate_bias), bias_token_stride,
-                                     _ptr(W1), _ptr(W2), _ptr(W1p), _ptr(expert_idx), _ptr(gate),
-                                     _ptr(offsets), _ptr(slot_of), _ptr(src_of), _ptr(xe), _ptr(ye),
-                                     _ptr(pre), _ptr(hid), _ptr(dy), _ptr(dx), _ptr(dWg), _ptr(dW1), _ptr(dW2), _ptr(dgate),
-                                     _ptr(workspace), _stream(stream)))
+    tail = (_ptr(x), _ptr(Wgp), _ptr(gate_bias), bias_token_stride, _ptr(W1), _ptr(W2), _ptr(W1p),
+            _ptr(expert_idx), _ptr(gate), _ptr(offsets), _ptr(slot_of), _ptr(src_of), _ptr(xe), _ptr(ye),
+            _ptr(pre), _ptr(hid), _ptr(dy), _ptr(dx), _ptr(dWg), _ptr(dW1), _ptr(dW2), _ptr(dgate),
+            _ptr(workspace), _stream(stream))
+    if n_chunks == 1:
+        _check(_lib().moe_layer_backward(C.byref(s), *tail))
+    else:
+        _check(_lib().moe_layer_backward_chunked(C.byref(s), n_chunks, *tail))

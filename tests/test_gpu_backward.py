@@ -26,7 +26,7 @@ CASES = {
 }
 
 
-def run_backward(li, act="gelu", keep=False):
+def run_backward(li, act="gelu", keep=False, n_chunks=1, with_oracle=True):
     """keep: the forward is moe_layer_forward_keep and hands its pre-activations to the
     backward pass; else the plain layer call, and the backward pass computes them again."""
     s = shape_of(li, act=act)
@@ -72,8 +72,10 @@ def run_backward(li, act="gelu", keep=False):
     moe.moe_layer_backward(s, L.x, b["Wgp"], L.bias, L.bias_stride, W1, W2, b["W1p"], b["expert_idx"],
                            b["gate"], b["offsets"], b["slot_of"], b["src_of"], b["xe"], b["ye"], pre, hid,
                            torch.from_numpy(dy).to(DEV), g["dx"], g["dWg"], g["dW1"], g["dW2"],
-                           g["dgate"], ws)
+                           g["dgate"], ws, n_chunks=n_chunks)
     torch.cuda.synchronize()
+    if not with_oracle:
+        return {n: t.cpu().numpy() for n, t in g.items()}, None
     o = bo.moe_layer_backward(li.x, li.Wg, li.W1, li.W2, dy, k=li.k, capacity=li.C, act=act,
                               bias=li.gate_bias, bias_stride=li.bias_token_stride)
     assert np.array_equal(b["slot_of"].cpu().numpy(), o.fwd.slot_of)
@@ -127,6 +129,25 @@ def test_backward_is_bitwise_reproducible():
     b, _ = run_backward(li, keep=True)
     for name in a:
         assert np.array_equal(a[name].view(np.uint32), b[name].view(np.uint32)), name
+
+
+@pytest.mark.parametrize("keep", [False, True], ids=["recompute", "keep"])
+@pytest.mark.parametrize("name", ["skewed", "k3"])
+def test_chunked_backward_changes_no_bit(name, keep):
+    """moe_layer_backward_chunked: every gradient is the same bits for every n_chunks, with one
+    group of GEMMs per chunk (all side streams and events in use), with a few chunks per group,
+    and with the default grouping (one group at these sizes)."""
+    li = wl.make_layer(CASES[name], seed=2)
+    ref, _ = run_backward(li, keep=keep, with_oracle=False)
+    for group_rows, chunks in ((1, (2, 3, 8, 64)), (64, (4, 8)), (0, (4,))):
+        before = moe.moe_tune_ffn_group_rows(group_rows)
+        try:
+            for n_chunks in chunks:
+                got, _ = run_backward(li, keep=keep, n_chunks=n_chunks, with_oracle=False)
+                for n in ref:
+                    assert np.array_equal(got[n].view(np.uint32), ref[n].view(np.uint32)), (n, n_chunks, group_rows)
+        finally:
+            moe.moe_tune_ffn_group_rows(before)
 
 
 @pytest.mark.parametrize("act", ["relu", "gelu_tanh", "identity"])

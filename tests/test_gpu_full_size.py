@@ -181,3 +181,74 @@ def test_backward_at_the_bench_configuration():
     for e in range(E):
         assert rel_rms_err(dW1[e], o.dW1[e]) <= tol, e
         assert rel_rms_err(dW2[e], o.dW2[e]) <= tol, e
+
+
+@pytest.mark.parametrize("name,n_chunks", [("skewed", 4), ("large_chunked", 1)])
+def test_backward_at_full_size_sampled_experts(name, n_chunks):
+    """Forward (keeping its pre-activations) + backward of configurations 3 and 4 at full size
+    against the backward oracle: dx, dgate and dWg in full (every token), dW1 / dW2 for a sample
+    of experts -- the fullest, the emptiest, and four in between -- since the oracle holds each
+    expert's weight gradient in fp64.  Configuration 3 runs the chunked backward pass with two
+    groups of GEMMs per pass."""
+    from oracle import bwd_oracle as bo
+    li = wl.make_layer(wl.CONFIGS[name], seed=0, threads=16)
+    T, d, E, h, k = li.T, li.d, li.E, li.h, li.k
+    s = shape_of(li)
+    L = DeviceLayer(li, s)
+    b = L.b
+    dev = "cuda:0"
+    pre = torch.empty(moe.moe_max_rows(s) * h, dtype=torch.float16, device=dev)
+    hid = torch.empty_like(pre)
+    moe.moe_layer_forward_keep(s, L.x, b["Wgp"], L.bias, L.bias_stride, b["W1p"], None, b["W2p"], None,
+                               b["expert_idx"], b["gate"], b["counts"], b["offsets"], b["slot_of"],
+                               b["src_of"], b["xe"], b["ye"], pre, hid, b["y"], b["workspace"])
+    dy = np.random.Generator(np.random.PCG64(31)).standard_normal((T, d)).astype(np.float32)
+    W1, W2 = upload(li.W1, "bf16"), upload(li.W2, "bf16")
+    f32 = lambda n: torch.full((n,), 3.0, dtype=torch.float32, device=dev)
+    g = dict(dx=f32(T * d), dWg=f32(d * E), dW1=f32(E * d * h), dW2=f32(E * d * h), dgate=f32(T * k))
+    ws = torch.empty(moe.moe_backward_workspace_bytes(s), dtype=torch.uint8, device=dev)
+    before = moe.moe_tune_ffn_group_rows(512 if n_chunks > 1 else 0)
+    try:
+        moe.moe_layer_backward(s, L.x, b["Wgp"], L.bias, L.bias_stride, W1, W2, b["W1p"], b["expert_idx"],
+                               b["gate"], b["offsets"], b["slot_of"], b["src_of"], b["xe"], b["ye"], pre, hid,
+                               torch.from_numpy(dy).to(dev), g["dx"], g["dWg"], g["dW1"], g["dW2"],
+                               g["dgate"], ws, n_chunks=n_chunks)
+        torch.cuda.synchronize()
+    finally:
+        moe.moe_tune_ffn_group_rows(before)
+    counts = b["counts"].cpu().numpy()
+    order = np.argsort(counts)
+    experts = np.unique(np.concatenate([order[:1], order[-1:], order[np.linspace(1, E - 2, 4).astype(int)]]))
+    print(f"{name}: backward oracle, weight gradients of experts {experts.tolist()} ...", flush=True)
+    o = bo.moe_layer_backward(li.x, li.Wg, li.W1, li.W2, dy, k=k, capacity=li.C, bias=li.gate_bias,
+                              bias_stride=li.bias_token_stride, experts=experts)
+    assert np.array_equal(b["slot_of"].cpu().numpy(), o.fwd.slot_of)
+    tol = 3e-2          # two chained bf16 operand roundings (see the backward parity tests)
+    dx = g["dx"].cpu().numpy().reshape(T, d)
+    dropped = (o.fwd.slot_of.reshape(T, k) < 0).all(1)
+    assert not dx[dropped].any()
+    # dx: with a skewed gate a third of the tokens are dropped outright (rows of exact zeros,
+    # which lower the RMS over all rows without telling anything) and the kept rows' norms
+    # spread widely (the largest 4.5 x the RMS over all): the same two roundings, applied to
+    # the oracle's own fp64 values on the CPU, already give max-abs err / RMS = 4.0e-2 at
+    # configuration 3.  A row's error scales with that row, so each row is held to the
+    # tolerance times its own RMS (or the RMS over all rows, where that is larger), and the
+    # error's RMS to 4e-3 of the gradient's (two roundings of 2^-9/sqrt(3) each: 1.6e-3, plus
+    # the fp16 pre-activations' part; 2.1e-3 in that CPU emulation).
+    err = dx - o.dx
+    rms = float(np.sqrt(np.mean(o.dx ** 2)))
+    row_scale = np.maximum(np.sqrt(np.mean(o.dx ** 2, axis=1)), rms)
+    errs = dict(dgate=rel_rms_err(g["dgate"].cpu().numpy().reshape(T, k), o.dgate),
+                dx_max_over_rms=float(np.abs(err).max() / rms),
+                dx_max_over_row_scale=float((np.abs(err).max(1) / row_scale).max()),
+                dx_rms=float(np.sqrt(np.mean(err ** 2)) / rms),
+                dWg=rel_rms_err(g["dWg"].cpu().numpy().reshape(d, E), o.dWg))
+    print(f"{name}: errors relative to the gradient's RMS: {errs}", flush=True)
+    assert errs["dgate"] <= 5e-3 and errs["dWg"] <= tol
+    assert errs["dx_max_over_row_scale"] <= tol and errs["dx_rms"] <= 4e-3
+    for e in experts.tolist():
+        for got_t, ref in ((g["dW1"].view(E, d, h)[e], o.dW1[e]), (g["dW2"].view(E, h, d)[e], o.dW2[e])):
+            got = got_t.cpu().numpy()
+            rms = float(np.sqrt(np.mean(ref ** 2)))
+            # few-row experts: error relative to the element plus the layer tolerance of the RMS
+            assert (np.abs(got - ref) <= 2.0 ** -7 * np.abs(ref) + tol * rms).all(), e
