@@ -33,8 +33,8 @@ INFINITY_CACHE_BYTES = 256 << 20
 # The counters cannot be read from inside the process, so the figure is a stored
 # measurement, reported only for the workload and launch configuration it was taken on
 # (null for any other): {(workload, n_chunks): (FETCH_SIZE KiB, WRITE_SIZE KiB)} per launch.
-GEMM1_TRAFFIC_KIB = {("large_chunked", 1): (1563240.7, 1406581.4),     # profiles/layer_hbm_traffic_pmc.txt
-                     ("gpt2s_moe", 1): (70064.8, 50061.3)}
+GEMM1_TRAFFIC_KIB = {("large_chunked", 1): (1560134.6, 1017952.0),     # profiles/layer_hbm_traffic_pmc.txt
+                     ("gpt2s_moe", 1): (69372.2, 50052.5)}
 FETCH_UNIT, WRITE_UNIT = 2.0, 1.0     # what the plain-copy calibration reads per counted KiB
 
 
@@ -267,7 +267,8 @@ def main() -> int:
         g1_bytes = A * l0.h * 2 + A * l0.d * 2 + l0.E * l0.d * l0.h * 4
         g1_gbps = g1_bytes / (g1_avg_ms * 1e-3) / 1e9
     roof = {"kernel": ("wgrad_gemm_kernel (dW2 = act(P)^T dye)" if args.backward else
-                       "grouped_gemm_mfma_kernel<bf16 in, fp16 out, GeLU> (first expert GEMM)"),
+                       moe.moe_expert_gemm_kernel(s, 0) + " <bf16 in, fp16 out, GeLU> (first expert GEMM)"
+                       if bf16 else "grouped_gemm_f32_kernel (first expert GEMM)"),
             "avg_launch_us": g1_avg_ms * 1e3, "launches": int(g1_ms.size),
             "algorithmic_flops": g1_flops, "algorithmic_bytes": g1_bytes,
             "traffic": None if args.backward else gemm1_traffic_bytes(args.workload, args.chunks),

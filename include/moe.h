@@ -263,7 +263,13 @@ int32_t moe_profile_read(int32_t stage, float *ms, int32_t cap);
  *   show what each costs (bit 0: no matrix instructions; bit 1: no LDS fragment reads
  *   after the first stage; bit 2: no global loads and LDS writes in the loop; bit 3: no
  *   output stores; bit 4: no phase offset between the two wavefront groups; built: 0, 1,
- *   2, 4, 6, 7, 8, 16) -- their outputs are wrong by construction.  K a multiple of 64. */
+ *   2, 4, 6, 7, 8, 16) -- their outputs are wrong by construction.  K a multiple of 64.
+ * moe_expert_gemm_kernel: which kernel an unchunked bf16 layer of shape s launches for its
+ *   expert GEMM `which` (0: first, xe W1; 1: second, H W2), written to name (host, len
+ *   bytes, always terminated) as "<kernel> <tile rows>x<tile columns>", so that a
+ *   measurement can say which kernel it timed.  MOE_EINVAL for which outside {0, 1}, a
+ *   null name or len == 0, an unsupported shape or an fp32 layer (one kernel there). */
+moe_status moe_expert_gemm_kernel(const moe_shape *s, int32_t which, char *name, size_t len);
 moe_status moe_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
 moe_status moe_calib_gemm(const void *A, const void *W, void *C, const int32_t *items,
                           const int32_t *n_items, int32_t max_items, int32_t N, int32_t K,

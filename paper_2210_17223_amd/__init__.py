@@ -5,7 +5,7 @@ include/moe_sched.h, include/moe_train.h, include/moe_offload.h, include/moe_com
 package only marshals arguments.  PyTorch is used for device memory and streams.
 """
 from .binding import (ACT, DTYPE, MoeError, Shape, alloc_buffers, lib, lib_path,
-                      moe_calib_copy, moe_calib_gemm, moe_calib_mfma, moe_capacity, moe_combine, moe_dispatch, moe_dispatch_static,
+                      moe_calib_copy, moe_calib_gemm, moe_calib_mfma, moe_capacity, moe_expert_gemm_kernel, moe_combine, moe_dispatch, moe_dispatch_static,
                       moe_dispatch_static_limit, moe_expert_ffn,
                       moe_last_error, moe_layer_chunked, moe_max_rows, moe_pack_gate,
                       moe_pack_weights, moe_packed_gate_bytes, moe_packed_weight_bytes,
@@ -29,7 +29,7 @@ __all__ = ["comm", "moe_layer_padded", "moe_padded_workspace_bytes", "moe_expert
            "moe_path_profile", "moe_popularity_estimate", "moe_schedule_experts",
            "moe_schedule_layer", "moe_top_lists_identical",
            "ACT", "DTYPE", "MoeError", "Shape", "alloc_buffers", "lib", "lib_path",
-           "moe_calib_copy", "moe_calib_gemm", "moe_calib_mfma", "moe_capacity", "moe_combine", "moe_dispatch", "moe_dispatch_static",
+           "moe_calib_copy", "moe_calib_gemm", "moe_calib_mfma", "moe_capacity", "moe_expert_gemm_kernel", "moe_combine", "moe_dispatch", "moe_dispatch_static",
            "moe_dispatch_static_limit", "moe_expert_ffn",
            "moe_last_error", "moe_layer_chunked", "moe_max_rows", "moe_pack_gate",
            "moe_pack_weights", "moe_packed_gate_bytes", "moe_packed_weight_bytes",

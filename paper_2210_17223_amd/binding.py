@@ -80,6 +80,7 @@ def lib() -> C.CDLL:
         L.moe_dispatch_static.argtypes = [sp] + [vp] * 8
         L.moe_dispatch_static.restype = C.c_int
         L.moe_dispatch_static_limit.restype = sz
+        L.moe_expert_gemm_kernel.argtypes = [sp, i32, C.c_char_p, sz]
         L.moe_dispatch_static_limit.argtypes = []
         L.moe_expert_ffn.argtypes = [sp] + [vp] * 9
         L.moe_combine.argtypes = [sp] + [vp] * 6
@@ -199,6 +200,13 @@ def moe_calib_copy(dst, src, nbytes: int, stream=None) -> None:
 def moe_calib_gemm(A, W, Cout, items, n_items, N: int, K: int, variant: int, gelu: bool, stream=None) -> None:
     _check(lib().moe_calib_gemm(_ptr(A), _ptr(W), _ptr(Cout), _ptr(items), _ptr(n_items), items.numel() // 4,
                                 N, K, variant, int(gelu), _stream(stream)))
+
+
+def moe_expert_gemm_kernel(s: Shape, which: int) -> str:
+    """Name and tile of the kernel an unchunked bf16 layer launches for expert GEMM `which`."""
+    buf = C.create_string_buffer(96)
+    _check(lib().moe_expert_gemm_kernel(C.byref(s), int(which), buf, C.sizeof(buf)))
+    return buf.value.decode()
 
 
 def moe_calib_mfma(sink, waves_per_simd: int, iters: int, random_operands: bool, stream=None) -> float:

@@ -127,4 +127,15 @@ moe_status moe_calib_gemm(const void *A, const void *W, void *C, const int32_t *
                              n_items, max_items, N, K, variant, gelu, static_cast<hipStream_t>(stream));
 }
 
+moe_status moe_expert_gemm_kernel(const moe_shape *s, int32_t which, char *name, size_t len)
+{
+    if (s == nullptr || name == nullptr || len == 0 || (which != 0 && which != 1) ||
+        moe_max_rows(s) <= 0 || s->dtype != MOE_BF16) {
+        set_error("moe_expert_gemm_kernel: which must be 0 or 1, name a buffer, the shape a supported bf16 layer");
+        return MOE_EINVAL;
+    }
+    expert_gemm_kernel_name(*s, which, 1, name, len);
+    return MOE_OK;
+}
+
 }  // extern "C"

@@ -68,6 +68,7 @@ struct GemmPlan {
     int32_t concurrent;      // work items in flight per XCD (sets the panel width)
 };
 GemmPlan choose_gemm_plan(const moe_shape &s, int which, int n_chunks);
+void expert_gemm_kernel_name(const moe_shape &s, int which, int n_chunks, char *name, size_t len);
 
 // Where each piece of the caller's workspace lives.
 struct Workspace {

@@ -13,6 +13,7 @@
 // H and ye are kept in fp16.
 // fp32 layers: a plain LDS-tiled vector-ALU GEMM (correctness configuration).
 #include "common.h"
+#include <cstdio>
 
 #include <hip/hip_ext.h>
 
@@ -685,6 +686,15 @@ void launch_mfma_cfg(const uint16_t *A, const uint16_t *W, const float *bias, TO
             A, W, bias, C, pre, items, nitems, max_items, N, K, stage, st, row_src, row_div);
 }
 
+// The ping-pong kernel addresses its operands with 32-bit element offsets from scalar bases
+// (the expert's weight matrix; the tile's first row, or the whole token matrix when the rows
+// are gathered) and walks whole 64-deep stages.
+inline bool pp_kernel_fits(int N, int K, bool gathered, uint64_t row_limit)
+{
+    return K % 64 == 0 && static_cast<uint64_t>(N) * K < (1ull << 32) &&
+           (gathered ? row_limit * static_cast<uint64_t>(K) : 256ull * K) < (1ull << 32);
+}
+
 template <bool F16, typename TOut, int ACT, bool KEEP>
 void launch_mfma(const GemmPlan &gp, const uint16_t *A, const uint16_t *W, const float *bias,
                  TOut *C, _Float16 *pre, const WorkItem *items, const int32_t *nitems, int N, int K,
@@ -697,10 +707,7 @@ void launch_mfma(const GemmPlan &gp, const uint16_t *A, const uint16_t *W, const
                                                               row_src, row_div)
     if (gp.bm == 256) {
         if constexpr (std::is_same<TOut, _Float16>::value) {
-            // the ping-pong kernel addresses its operands with 32-bit element offsets
-            const bool fits = K % 64 == 0 && static_cast<uint64_t>(N) * K < (1ull << 32) &&
-                              (row_src == nullptr ? 256ull * K : row_limit * static_cast<uint64_t>(K)) < (1ull << 32);
-            if (fits) {
+            if (pp_kernel_fits(N, K, row_src != nullptr, row_limit)) {
                 constexpr size_t lds = 2 * (256 + 256) * (64 + 8) * sizeof(uint16_t);
                 auto kern = grouped_gemm_pp_kernel<F16, ACT, KEEP>;
                 static PerDeviceOnce once;
@@ -747,6 +754,17 @@ void launch_mfma_pair(const moe_shape &s, const uint16_t *xe, const uint16_t *W1
 }
 
 }  // namespace
+
+// Which kernel the layer launches for expert GEMM `which` (0: first, 1: second) of a bf16 layer,
+// for labelling measurements: "<kernel> <tile rows>x<tile columns>".
+void expert_gemm_kernel_name(const moe_shape &s, int which, int n_chunks, char *name, size_t len)
+{
+    const GemmPlan gp = choose_gemm_plan(s, which, n_chunks);
+    const int N = which == 0 ? s.d_ff : s.d_model, K = which == 0 ? s.d_model : s.d_ff;
+    const bool pp = gp.bm == 256 && pp_kernel_fits(N, K, which == 0, static_cast<uint64_t>(s.T));
+    std::snprintf(name, len, "%s %dx%d", pp ? "grouped_gemm_pp_kernel" : "grouped_gemm_mfma_kernel",
+                  gp.bm, gp.bn);
+}
 
 // Measurement aid: the 256 x 256 kernel alone on caller-made operands and work list, with
 // parts of it left out (see ABL above).  gelu != 0 applies the activation.

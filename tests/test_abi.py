@@ -116,3 +116,21 @@ def test_static_dispatch_refuses_what_does_not_fit_its_array():
     assert rc == 2 and "static array holds" in moe.moe_last_error()
     rc = L.moe_dispatch_static(C.byref(s), None, p, p, p, p, p, p, None)
     assert rc == 1
+
+
+def test_expert_gemm_kernel_names_the_kernel_and_its_tile():
+    """moe_expert_gemm_kernel is host logic only: the large layer takes the 256 x 256 ping-pong
+    kernel for both GEMMs, the GPT-2-small layer the 128-row tiles of the general kernel."""
+    big = wl.CONFIGS["large_chunked"]
+    s = moe.Shape.make(big["T"], big["d"], big["E"], big["h"], big["k"], big["C"], dtype="bf16", act="gelu")
+    assert moe.moe_expert_gemm_kernel(s, 0) == "grouped_gemm_pp_kernel 256x256"
+    assert moe.moe_expert_gemm_kernel(s, 1) == "grouped_gemm_pp_kernel 256x256"
+    small = wl.CONFIGS["gpt2s_moe"]
+    s2 = moe.Shape.make(small["T"], small["d"], small["E"], small["h"], small["k"], small["C"], dtype="bf16", act="gelu")
+    assert moe.moe_expert_gemm_kernel(s2, 0).startswith("grouped_gemm_mfma_kernel 128x")
+    tiny = wl.CONFIGS["tiny_fp32"]
+    s3 = moe.Shape.make(tiny["T"], tiny["d"], tiny["E"], tiny["h"], tiny["k"], tiny["C"], dtype="f32", act="gelu")
+    with pytest.raises(moe.MoeError):
+        moe.moe_expert_gemm_kernel(s3, 0)
+    with pytest.raises(moe.MoeError):
+        moe.moe_expert_gemm_kernel(s, 2)
