@@ -571,7 +571,7 @@ def gemm_ablation() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     E, rows_e, BM = 64, 1024, 256
-    variants = [(0, "whole kernel"), (16, "whole, both wavefront groups in phase"), (8, "no output stores"),
+    variants = [(0, "whole kernel"), (8, "no output stores"),
                 (6, "MFMAs + barriers only (one stage of operands)"), (4, "MFMAs + LDS fragment reads"),
                 (2, "MFMAs + global loads + LDS writes"), (1, "everything but the MFMAs"),
                 (7, "barriers, prologue and epilogue only")]

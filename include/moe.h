@@ -261,9 +261,9 @@ int32_t moe_profile_read(int32_t stage, float *ms, int32_t cap);
  *   1..256 and the first column a multiple of 256, *n_items <= max_items (device).
  *   variant 0 is the kernel as the layer runs it; other variants leave parts of it out to
  *   show what each costs (bit 0: no matrix instructions; bit 1: no LDS fragment reads
- *   after the first stage; bit 2: no global loads and LDS writes in the loop; bit 3: no
- *   output stores; bit 4: no phase offset between the two wavefront groups; built: 0, 1,
- *   2, 4, 6, 7, 8, 16) -- their outputs are wrong by construction.  K a multiple of 64.
+ *   after the first step; bit 2: no global loads and LDS writes in the loop; bit 3: no
+ *   output stores; built: 0, 1, 2, 4, 6, 7, 8) -- their outputs are wrong by
+ *   construction.  K a multiple of 64, N * K * 2 and 256 * K * 2 below 2^31.
  * moe_expert_gemm_kernel: which kernel an unchunked bf16 layer of shape s launches for its
  *   expert GEMM `which` (0: first, xe W1; 1: second, H W2), written to name (host, len
  *   bytes, always terminated) as "<kernel> <tile rows>x<tile columns>", so that a

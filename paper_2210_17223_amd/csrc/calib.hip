@@ -118,7 +118,7 @@ moe_status moe_calib_gemm(const void *A, const void *W, void *C, const int32_t *
 {
     if (A == nullptr || W == nullptr || C == nullptr || items == nullptr || n_items == nullptr ||
         max_items < 1 || N < 8 || K < 64 || K % 64 != 0 || N % 8 != 0 ||
-        static_cast<uint64_t>(N) * K >= (1ull << 32)) {
+        static_cast<uint64_t>(N) * K * 2 >= (1ull << 31) || 256ull * K * 2 >= (1ull << 31)) {
         set_error("moe_calib_gemm: NULL pointer, or N not a multiple of 8, or K not a multiple of 64");
         return MOE_EINVAL;
     }

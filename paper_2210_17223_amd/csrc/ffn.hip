@@ -8,9 +8,10 @@
 //
 // bf16 layers: MFMA 32x32x16 tiles.  Both operands are stored with the contraction
 // index contiguous (activations by nature, weights after moe_pack_weights), staged
-// through LDS in 128 x 64 tiles, and the weight tile is fed as the MFMA "A" operand
+// through LDS in 64-deep stages, and the weight tile is fed as the MFMA "A" operand
 // so that each lane ends up with four consecutive output columns of one row.
-// H and ye are kept in fp16.
+// grouped_gemm_w4_kernel runs the 256 x 256 output tiles of the large layers,
+// grouped_gemm_mfma_kernel the smaller tile shapes.  H and ye are kept in fp16.
 // fp32 layers: a plain LDS-tiled vector-ALU GEMM (correctness configuration).
 #include "common.h"
 #include <cstdio>
@@ -379,42 +380,58 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void grouped_gemm_mfma_kernel(
     }
 }
 
-// ---------------------------------------------------------------- 256 x 256 ping-pong GEMM
+// ---------------------------------------------------------------- 256 x 256 GEMM, four wavefronts
 // The same product as grouped_gemm_mfma_kernel for 256 x 256 output tiles, fp16 output and a
-// contraction depth that is a multiple of 64, with two changes that measured faster on the
-// large shapes (3 % on the first GEMM of the T = 32768 layer, 13 % at K = 1024):
-//  * The eight wavefronts form two groups of four (one wavefront of each group per SIMD) that
-//    run one 32-deep phase apart: while one group issues its 16 MFMAs the other moves data
-//    (writes its share of the next stage to LDS, requests the stage after it, reads its own
-//    fragments).  Four barriers per 64-deep stage keep the groups in step; the group that
-//    starts late passes one extra barrier before the loop, the other one after it, so every
-//    wavefront passes the same number.
-//  * The tile leaves through LDS: every wavefront writes its 128 x 64 sub-tile to a patch of
-//    its own and stores it as whole 128-byte lines, 16 bytes per lane, instead of 8 bytes per
-//    lane into 32 different lines per instruction.
-// Operand addresses are 32-bit element offsets from scalar bases (the tile's first row, the
-// expert's weight matrix; with row_src the token matrix), which the host checks fit.
+// contraction depth that is a multiple of 64, laid out for one wavefront per SIMD:
+//  * four wavefronts of 128 x 128 (2 x 2): every operand fragment read from LDS feeds four
+//    MFMAs (128 KB of LDS reads per 64-deep stage against 196 KB for eight wavefronts of
+//    128 x 64); the 16 accumulators of a wavefront (256 registers) are pinned to AGPRs, which
+//    leaves the 256 VGPRs to fragments and staging;
+//  * TWO stages of global loads in flight in registers (2 x 64 VGPRs) beside the double-buffered
+//    LDS tiles, through buffer loads whose per-lane byte offsets never change (the stage goes
+//    into the scalar offset): no address arithmetic in the loop;
+//  * one barrier per stage, and every memory instruction of a stage (32 LDS fragment reads,
+//    16 LDS writes, 16 global loads per wavefront) issued singly between two MFMAs in a fixed
+//    order: fragment reads one 16-deep step ahead, the LDS writes of the next stage spread
+//    over the first three steps (all before the barrier), a register reloaded after it was
+//    written.  The MFMAs are inline assembly so that the accumulators stay in AGPRs and the
+//    order holds; nothing depends on an MFMA result before the loop ends.
+//  * The tile leaves through LDS: every wavefront writes its 128 x 128 sub-tile to a patch of
+//    its own and stores it as whole lines, 16 bytes per lane.
+// Loads past the last stage fetch the last stage again (never used) instead of branching.
+// Operand addresses are 32-bit byte offsets into two buffer resources (the tile's rows, or
+// the whole token matrix when the rows are gathered through row_src; the expert's weight
+// matrix), which the host checks fit.
 #define MOE_LGKM0() asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")
+#define MOE_SB() __builtin_amdgcn_sched_barrier(0)
 #define MOE_BAR()                                                                                 \
     do {                                                                                         \
-        __builtin_amdgcn_sched_barrier(0);                                                       \
+        MOE_SB();                                                                                \
         __builtin_amdgcn_s_barrier();                                                            \
-        __builtin_amdgcn_sched_barrier(0);                                                       \
+        MOE_SB();                                                                                \
     } while (0)
 
+template <bool F16>
+__device__ __forceinline__ void mfma_32x32x16_agpr(f32x16 &acc, const u32x4 &a, const u32x4 &b)
+{
+    if constexpr (F16)
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    else
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
 // ABL (measurement only, 0 in the layer): bit 0 leaves out the MFMAs, bit 1 the LDS fragment
-// reads after the first stage, bit 2 the global loads and LDS writes inside the loop, bit 3 the
-// output stores, bit 4 the phase offset between the two groups.  Results are then wrong by
-// construction; every access stays inside the buffers.
+// reads after the first step, bit 2 the global loads and LDS writes inside the loop, bit 3 the
+// output stores.  Results are then wrong by construction; every access stays inside the buffers.
 template <bool F16, int ACT, bool KEEP, int ABL = 0>
-__global__ __launch_bounds__(512, 2) void grouped_gemm_pp_kernel(
+__global__ __launch_bounds__(256, 1) void grouped_gemm_w4_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W,
     const float *__restrict__ bias, _Float16 *__restrict__ C, _Float16 *__restrict__ Pre,
     const WorkItem *__restrict__ items, const int32_t *__restrict__ nitems, int N, int K,
-    const int32_t *__restrict__ row_src, int row_div)
+    const int32_t *__restrict__ row_src, int row_div, int a_rows)
 {
-    constexpr int WM = 2, TM = 4, TN = 2;            // 2 x 4 wavefronts of 128 x 64 each
-    constexpr int BM = 256, BN = 256, BK = 64, LD = BK + 8, NT = 512, AV = 4, WV = 4;
+    constexpr int TM = 4, TN = 4;                    // 2 x 2 wavefronts of 128 x 128 each
+    constexpr int BM = 256, BN = 256, BK = 64, LD = BK + 8, NT = 256, NV = 8, PD = 2;
     const int total = *nitems;
     const int per_xcd = (total + 7) / 8;
     const int slot = blockIdx.x / 8;
@@ -431,29 +448,32 @@ __global__ __launch_bounds__(512, 2) void grouped_gemm_pp_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int grp = wave >> 2;
-    const int wm = wave % WM, wn = wave / WM;
+    const int wm = wave & 1, wn = wave >> 1;
     const uint16_t *Wexp = W + static_cast<size_t>(item.expert) * N * K;
     // gathered rows are offsets from A itself, packed rows from the tile's first row
     const uint16_t *Abase = row_src != nullptr ? A : A + static_cast<size_t>(item.row0) * K;
+    const unsigned a_bytes = static_cast<unsigned>(row_src != nullptr ? a_rows : rows) *
+                             static_cast<unsigned>(K) * 2u;
+    const __amdgpu_buffer_rsrc_t rsa =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(Abase), 0, a_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(Wexp), 0, static_cast<unsigned>(N) * static_cast<unsigned>(K) * 2u,
+        0x00020000);
 
-    unsigned a_src[AV], w_src[WV];
+    int a_src[NV], w_src[NV];          // byte offsets of vector q: row (tid + 256 q) / 8, 16-byte piece tid % 8
     const int ld_col = (tid & 7) * 8;
-    const int off0 = (tid >> 3) * LD + ld_col;       // LDS place of vector q: off0 + q * 64 * LD
+    const int off0 = (tid >> 3) * LD + ld_col;       // LDS place of vector q: off0 + q * 32 * LD
 #pragma unroll
-    for (int q = 0; q < AV; ++q) {
+    for (int q = 0; q < NV; ++q) {
         const int r = min((tid + NT * q) >> 3, rows - 1);
-        const unsigned arow = row_src != nullptr
-                                  ? static_cast<unsigned>(row_src[item.row0 + r] / row_div)
-                                  : static_cast<unsigned>(r);
-        a_src[q] = arow * static_cast<unsigned>(K) + ld_col;
+        const int arow = row_src != nullptr ? row_src[item.row0 + r] / row_div : r;
+        a_src[q] = (arow * K + ld_col) * 2;
     }
 #pragma unroll
-    for (int q = 0; q < WV; ++q) {
+    for (int q = 0; q < NV; ++q) {
         const int r = (tid + NT * q) >> 3;
-        w_src[q] = static_cast<unsigned>(min(n0 + r, N - 1)) * static_cast<unsigned>(K) + ld_col;
+        w_src[q] = (min(n0 + r, N - 1) * K + ld_col) * 2;
     }
-    const int jact = min(TM, max(0, (rows - wm * TM * 32 + 31) / 32));
 
     f32x16 acc[TN][TM];
 #pragma unroll
@@ -463,110 +483,190 @@ __global__ __launch_bounds__(512, 2) void grouped_gemm_pp_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    u32x4 a_reg[AV], w_reg[WV];
+    u32x4 ra[PD][NV], rw[PD][NV];      // PD stages of operands on their way to LDS
     u32x4 wf[2][TN], af[2][TM];
     const int KT = K / BK;
     const int fr = lane & 31, fk = (lane >> 5) * 8;
     const int wfrag = (wn * TN * 32 + fr) * LD + fk;
     const int afrag = (wm * TM * 32 + fr) * LD + fk;
 
-#define MOE_LOADG(kt_, q0, q1)                                                                    \
-    {                                                                                            \
-        _Pragma("unroll") for (int q = q0; q < q1; ++q) a_reg[q] =                               \
-            *reinterpret_cast<const u32x4 *>(Abase + (a_src[q] + static_cast<unsigned>((kt_) * BK))); \
-        _Pragma("unroll") for (int q = q0; q < q1; ++q) w_reg[q] =                               \
-            *reinterpret_cast<const u32x4 *>(Wexp + (w_src[q] + static_cast<unsigned>((kt_) * BK)));  \
-    }
-#define MOE_STOREL(buf, q0, q1)                                                                   \
-    {                                                                                            \
-        _Pragma("unroll") for (int q = q0; q < q1; ++q)                                          \
-            *reinterpret_cast<u32x4 *>(As + (buf) * A_BUF + off0 + q * 64 * LD) = a_reg[q];      \
-        _Pragma("unroll") for (int q = q0; q < q1; ++q)                                          \
-            *reinterpret_cast<u32x4 *>(Ws + (buf) * W_BUF + off0 + q * 64 * LD) = w_reg[q];      \
-    }
-#define MOE_READF(slot_, buf, ks)                                                                 \
-    {                                                                                            \
-        _Pragma("unroll") for (int i = 0; i < TN; ++i) wf[slot_][i] =                            \
-            *reinterpret_cast<const u32x4 *>(Ws + (buf) * W_BUF + wfrag + i * 32 * LD + (ks) * 16); \
-        _Pragma("unroll") for (int j = 0; j < TM; ++j) af[slot_][j] =                            \
-            *reinterpret_cast<const u32x4 *>(As + (buf) * A_BUF + afrag + j * 32 * LD + (ks) * 16); \
-    }
-#define MOE_MMA(slot_)                                                                            \
-    {                                                                                            \
-        _Pragma("unroll") for (int j = 0; j < TM; ++j)                                           \
-        {                                                                                        \
-            if (FULL || j < jact) {                                                              \
-                _Pragma("unroll") for (int i = 0; i < TN; ++i)                                   \
-                    acc[i][j] = mfma_32x32x16<F16>(wf[slot_][i], af[slot_][j], acc[i][j]);       \
-            }                                                                                    \
+#define MOE_LDA(set, q, kt_)                                                                      \
+    ra[set][q] = __builtin_bit_cast(                                                             \
+        u32x4, __builtin_amdgcn_raw_buffer_load_b128(rsa, a_src[q], (kt_) * (BK * 2), 0))
+#define MOE_LDW(set, q, kt_)                                                                      \
+    rw[set][q] = __builtin_bit_cast(                                                             \
+        u32x4, __builtin_amdgcn_raw_buffer_load_b128(rsw, w_src[q], (kt_) * (BK * 2), 0))
+#define MOE_STA(set, q, buf)                                                                      \
+    *reinterpret_cast<u32x4 *>(As + (buf) * A_BUF + off0 + (q) * 32 * LD) = ra[set][q]
+#define MOE_STW(set, q, buf)                                                                      \
+    *reinterpret_cast<u32x4 *>(Ws + (buf) * W_BUF + off0 + (q) * 32 * LD) = rw[set][q]
+#define MOE_RDW(slot_, i, buf, ks)                                                                \
+    wf[slot_][i] = *reinterpret_cast<const u32x4 *>(Ws + (buf) * W_BUF + wfrag + (i) * 32 * LD + (ks) * 16)
+#define MOE_RDA(slot_, j, buf, ks)                                                                \
+    af[slot_][j] = *reinterpret_cast<const u32x4 *>(As + (buf) * A_BUF + afrag + (j) * 32 * LD + (ks) * 16)
+// LDS write / global load number v of a stage: the A rows for v < 8, the weight rows above
+#define MOE_WR(set, v, buf)                                                                       \
+    do {                                                                                         \
+        if constexpr (!(ABL & 4)) {                                                              \
+            if constexpr ((v) < 8) MOE_STA(set, (v), buf); else MOE_STW(set, (v) - 8, buf);       \
         }                                                                                        \
+    } while (0)
+#define MOE_LD(set, v, kt_)                                                                       \
+    do {                                                                                         \
+        if constexpr (!(ABL & 4)) {                                                              \
+            if constexpr ((v) < 8) MOE_LDA(set, (v), kt_); else MOE_LDW(set, (v) - 8, kt_);       \
+        }                                                                                        \
+    } while (0)
+#define MOE_RD(slot_, v, buf, ks)                                                                 \
+    do {                                                                                         \
+        if constexpr (!(ABL & 2)) {                                                              \
+            if constexpr ((v) < 4) MOE_RDW(slot_, (v), buf, ks); else MOE_RDA(slot_, (v) - 4, buf, ks); \
+        }                                                                                        \
+    } while (0)
+// MFMA m of a 16-deep step: row sub-tile m / 4, column sub-tile m % 4
+#define MOE_MM(slot_, m)                                                                          \
+    do {                                                                                         \
+        constexpr int i_ = (m) & 3, j_ = (m) >> 2;                                               \
+        if constexpr (!(ABL & 1))                                                                \
+            mfma_32x32x16_agpr<F16>(acc[i_][j_], wf[slot_][i_], af[slot_][j_]);                  \
+    } while (0)
+#define MOE_PAIR(slot_, m, F)                                                                     \
+    MOE_MM(slot_, m);                                                                            \
+    F(std::integral_constant<int, (m)>{});                                                       \
+    MOE_SB();
+#define MOE_KSTEP(slot_, F)                                                                       \
+    {                                                                                            \
+        MOE_PAIR(slot_, 0, F) MOE_PAIR(slot_, 1, F) MOE_PAIR(slot_, 2, F) MOE_PAIR(slot_, 3, F)   \
+        MOE_PAIR(slot_, 4, F) MOE_PAIR(slot_, 5, F) MOE_PAIR(slot_, 6, F) MOE_PAIR(slot_, 7, F)   \
+        MOE_PAIR(slot_, 8, F) MOE_PAIR(slot_, 9, F) MOE_PAIR(slot_, 10, F) MOE_PAIR(slot_, 11, F) \
+        MOE_PAIR(slot_, 12, F) MOE_PAIR(slot_, 13, F) MOE_PAIR(slot_, 14, F) MOE_PAIR(slot_, 15, F) \
     }
-// One 64-deep stage kt in LDS buffer kt & 1, as two phases of {move, barrier, multiply, barrier}.
-#define MOE_PP_STAGES                                                                             \
-    for (int kt = 0; kt < KT; ++kt) {                                                            \
+// Stage kt: LDS buffer kt & 1 is multiplied; register set SET (stage kt + 1) goes to the other
+// buffer and is refilled with stage kt + 1 + PD; the fragments of step 0 are already in slot 0.
+// Memory instruction m of a step follows MFMA m: eight fragment reads, then LDS writes 6 / 5 / 5
+// (steps 0, 1, 2) and global loads 2 / 3 / 3 / 8.
+#define MOE_W4_STAGE(kt_, SET)                                                                    \
+    {                                                                                            \
+        const int kt = (kt_);                                                                    \
         const int buf = kt & 1;                                                                  \
-        const bool next1 = !(ABL & 4) && kt + 1 < KT, next2 = !(ABL & 4) && kt + 2 < KT;         \
-        const bool reads = !(ABL & 2) || kt == 0;                                                \
-        if (next1) MOE_STOREL(buf ^ 1, 0, 2)                                                     \
-        if (next2) MOE_LOADG(kt + 2, 0, 2)                                                       \
-        if (reads) {                                                                             \
-            MOE_READF(0, buf, 0)                                                                 \
-            MOE_READF(1, buf, 1)                                                                 \
+        const int ktl = min(kt + 1 + PD, KT - 1);                                                \
+        {                                                                                        \
+            auto mem0 = [&](auto mc) {                                                           \
+                constexpr int m = decltype(mc)::value;                                           \
+                if constexpr (m < 8) MOE_RD(1, m, buf, 1);                                       \
+                else if constexpr (m < 14) MOE_WR(SET, m - 8, buf ^ 1);                          \
+                else MOE_LD(SET, m - 14, ktl);                                                   \
+            };                                                                                   \
+            MOE_KSTEP(0, mem0)                                                                   \
+        }                                                                                        \
+        {                                                                                        \
+            auto mem1 = [&](auto mc) {                                                           \
+                constexpr int m = decltype(mc)::value;                                           \
+                if constexpr (m < 8) MOE_RD(0, m, buf, 2);                                       \
+                else if constexpr (m < 13) MOE_WR(SET, m - 8 + 6, buf ^ 1);                      \
+                else MOE_LD(SET, m - 13 + 2, ktl);                                               \
+            };                                                                                   \
+            MOE_KSTEP(1, mem1)                                                                   \
+        }                                                                                        \
+        {                                                                                        \
+            auto mem2 = [&](auto mc) {                                                           \
+                constexpr int m = decltype(mc)::value;                                           \
+                if constexpr (m < 8) MOE_RD(1, m, buf, 3);                                       \
+                else if constexpr (m < 13) MOE_WR(SET, m - 8 + 11, buf ^ 1);                     \
+                else MOE_LD(SET, m - 13 + 5, ktl);                                               \
+            };                                                                                   \
+            MOE_KSTEP(0, mem2)                                                                   \
         }                                                                                        \
         MOE_LGKM0();                                                                             \
         MOE_BAR();                                                                               \
-        __builtin_amdgcn_s_setprio(2);                                                           \
-        if constexpr (!(ABL & 1)) {                                                              \
-            MOE_MMA(0)                                                                           \
-            MOE_MMA(1)                                                                           \
+        {                                                                                        \
+            auto mem3 = [&](auto mc) {                                                           \
+                constexpr int m = decltype(mc)::value;                                           \
+                if constexpr (m < 8) MOE_RD(0, m, buf ^ 1, 0);                                   \
+                else MOE_LD(SET, m, ktl);                                                        \
+            };                                                                                   \
+            MOE_KSTEP(1, mem3)                                                                   \
         }                                                                                        \
-        __builtin_amdgcn_s_setprio(0);                                                           \
-        MOE_BAR();                                                                               \
-        if (next1) MOE_STOREL(buf ^ 1, 2, 4)                                                     \
-        if (next2) MOE_LOADG(kt + 2, 2, 4)                                                       \
-        if (reads) {                                                                             \
-            MOE_READF(0, buf, 2)                                                                 \
-            MOE_READF(1, buf, 3)                                                                 \
+    }
+#define MOE_W4_STAGES                                                                             \
+    {                                                                                            \
+        int k2 = 0;                                                                              \
+        for (; k2 + 1 < KT; k2 += 2) {                                                           \
+            MOE_W4_STAGE(k2, 1)                                                                  \
+            MOE_W4_STAGE(k2 + 1, 0)                                                              \
         }                                                                                        \
-        MOE_LGKM0();                                                                             \
-        MOE_BAR();                                                                               \
-        __builtin_amdgcn_s_setprio(2);                                                           \
-        if constexpr (!(ABL & 1)) {                                                              \
-            MOE_MMA(0)                                                                           \
-            MOE_MMA(1)                                                                           \
-        }                                                                                        \
-        __builtin_amdgcn_s_setprio(0);                                                           \
-        MOE_BAR();                                                                               \
+        if (k2 < KT) MOE_W4_STAGE(k2, 1)                                                         \
     }
 
-    MOE_LOADG(0, 0, 4)
-    MOE_STOREL(0, 0, 4)
+    // prologue: stage 0 through set 0 into LDS buffer 0, stage 1 in set 1, stage 2 in set 0
+    {
+        const int k1 = min(1, KT - 1), k2 = min(2, KT - 1);
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            MOE_LDA(0, q, 0);
+            MOE_LDW(0, q, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            MOE_LDA(1, q, k1);
+            MOE_LDW(1, q, k1);
+        }
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            MOE_STA(0, q, 0);
+            MOE_STW(0, q, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            MOE_LDA(0, q, k2);
+            MOE_LDW(0, q, k2);
+        }
+    }
     MOE_LGKM0();
     MOE_BAR();
-    if (KT > 1) MOE_LOADG(1, 0, 4)
-    if (!(ABL & 16) && grp == 1) MOE_BAR();           // this group runs one phase behind the other
-    if (jact == TM) {
-        constexpr bool FULL = true;
-        MOE_PP_STAGES
-    } else {
-        constexpr bool FULL = false;
-        MOE_PP_STAGES
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+        MOE_RDW(0, i, 0, 0);
+        MOE_RDW(1, i, 0, 1);
     }
-    if (!(ABL & 16) && grp == 0) MOE_BAR();           // every wavefront has passed the same number of barriers
-#undef MOE_PP_STAGES
-#undef MOE_LOADG
-#undef MOE_STOREL
-#undef MOE_READF
-#undef MOE_MMA
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        MOE_RDA(0, j, 0, 0);
+        MOE_RDA(1, j, 0, 1);
+    }
+    // Every wavefront multiplies all four of its row sub-tiles: sub-tiles past the tile's end
+    // hold clamped rows whose results are never stored, and the tile's time is set by its
+    // fullest wavefront either way.  (Branches around the MFMAs, or a second copy of the loop
+    // without them, make the compiler move accumulators out of the AGPRs inside the loop.)
+    MOE_W4_STAGES
+#undef MOE_W4_STAGES
+#undef MOE_W4_STAGE
+#undef MOE_KSTEP
+#undef MOE_PAIR
+#undef MOE_MM
+#undef MOE_RD
+#undef MOE_LD
+#undef MOE_WR
+#undef MOE_RDA
+#undef MOE_RDW
+#undef MOE_STW
+#undef MOE_STA
+#undef MOE_LDW
+#undef MOE_LDA
 
     // Epilogue.  acc[i][j][4*g + c]: column (wn*TN + i)*32 + 8*g + 4*(lane/32) + c, row
-    // (wm*TM + j)*32 + lane%32 of the tile.  The LDS tiles are free (every wavefront is past
-    // its last read): the wavefront's sub-tile goes to its own patch, row pitch 144 bytes.
-    constexpr int PITCH = 144;
+    // (wm*TM + j)*32 + lane%32 of the tile.  Every wavefront is past its last LDS read after
+    // the barrier; the MFMA results have left the pipeline after the no-ops (the compiler does
+    // not see through the inline assembly).  The wavefront's 128 x 128 sub-tile goes to its
+    // own patch, row pitch 272 bytes.
+    MOE_LGKM0();
+    MOE_BAR();
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    constexpr int PITCH = 272;
     char *patch = reinterpret_cast<char *>(smem) + wave * (TM * 32) * PITCH;
     const float *bexp = bias != nullptr ? bias + static_cast<size_t>(item.expert) * N : nullptr;
     const int rbase = item.row0 + wm * TM * 32;
-    const int ncol = n0 + wn * TN * 32 + (lane & 7) * 8;
+    const int ncol = n0 + wn * TN * 32 + (lane & 15) * 8;
 #pragma unroll
     for (int pass = KEEP ? 0 : 1; pass < 2; ++pass) {      // pass 0: pre-activations, 1: outputs
         _Float16 *out = pass == 0 ? Pre : C;
@@ -588,10 +688,10 @@ __global__ __launch_bounds__(512, 2) void grouped_gemm_pp_kernel(
                 }
         MOE_LGKM0();
         __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int it = 0; it < TM * 4; ++it) {
-            const int rr = it * 8 + (lane >> 3);
-            const u32x4 q = *reinterpret_cast<const u32x4 *>(patch + rr * PITCH + (lane & 7) * 16);
+#pragma unroll 8
+        for (int it = 0; it < TM * 8; ++it) {
+            const int rr = it * 4 + (lane >> 4);
+            const u32x4 q = *reinterpret_cast<const u32x4 *>(patch + rr * PITCH + (lane & 15) * 16);
             const int r = rbase + rr;
             if (r < item.row1 && ncol < N && (!(ABL & 8) || q[0] == 0x7fc07fc1u))
                 *reinterpret_cast<u32x4 *>(out + static_cast<size_t>(r) * N + ncol) = q;
@@ -603,6 +703,7 @@ __global__ __launch_bounds__(512, 2) void grouped_gemm_pp_kernel(
     }
 }
 #undef MOE_LGKM0
+#undef MOE_SB
 #undef MOE_BAR
 
 // ---------------------------------------------------------------- weight packing
@@ -686,13 +787,13 @@ void launch_mfma_cfg(const uint16_t *A, const uint16_t *W, const float *bias, TO
             A, W, bias, C, pre, items, nitems, max_items, N, K, stage, st, row_src, row_div);
 }
 
-// The ping-pong kernel addresses its operands with 32-bit element offsets from scalar bases
-// (the expert's weight matrix; the tile's first row, or the whole token matrix when the rows
-// are gathered) and walks whole 64-deep stages.
-inline bool pp_kernel_fits(int N, int K, bool gathered, uint64_t row_limit)
+// The four-wavefront kernel addresses its operands with 32-bit byte offsets into buffer
+// resources (the expert's weight matrix; the tile's rows, or the whole token matrix when the
+// rows are gathered) and walks whole 64-deep stages.
+inline bool w4_kernel_fits(int N, int K, bool gathered, uint64_t row_limit)
 {
-    return K % 64 == 0 && static_cast<uint64_t>(N) * K < (1ull << 32) &&
-           (gathered ? row_limit * static_cast<uint64_t>(K) : 256ull * K) < (1ull << 32);
+    return K % 64 == 0 && static_cast<uint64_t>(N) * K * 2 < (1ull << 31) &&
+           (gathered ? row_limit * static_cast<uint64_t>(K) : 256ull * K) * 2 < (1ull << 31);
 }
 
 template <bool F16, typename TOut, int ACT, bool KEEP>
@@ -707,16 +808,17 @@ void launch_mfma(const GemmPlan &gp, const uint16_t *A, const uint16_t *W, const
                                                               row_src, row_div)
     if (gp.bm == 256) {
         if constexpr (std::is_same<TOut, _Float16>::value) {
-            if (pp_kernel_fits(N, K, row_src != nullptr, row_limit)) {
+            if (w4_kernel_fits(N, K, row_src != nullptr, row_limit)) {
                 constexpr size_t lds = 2 * (256 + 256) * (64 + 8) * sizeof(uint16_t);
-                auto kern = grouped_gemm_pp_kernel<F16, ACT, KEEP>;
+                auto kern = grouped_gemm_w4_kernel<F16, ACT, KEEP>;
                 static PerDeviceOnce once;
                 once.raise_lds(reinterpret_cast<const void *>(kern), static_cast<int>(lds));
                 const int grid = static_cast<int>(align_up(static_cast<size_t>(gp.max_items), 8));
                 hipEvent_t t0, t1;
                 prof_kernel_events(stage, &t0, &t1);
-                hipExtLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, st, t0, t1, 0, A, W, bias, C,
-                                      pre, items, nitems, N, K, row_src, row_div);
+                hipExtLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, t0, t1, 0, A, W, bias, C,
+                                      pre, items, nitems, N, K, row_src, row_div,
+                                      static_cast<int>(row_limit));
                 return;
             }
         }
@@ -761,8 +863,8 @@ void expert_gemm_kernel_name(const moe_shape &s, int which, int n_chunks, char *
 {
     const GemmPlan gp = choose_gemm_plan(s, which, n_chunks);
     const int N = which == 0 ? s.d_ff : s.d_model, K = which == 0 ? s.d_model : s.d_ff;
-    const bool pp = gp.bm == 256 && pp_kernel_fits(N, K, which == 0, static_cast<uint64_t>(s.T));
-    std::snprintf(name, len, "%s %dx%d", pp ? "grouped_gemm_pp_kernel" : "grouped_gemm_mfma_kernel",
+    const bool w4 = gp.bm == 256 && w4_kernel_fits(N, K, which == 0, static_cast<uint64_t>(s.T));
+    std::snprintf(name, len, "%s %dx%d", w4 ? "grouped_gemm_w4_kernel" : "grouped_gemm_mfma_kernel",
                   gp.bm, gp.bn);
 }
 
@@ -776,13 +878,13 @@ moe_status launch_calib_gemm(const uint16_t *A, const uint16_t *W, _Float16 *C, 
     const int grid = static_cast<int>(align_up(static_cast<size_t>(max_items), 8));
 #define MOE_CALIB_CASE(ABL_)                                                                      \
     case ABL_: {                                                                                  \
-        auto k1 = grouped_gemm_pp_kernel<false, MOE_ACT_GELU_ERF, false, ABL_>;                   \
-        auto k0 = grouped_gemm_pp_kernel<false, MOE_ACT_IDENTITY, false, ABL_>;                   \
+        auto k1 = grouped_gemm_w4_kernel<false, MOE_ACT_GELU_ERF, false, ABL_>;                   \
+        auto k0 = grouped_gemm_w4_kernel<false, MOE_ACT_IDENTITY, false, ABL_>;                   \
         static PerDeviceOnce once1, once0;                                                        \
         once1.raise_lds(reinterpret_cast<const void *>(k1), static_cast<int>(lds));               \
         once0.raise_lds(reinterpret_cast<const void *>(k0), static_cast<int>(lds));               \
-        hipLaunchKernelGGL(gelu ? k1 : k0, dim3(grid), dim3(512), lds, st, A, W, nullptr, C,      \
-                           nullptr, items, nitems, N, K, nullptr, 1);                             \
+        hipLaunchKernelGGL(gelu ? k1 : k0, dim3(grid), dim3(256), lds, st, A, W, nullptr, C,      \
+                           nullptr, items, nitems, N, K, nullptr, 1, 0);                          \
         break;                                                                                    \
     }
     switch (abl) {
@@ -793,9 +895,8 @@ moe_status launch_calib_gemm(const uint16_t *A, const uint16_t *W, _Float16 *C, 
         MOE_CALIB_CASE(6)
         MOE_CALIB_CASE(7)
         MOE_CALIB_CASE(8)
-        MOE_CALIB_CASE(16)
     default:
-        set_error("moe_calib_gemm: variant %d is not built (0, 1, 2, 4, 6, 7, 8, 16)", abl);
+        set_error("moe_calib_gemm: variant %d is not built (0, 1, 2, 4, 6, 7, 8)", abl);
         return MOE_EINVAL;
     }
 #undef MOE_CALIB_CASE

@@ -119,12 +119,12 @@ def test_static_dispatch_refuses_what_does_not_fit_its_array():
 
 
 def test_expert_gemm_kernel_names_the_kernel_and_its_tile():
-    """moe_expert_gemm_kernel is host logic only: the large layer takes the 256 x 256 ping-pong
+    """moe_expert_gemm_kernel is host logic only: the large layer takes the 256 x 256 four-wavefront
     kernel for both GEMMs, the GPT-2-small layer the 128-row tiles of the general kernel."""
     big = wl.CONFIGS["large_chunked"]
     s = moe.Shape.make(big["T"], big["d"], big["E"], big["h"], big["k"], big["C"], dtype="bf16", act="gelu")
-    assert moe.moe_expert_gemm_kernel(s, 0) == "grouped_gemm_pp_kernel 256x256"
-    assert moe.moe_expert_gemm_kernel(s, 1) == "grouped_gemm_pp_kernel 256x256"
+    assert moe.moe_expert_gemm_kernel(s, 0) == "grouped_gemm_w4_kernel 256x256"
+    assert moe.moe_expert_gemm_kernel(s, 1) == "grouped_gemm_w4_kernel 256x256"
     small = wl.CONFIGS["gpt2s_moe"]
     s2 = moe.Shape.make(small["T"], small["d"], small["E"], small["h"], small["k"], small["C"], dtype="bf16", act="gelu")
     assert moe.moe_expert_gemm_kernel(s2, 0).startswith("grouped_gemm_mfma_kernel 128x")

@@ -184,8 +184,8 @@ def test_gate_ties_go_to_the_lowest_index(T, d, E, k):
                                           (320, 3072, "gelu_tanh", True)],
                          ids=["first_gemm_256_tiles", "second_gemm_256_tiles", "first_gemm_kept_preactivations"])
 def test_large_tile_kernel(d, h, act, keep):
-    """Shapes whose expert GEMMs take the 256 x 256 tile kernel (two wavefront groups half a
-    stage apart, tile stored through LDS) at sizes the oracle still finishes in seconds: ragged
+    """Shapes whose expert GEMMs take the 256 x 256 tile kernel (four wavefronts of 128 x 128,
+    accumulators in AGPRs, tile stored through LDS) at sizes the oracle still finishes in seconds: ragged
     row tiles, overflowing and near-empty experts (Zipf gate bias), FFN biases, and the variant
     that also keeps the pre-activations."""
     cfg = wl.scaled("skewed", T=8192, d=d, h=h, E=8, k=2, cf=1.1)
