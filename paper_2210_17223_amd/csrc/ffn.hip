@@ -671,21 +671,27 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_w4_kernel(
     for (int pass = KEEP ? 0 : 1; pass < 2; ++pass) {      // pass 0: pre-activations, 1: outputs
         _Float16 *out = pass == 0 ? Pre : C;
 #pragma unroll
-        for (int j = 0; j < TM; ++j)
+        for (int i = 0; i < TN; ++i)
 #pragma unroll
-            for (int i = 0; i < TN; ++i)
+            for (int g = 0; g < 4; ++g) {
+                const int col = i * 32 + 8 * g + 4 * (lane >> 5);
+                float b4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (bexp != nullptr) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int col = i * 32 + 8 * g + 4 * (lane >> 5);
+                    for (int c = 0; c < 4; ++c) b4[c] = bexp[min(n0 + wn * TN * 32 + col + c, N - 1)];
+                }
+#pragma unroll
+                for (int j = 0; j < TM; ++j) {
                     float v[4];
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
-                        float s = acc[i][j][4 * g + c];
-                        if (bexp != nullptr) s += bexp[min(n0 + wn * TN * 32 + col + c, N - 1)];
+                        const float s = acc[i][j][4 * g + c] + b4[c];
                         v[c] = pass == 0 ? s : activate<ACT, true>(s);
                     }
                     store4(reinterpret_cast<_Float16 *>(patch + (j * 32 + fr) * PITCH) + col, v);
                 }
+                MOE_SB();      // a few accumulator registers at a time leave the AGPRs
+            }
         MOE_LGKM0();
         __builtin_amdgcn_wave_barrier();
 #pragma unroll 8
