@@ -33,8 +33,8 @@ INFINITY_CACHE_BYTES = 256 << 20
 # The counters cannot be read from inside the process, so the figure is a stored
 # measurement, reported only for the workload and launch configuration it was taken on
 # (null for any other): {(workload, n_chunks): (FETCH_SIZE KiB, WRITE_SIZE KiB)} per launch.
-GEMM1_TRAFFIC_KIB = {("large_chunked", 1): (1560134.6, 1017952.0),     # profiles/layer_hbm_traffic_pmc.txt
-                     ("gpt2s_moe", 1): (69372.2, 50052.5)}
+GEMM1_TRAFFIC_KIB = {("large_chunked", 1): (1559144.2, 1017952.0),     # profiles/layer_hbm_traffic_pmc.txt
+                     ("gpt2s_moe", 1): (69506.5, 50068.6)}
 FETCH_UNIT, WRITE_UNIT = 2.0, 1.0     # what the plain-copy calibration reads per counted KiB
 
 
