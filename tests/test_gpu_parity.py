@@ -230,6 +230,28 @@ def test_large_tile_kernel(d, h, act, keep):
     assert not ye2[o.A * li.d:].any()
 
 
+@pytest.mark.parametrize("d,h,which", [(64, 4096, 0), (128, 4096, 0), (2048, 192, 1)],
+                         ids=["one_stage", "two_stages", "three_stages"])
+def test_large_tile_kernel_with_a_short_contraction(d, h, which):
+    """The 256 x 256 tile kernel keeps two stages of loads in flight and pairs its stages: a
+    contraction of one, two or three 64-deep stages (GEMM `which` of these layers) must still come
+    out right -- the loads past the last stage fetch the last stage again and are never used."""
+    cfg = wl.scaled("gpt2s_moe", T=16384, d=d, h=h, E=8, k=1 if which == 0 else 2, cf=1.0)
+    li = wl.make_layer(cfg, seed=33, threads=8)
+    s = shape_of(li)
+    assert moe.moe_expert_gemm_kernel(s, which).startswith("grouped_gemm_w4_kernel")
+    o = run_oracle(li)
+    L = DeviceLayer(li, s)
+    L.layer(1)
+    assert_ints_equal(L.ints(), o)
+    y = L.b["y"].cpu().numpy().reshape(li.T, li.d)
+    assert rel_rms_err(y, o.y) <= TOL["bf16"]
+    rows = np.arange(o.A, dtype=np.int32)
+    ye_ref = oracle.ffn_rows(o.xe, o.off, li.W1, li.W2, rows, "gelu", None, None)
+    ye = L.b["ye"].float().cpu().numpy().reshape(-1, li.d)
+    assert rel_rms_err(ye[:o.A], ye_ref) <= TOL["bf16"]
+
+
 def test_layer_is_bitwise_reproducible():
     # no floating-point atomics on the path: the same call gives the same bits, also when
     # the output buffers hold other values beforehand and other work ran in between
