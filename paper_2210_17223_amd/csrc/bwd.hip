@@ -31,6 +31,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
+#include "gemm_w4.h"
+
 constexpr int kBM = 128, kBK = 64, kLD = kBK + 8;
 // output tile 128 x (64 WN): WN = 2 (four wavefronts) or 4 (eight)
 constexpr size_t gemm_lds(int wn) { return 2 * (kBM + 64 * wn) * kLD * sizeof(uint16_t); }
@@ -300,6 +302,122 @@ __global__ __launch_bounds__(128 * WN, 2) void bwd_gemm_kernel(
                     for (int c = 0; c < 4; ++c) a[c] = v[c] * act_derivative<ACT>(static_cast<float>(p[c]));
                     store_bf16x4(static_cast<uint16_t *>(Cout) + at, a);
                 }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- GEMM, 256 x 256 tiles
+// The same three products on the forward's four-wavefront layout (gemm_w4.h), for layers whose
+// row GEMMs have enough 256 x 256 tiles to fill the chip.  The tile leaves through LDS as
+// whole lines (16-bit outputs) or straight from the registers (fp32); for EPI 2 the tile of
+// pre-activations comes in through the same LDS patch, as whole lines.
+template <int EPI, int ACT>
+__global__ __launch_bounds__(256, 1) void bwd_gemm_w4_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, void *__restrict__ Cout,
+    _Float16 *__restrict__ Pbuf, const WorkItem *__restrict__ items,
+    const int32_t *__restrict__ nitems, int N, int K)
+{
+    constexpr bool F16 = false;
+    constexpr int ABL = 0;
+    const int32_t *const row_src = nullptr;          // packed rows only
+    constexpr int row_div = 1, a_rows = 0;
+#include "gemm_w4_body.inc"
+
+    // acc[i][j][4*g + c]: column (wn*TN + i)*32 + 8*g + 4*(lane/32) + c, row (wm*TM + j)*32 +
+    // lane%32 of the tile.  Every wavefront is past its last LDS read after the barrier, the
+    // MFMA results have left the pipeline after the no-ops.
+    MOE_LGKM0();
+    MOE_BAR();
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    const int rbase = item.row0 + wm * TM * 32;
+    if constexpr (EPI == 0) {
+        float *out = static_cast<float *>(Cout);
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + (wn * TN + i) * 32 + 8 * g + 4 * (lane >> 5);
+#pragma unroll
+                for (int j = 0; j < TM; ++j) {
+                    const int r = rbase + j * 32 + fr;
+                    if (r < item.row1 && n < N)
+                        *reinterpret_cast<float4 *>(out + static_cast<size_t>(r) * N + n) =
+                            make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
+                                        acc[i][j][4 * g + 3]);
+                }
+                MOE_SB();      // a few accumulator registers at a time leave the AGPRs
+            }
+    } else {
+        constexpr int PITCH = 272;                   // the wavefront's 128 x 128 patch of 16-bit values
+        char *patch = reinterpret_cast<char *>(smem) + wave * (TM * 32) * PITCH;
+        const int ncol = n0 + wn * TN * 32 + (lane & 15) * 8;
+        // whole 256-byte row pieces between the patch and a [rows, N] matrix of 16-bit values
+        auto lines_out = [&](uint16_t *dst) {
+#pragma unroll 8
+            for (int it = 0; it < TM * 8; ++it) {
+                const int rr = it * 4 + (lane >> 4);
+                const u32x4 q = *reinterpret_cast<const u32x4 *>(patch + rr * PITCH + (lane & 15) * 16);
+                const int r = rbase + rr;
+                if (r < item.row1 && ncol < N)
+                    *reinterpret_cast<u32x4 *>(dst + static_cast<size_t>(r) * N + ncol) = q;
+            }
+        };
+        if constexpr (EPI == 2) {
+            const uint16_t *src = reinterpret_cast<const uint16_t *>(Pbuf);
+#pragma unroll 8
+            for (int it = 0; it < TM * 8; ++it) {
+                const int rr = it * 4 + (lane >> 4);
+                const int r = rbase + rr;
+                u32x4 q = {0u, 0u, 0u, 0u};
+                if (r < item.row1 && ncol < N)
+                    q = *reinterpret_cast<const u32x4 *>(src + static_cast<size_t>(r) * N + ncol);
+                *reinterpret_cast<u32x4 *>(patch + rr * PITCH + (lane & 15) * 16) = q;
+            }
+            MOE_LGKM0();
+            __builtin_amdgcn_wave_barrier();
+        }
+#pragma unroll
+        for (int pass = EPI == 1 ? 0 : 1; pass < 2; ++pass) {     // EPI 1, pass 0: the pre-activations
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int col = i * 32 + 8 * g + 4 * (lane >> 5);
+#pragma unroll
+                    for (int j = 0; j < TM; ++j) {
+                        char *at = patch + (j * 32 + fr) * PITCH + col * 2;
+                        float v[4];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) v[c] = acc[i][j][4 * g + c];
+                        if (EPI == 1 && pass == 0) {
+                            f16x4 p;
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) p[c] = static_cast<_Float16>(v[c]);
+                            *reinterpret_cast<f16x4 *>(at) = p;
+                        } else {
+                            float a[4];
+                            if constexpr (EPI == 1) {
+#pragma unroll
+                                for (int c = 0; c < 4; ++c) a[c] = act_value<ACT>(v[c]);
+                            } else {
+                                const f16x4 p = *reinterpret_cast<const f16x4 *>(at);
+#pragma unroll
+                                for (int c = 0; c < 4; ++c)
+                                    a[c] = v[c] * act_derivative<ACT>(static_cast<float>(p[c]));
+                            }
+                            store_bf16x4(reinterpret_cast<uint16_t *>(at), a);
+                        }
+                    }
+                    MOE_SB();
+                }
+            MOE_LGKM0();
+            __builtin_amdgcn_wave_barrier();
+            lines_out(EPI == 1 && pass == 0 ? reinterpret_cast<uint16_t *>(Pbuf)
+                                            : static_cast<uint16_t *>(Cout));
+            if (EPI == 1 && pass == 0) {
+                MOE_LGKM0();
+                __builtin_amdgcn_wave_barrier();
             }
         }
     }
@@ -708,16 +826,26 @@ struct BwdWorkspace {
     size_t bytes;
 };
 
-// 128-row tiles; 256 columns wide when the contraction is long enough to pay for the larger
-// tile's prologue (as in the forward), else 128
-GemmPlan plan128(int N, int K, int64_t max_rows, int E)
+// 256 x 256 tiles (the four-wavefront kernel) when there are enough of them to fill the chip,
+// as in the forward; else 128-row tiles, 256 columns wide when the contraction is long enough
+// to pay for the larger tile's prologue, else 128
+GemmPlan plan_rows(int N, int K, int64_t max_rows, int E)
 {
     GemmPlan gp;
-    gp.bm = kBM;
-    gp.bn = (K >= 2048 && N >= 256) ? 256 : 128;
-    gp.concurrent = gp.bn == 256 ? 32 : 64;
+    const int64_t big_tiles = (max_rows / 256 + E / 2) * ((N + 255) / 256);
+    const bool fits = K % 64 == 0 && static_cast<uint64_t>(N) * K * 2 < (1ull << 31) &&
+                      256ull * K * 2 < (1ull << 31);
+    if (big_tiles >= 768 && fits) {
+        gp.bm = 256;
+        gp.bn = 256;
+        gp.concurrent = 32;
+    } else {
+        gp.bm = kBM;
+        gp.bn = (K >= 2048 && N >= 256) ? 256 : 128;
+        gp.concurrent = gp.bn == 256 ? 32 : 64;
+    }
     gp.tiles_n = (N + gp.bn - 1) / gp.bn;
-    gp.max_row_tiles = static_cast<int32_t>((max_rows + kBM - 1) / kBM + E);
+    gp.max_row_tiles = static_cast<int32_t>((max_rows + gp.bm - 1) / gp.bm + E);
     gp.max_items = gp.max_row_tiles * gp.tiles_n;
     return gp;
 }
@@ -733,8 +861,8 @@ void layout_bwd(const moe_shape &s, void *base, BwdWorkspace *w)
         return at;
     };
     w->lists = Workspace{};
-    w->lists.gp[0] = plan128(s.d_ff, s.d_model, R, s.E);
-    w->lists.gp[1] = plan128(s.d_model, s.d_ff, R, s.E);
+    w->lists.gp[0] = plan_rows(s.d_ff, s.d_model, R, s.E);
+    w->lists.gp[1] = plan_rows(s.d_model, s.d_ff, R, s.E);
     for (int g = 0; g < 2; ++g) {      // one list per FFN group of a chunked backward pass
         w->lists.items[g] = reinterpret_cast<WorkItem *>(
             take(sizeof(WorkItem) * w->lists.gp[g].max_items * kMaxChunks));
@@ -779,12 +907,25 @@ void launch_gemm_k(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, c
 
 template <int EPI, int ACT>
 void launch_gemm(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, const WorkItem *items,
-                 const int32_t *nitems, int N, int K, int bn, int grid_items, int stage, hipStream_t st)
+                 const int32_t *nitems, int N, int K, const GemmPlan &gp, int stage, hipStream_t st)
 {
+    const int grid_items = gp.max_items;
+    if (gp.bm == 256) {
+        constexpr size_t lds = 2 * (256 + 256) * (64 + 8) * sizeof(uint16_t);
+        auto kern = bwd_gemm_w4_kernel<EPI, ACT>;
+        static PerDeviceOnce once;
+        once.raise_lds(reinterpret_cast<const void *>(kern), static_cast<int>(lds));
+        const int grid = static_cast<int>(align_up(static_cast<size_t>(grid_items), 8));
+        hipEvent_t t0, t1;
+        prof_kernel_events(stage, &t0, &t1);
+        hipExtLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, t0, t1, 0, A, W, C, P, items, nitems,
+                              N, K);
+        return;
+    }
 #define MOE_BWD_GEMM(KTAIL_, WN_)                                                                 \
     launch_gemm_k<EPI, ACT, KTAIL_, WN_>(A, W, C, P, items, nitems, N, K, grid_items, stage, st)
     const bool tail = K % kBK != 0;
-    if (bn == 256) {
+    if (gp.bn == 256) {
         if (tail) MOE_BWD_GEMM(true, 4); else MOE_BWD_GEMM(false, 4);
     } else {
         if (tail) MOE_BWD_GEMM(true, 2); else MOE_BWD_GEMM(false, 2);
@@ -888,14 +1029,14 @@ moe_status backward_t(const moe_shape &s, int n_chunks, const uint16_t *x, const
         const WorkItem *it1 = w.lists.items[1] + static_cast<size_t>(f) * g1.max_items;
         // P = xe W1 (fp16), Hb = act(P) (bf16) -- unless the forward kept P and its hidden activations
         if (pre == nullptr)
-            launch_gemm<1, ACT>(xe, W1p, w.Hb, w.P, it0, w.lists.nitems[0] + f, h, d, g0.bn, g0.max_items,
+            launch_gemm<1, ACT>(xe, W1p, w.Hb, w.P, it0, w.lists.nitems[0] + f, h, d, g0,
                                 kStageBwdRecompute, st);
         // dP = (dye W2^T) * act'(P): W2 [E][h][d] is already "rows n = h, contraction d contiguous"
-        launch_gemm<2, ACT>(w.dye, W2, w.dP, P, it0, w.lists.nitems[0] + f, h, d, g0.bn, g0.max_items,
+        launch_gemm<2, ACT>(w.dye, W2, w.dP, P, it0, w.lists.nitems[0] + f, h, d, g0,
                             kStageBwdDP, st);
         // dxe = dP W1^T: W1 [E][d][h] is "rows n = d, contraction h contiguous"
-        launch_gemm<0, ACT>(w.dP, W1, w.dxe, nullptr, it1, w.lists.nitems[1] + f, d, h, g1.bn,
-                            g1.max_items, kStageBwdDxe, st);
+        launch_gemm<0, ACT>(w.dP, W1, w.dxe, nullptr, it1, w.lists.nitems[1] + f, d, h, g1, kStageBwdDxe,
+                            st);
     };
     // dW2[e] [h][d] = act(P)^T dye ; dW1[e] [d][h] = xe^T dP, operands as they are
     auto weight_grads = [&]() {

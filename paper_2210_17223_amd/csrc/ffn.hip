@@ -380,45 +380,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void grouped_gemm_mfma_kernel(
     }
 }
 
-// ---------------------------------------------------------------- 256 x 256 GEMM, four wavefronts
-// The same product as grouped_gemm_mfma_kernel for 256 x 256 output tiles, fp16 output and a
-// contraction depth that is a multiple of 64, laid out for one wavefront per SIMD:
-//  * four wavefronts of 128 x 128 (2 x 2): every operand fragment read from LDS feeds four
-//    MFMAs (128 KB of LDS reads per 64-deep stage against 196 KB for eight wavefronts of
-//    128 x 64); the 16 accumulators of a wavefront (256 registers) are pinned to AGPRs, which
-//    leaves the 256 VGPRs to fragments and staging;
-//  * TWO stages of global loads in flight in registers (2 x 64 VGPRs) beside the double-buffered
-//    LDS tiles, through buffer loads whose per-lane byte offsets never change (the stage goes
-//    into the scalar offset): no address arithmetic in the loop;
-//  * one barrier per stage, and every memory instruction of a stage (32 LDS fragment reads,
-//    16 LDS writes, 16 global loads per wavefront) issued singly between two MFMAs in a fixed
-//    order: fragment reads one 16-deep step ahead, the LDS writes of the next stage spread
-//    over the first three steps (all before the barrier), a register reloaded after it was
-//    written.  The MFMAs are inline assembly so that the accumulators stay in AGPRs and the
-//    order holds; nothing depends on an MFMA result before the loop ends.
-//  * The tile leaves through LDS: every wavefront writes its 128 x 128 sub-tile to a patch of
-//    its own and stores it as whole lines, 16 bytes per lane.
-// Loads past the last stage fetch the last stage again (never used) instead of branching.
-// Operand addresses are 32-bit byte offsets into two buffer resources (the tile's rows, or
-// the whole token matrix when the rows are gathered through row_src; the expert's weight
-// matrix), which the host checks fit.
-#define MOE_LGKM0() asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")
-#define MOE_SB() __builtin_amdgcn_sched_barrier(0)
-#define MOE_BAR()                                                                                 \
-    do {                                                                                         \
-        MOE_SB();                                                                                \
-        __builtin_amdgcn_s_barrier();                                                            \
-        MOE_SB();                                                                                \
-    } while (0)
-
-template <bool F16>
-__device__ __forceinline__ void mfma_32x32x16_agpr(f32x16 &acc, const u32x4 &a, const u32x4 &b)
-{
-    if constexpr (F16)
-        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-    else
-        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
+#include "gemm_w4.h"
 
 // ABL (measurement only, 0 in the layer): bit 0 leaves out the MFMAs, bit 1 the LDS fragment
 // reads after the first step, bit 2 the global loads and LDS writes inside the loop, bit 3 the
@@ -430,229 +392,7 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_w4_kernel(
     const WorkItem *__restrict__ items, const int32_t *__restrict__ nitems, int N, int K,
     const int32_t *__restrict__ row_src, int row_div, int a_rows)
 {
-    constexpr int TM = 4, TN = 4;                    // 2 x 2 wavefronts of 128 x 128 each
-    constexpr int BM = 256, BN = 256, BK = 64, LD = BK + 8, NT = 256, NV = 8, PD = 2;
-    const int total = *nitems;
-    const int per_xcd = (total + 7) / 8;
-    const int slot = blockIdx.x / 8;
-    const int item_idx = (blockIdx.x % 8) * per_xcd + slot;
-    if (slot >= per_xcd || item_idx >= total) return;
-    const WorkItem item = items[item_idx];
-    const int n0 = item.n0;
-    const int rows = item.row1 - item.row0;
-
-    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    constexpr int A_BUF = BM * LD, W_BUF = BN * LD;
-    uint16_t *As = smem;               // [2][BM][LD]
-    uint16_t *Ws = smem + 2 * A_BUF;   // [2][BN][LD]
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave & 1, wn = wave >> 1;
-    const uint16_t *Wexp = W + static_cast<size_t>(item.expert) * N * K;
-    // gathered rows are offsets from A itself, packed rows from the tile's first row
-    const uint16_t *Abase = row_src != nullptr ? A : A + static_cast<size_t>(item.row0) * K;
-    const unsigned a_bytes = static_cast<unsigned>(row_src != nullptr ? a_rows : rows) *
-                             static_cast<unsigned>(K) * 2u;
-    const __amdgpu_buffer_rsrc_t rsa =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(Abase), 0, a_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsw = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t *>(Wexp), 0, static_cast<unsigned>(N) * static_cast<unsigned>(K) * 2u,
-        0x00020000);
-
-    int a_src[NV], w_src[NV];          // byte offsets of vector q: row (tid + 256 q) / 8, 16-byte piece tid % 8
-    const int ld_col = (tid & 7) * 8;
-    const int off0 = (tid >> 3) * LD + ld_col;       // LDS place of vector q: off0 + q * 32 * LD
-#pragma unroll
-    for (int q = 0; q < NV; ++q) {
-        const int r = min((tid + NT * q) >> 3, rows - 1);
-        const int arow = row_src != nullptr ? row_src[item.row0 + r] / row_div : r;
-        a_src[q] = (arow * K + ld_col) * 2;
-    }
-#pragma unroll
-    for (int q = 0; q < NV; ++q) {
-        const int r = (tid + NT * q) >> 3;
-        w_src[q] = (min(n0 + r, N - 1) * K + ld_col) * 2;
-    }
-
-    f32x16 acc[TN][TM];
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    u32x4 ra[PD][NV], rw[PD][NV];      // PD stages of operands on their way to LDS
-    u32x4 wf[2][TN], af[2][TM];
-    const int KT = K / BK;
-    const int fr = lane & 31, fk = (lane >> 5) * 8;
-    const int wfrag = (wn * TN * 32 + fr) * LD + fk;
-    const int afrag = (wm * TM * 32 + fr) * LD + fk;
-
-#define MOE_LDA(set, q, kt_)                                                                      \
-    ra[set][q] = __builtin_bit_cast(                                                             \
-        u32x4, __builtin_amdgcn_raw_buffer_load_b128(rsa, a_src[q], (kt_) * (BK * 2), 0))
-#define MOE_LDW(set, q, kt_)                                                                      \
-    rw[set][q] = __builtin_bit_cast(                                                             \
-        u32x4, __builtin_amdgcn_raw_buffer_load_b128(rsw, w_src[q], (kt_) * (BK * 2), 0))
-#define MOE_STA(set, q, buf)                                                                      \
-    *reinterpret_cast<u32x4 *>(As + (buf) * A_BUF + off0 + (q) * 32 * LD) = ra[set][q]
-#define MOE_STW(set, q, buf)                                                                      \
-    *reinterpret_cast<u32x4 *>(Ws + (buf) * W_BUF + off0 + (q) * 32 * LD) = rw[set][q]
-#define MOE_RDW(slot_, i, buf, ks)                                                                \
-    wf[slot_][i] = *reinterpret_cast<const u32x4 *>(Ws + (buf) * W_BUF + wfrag + (i) * 32 * LD + (ks) * 16)
-#define MOE_RDA(slot_, j, buf, ks)                                                                \
-    af[slot_][j] = *reinterpret_cast<const u32x4 *>(As + (buf) * A_BUF + afrag + (j) * 32 * LD + (ks) * 16)
-// LDS write / global load number v of a stage: the A rows for v < 8, the weight rows above
-#define MOE_WR(set, v, buf)                                                                       \
-    do {                                                                                         \
-        if constexpr (!(ABL & 4)) {                                                              \
-            if constexpr ((v) < 8) MOE_STA(set, (v), buf); else MOE_STW(set, (v) - 8, buf);       \
-        }                                                                                        \
-    } while (0)
-#define MOE_LD(set, v, kt_)                                                                       \
-    do {                                                                                         \
-        if constexpr (!(ABL & 4)) {                                                              \
-            if constexpr ((v) < 8) MOE_LDA(set, (v), kt_); else MOE_LDW(set, (v) - 8, kt_);       \
-        }                                                                                        \
-    } while (0)
-#define MOE_RD(slot_, v, buf, ks)                                                                 \
-    do {                                                                                         \
-        if constexpr (!(ABL & 2)) {                                                              \
-            if constexpr ((v) < 4) MOE_RDW(slot_, (v), buf, ks); else MOE_RDA(slot_, (v) - 4, buf, ks); \
-        }                                                                                        \
-    } while (0)
-// MFMA m of a 16-deep step: row sub-tile m / 4, column sub-tile m % 4
-#define MOE_MM(slot_, m)                                                                          \
-    do {                                                                                         \
-        constexpr int i_ = (m) & 3, j_ = (m) >> 2;                                               \
-        if constexpr (!(ABL & 1))                                                                \
-            mfma_32x32x16_agpr<F16>(acc[i_][j_], wf[slot_][i_], af[slot_][j_]);                  \
-    } while (0)
-#define MOE_PAIR(slot_, m, F)                                                                     \
-    MOE_MM(slot_, m);                                                                            \
-    F(std::integral_constant<int, (m)>{});                                                       \
-    MOE_SB();
-#define MOE_KSTEP(slot_, F)                                                                       \
-    {                                                                                            \
-        MOE_PAIR(slot_, 0, F) MOE_PAIR(slot_, 1, F) MOE_PAIR(slot_, 2, F) MOE_PAIR(slot_, 3, F)   \
-        MOE_PAIR(slot_, 4, F) MOE_PAIR(slot_, 5, F) MOE_PAIR(slot_, 6, F) MOE_PAIR(slot_, 7, F)   \
-        MOE_PAIR(slot_, 8, F) MOE_PAIR(slot_, 9, F) MOE_PAIR(slot_, 10, F) MOE_PAIR(slot_, 11, F) \
-        MOE_PAIR(slot_, 12, F) MOE_PAIR(slot_, 13, F) MOE_PAIR(slot_, 14, F) MOE_PAIR(slot_, 15, F) \
-    }
-// Stage kt: LDS buffer kt & 1 is multiplied; register set SET (stage kt + 1) goes to the other
-// buffer and is refilled with stage kt + 1 + PD; the fragments of step 0 are already in slot 0.
-// Memory instruction m of a step follows MFMA m: eight fragment reads, then LDS writes 6 / 5 / 5
-// (steps 0, 1, 2) and global loads 2 / 3 / 3 / 8.
-#define MOE_W4_STAGE(kt_, SET)                                                                    \
-    {                                                                                            \
-        const int kt = (kt_);                                                                    \
-        const int buf = kt & 1;                                                                  \
-        const int ktl = min(kt + 1 + PD, KT - 1);                                                \
-        {                                                                                        \
-            auto mem0 = [&](auto mc) {                                                           \
-                constexpr int m = decltype(mc)::value;                                           \
-                if constexpr (m < 8) MOE_RD(1, m, buf, 1);                                       \
-                else if constexpr (m < 14) MOE_WR(SET, m - 8, buf ^ 1);                          \
-                else MOE_LD(SET, m - 14, ktl);                                                   \
-            };                                                                                   \
-            MOE_KSTEP(0, mem0)                                                                   \
-        }                                                                                        \
-        {                                                                                        \
-            auto mem1 = [&](auto mc) {                                                           \
-                constexpr int m = decltype(mc)::value;                                           \
-                if constexpr (m < 8) MOE_RD(0, m, buf, 2);                                       \
-                else if constexpr (m < 13) MOE_WR(SET, m - 8 + 6, buf ^ 1);                      \
-                else MOE_LD(SET, m - 13 + 2, ktl);                                               \
-            };                                                                                   \
-            MOE_KSTEP(1, mem1)                                                                   \
-        }                                                                                        \
-        {                                                                                        \
-            auto mem2 = [&](auto mc) {                                                           \
-                constexpr int m = decltype(mc)::value;                                           \
-                if constexpr (m < 8) MOE_RD(1, m, buf, 3);                                       \
-                else if constexpr (m < 13) MOE_WR(SET, m - 8 + 11, buf ^ 1);                     \
-                else MOE_LD(SET, m - 13 + 5, ktl);                                               \
-            };                                                                                   \
-            MOE_KSTEP(0, mem2)                                                                   \
-        }                                                                                        \
-        MOE_LGKM0();                                                                             \
-        MOE_BAR();                                                                               \
-        {                                                                                        \
-            auto mem3 = [&](auto mc) {                                                           \
-                constexpr int m = decltype(mc)::value;                                           \
-                if constexpr (m < 8) MOE_RD(0, m, buf ^ 1, 0);                                   \
-                else MOE_LD(SET, m, ktl);                                                        \
-            };                                                                                   \
-            MOE_KSTEP(1, mem3)                                                                   \
-        }                                                                                        \
-    }
-#define MOE_W4_STAGES                                                                             \
-    {                                                                                            \
-        int k2 = 0;                                                                              \
-        for (; k2 + 1 < KT; k2 += 2) {                                                           \
-            MOE_W4_STAGE(k2, 1)                                                                  \
-            MOE_W4_STAGE(k2 + 1, 0)                                                              \
-        }                                                                                        \
-        if (k2 < KT) MOE_W4_STAGE(k2, 1)                                                         \
-    }
-
-    // prologue: stage 0 through set 0 into LDS buffer 0, stage 1 in set 1, stage 2 in set 0
-    {
-        const int k1 = min(1, KT - 1), k2 = min(2, KT - 1);
-#pragma unroll
-        for (int q = 0; q < NV; ++q) {
-            MOE_LDA(0, q, 0);
-            MOE_LDW(0, q, 0);
-        }
-#pragma unroll
-        for (int q = 0; q < NV; ++q) {
-            MOE_LDA(1, q, k1);
-            MOE_LDW(1, q, k1);
-        }
-#pragma unroll
-        for (int q = 0; q < NV; ++q) {
-            MOE_STA(0, q, 0);
-            MOE_STW(0, q, 0);
-        }
-#pragma unroll
-        for (int q = 0; q < NV; ++q) {
-            MOE_LDA(0, q, k2);
-            MOE_LDW(0, q, k2);
-        }
-    }
-    MOE_LGKM0();
-    MOE_BAR();
-#pragma unroll
-    for (int i = 0; i < TN; ++i) {
-        MOE_RDW(0, i, 0, 0);
-        MOE_RDW(1, i, 0, 1);
-    }
-#pragma unroll
-    for (int j = 0; j < TM; ++j) {
-        MOE_RDA(0, j, 0, 0);
-        MOE_RDA(1, j, 0, 1);
-    }
-    // Every wavefront multiplies all four of its row sub-tiles: sub-tiles past the tile's end
-    // hold clamped rows whose results are never stored, and the tile's time is set by its
-    // fullest wavefront either way.  (Branches around the MFMAs, or a second copy of the loop
-    // without them, make the compiler move accumulators out of the AGPRs inside the loop.)
-    MOE_W4_STAGES
-#undef MOE_W4_STAGES
-#undef MOE_W4_STAGE
-#undef MOE_KSTEP
-#undef MOE_PAIR
-#undef MOE_MM
-#undef MOE_RD
-#undef MOE_LD
-#undef MOE_WR
-#undef MOE_RDA
-#undef MOE_RDW
-#undef MOE_STW
-#undef MOE_STA
-#undef MOE_LDW
-#undef MOE_LDA
+#include "gemm_w4_body.inc"
 
     // Epilogue.  acc[i][j][4*g + c]: column (wn*TN + i)*32 + 8*g + 4*(lane/32) + c, row
     // (wm*TM + j)*32 + lane%32 of the tile.  Every wavefront is past its last LDS read after

@@ -183,13 +183,15 @@ def test_backward_at_the_bench_configuration():
         assert rel_rms_err(dW2[e], o.dW2[e]) <= tol, e
 
 
-@pytest.mark.parametrize("name,n_chunks", [("skewed", 4), ("large_chunked", 1)])
-def test_backward_at_full_size_sampled_experts(name, n_chunks):
+@pytest.mark.parametrize("name,n_chunks,keep", [("skewed", 4, True), ("skewed", 1, False), ("large_chunked", 1, True)],
+                         ids=["skewed-4", "skewed-recompute", "large_chunked-1"])
+def test_backward_at_full_size_sampled_experts(name, n_chunks, keep):
     """Forward (keeping its pre-activations) + backward of configurations 3 and 4 at full size
     against the backward oracle: dx, dgate and dWg in full (every token), dW1 / dW2 for a sample
     of experts -- the fullest, the emptiest, and four in between -- since the oracle holds each
     expert's weight gradient in fp64.  Configuration 3 runs the chunked backward pass with two
-    groups of GEMMs per pass."""
+    groups of GEMMs per pass, and once more without the kept buffers (the backward pass then
+    computes the pre-activations again, with the 256 x 256 tile kernel at this size)."""
     from oracle import bwd_oracle as bo
     li = wl.make_layer(wl.CONFIGS[name], seed=0, threads=16)
     T, d, E, h, k = li.T, li.d, li.E, li.h, li.k
@@ -197,11 +199,15 @@ def test_backward_at_full_size_sampled_experts(name, n_chunks):
     L = DeviceLayer(li, s)
     b = L.b
     dev = "cuda:0"
-    pre = torch.empty(moe.moe_max_rows(s) * h, dtype=torch.float16, device=dev)
-    hid = torch.empty_like(pre)
-    moe.moe_layer_forward_keep(s, L.x, b["Wgp"], L.bias, L.bias_stride, b["W1p"], None, b["W2p"], None,
-                               b["expert_idx"], b["gate"], b["counts"], b["offsets"], b["slot_of"],
-                               b["src_of"], b["xe"], b["ye"], pre, hid, b["y"], b["workspace"])
+    pre = hid = None
+    if keep:
+        pre = torch.empty(moe.moe_max_rows(s) * h, dtype=torch.float16, device=dev)
+        hid = torch.empty_like(pre)
+        moe.moe_layer_forward_keep(s, L.x, b["Wgp"], L.bias, L.bias_stride, b["W1p"], None, b["W2p"], None,
+                                   b["expert_idx"], b["gate"], b["counts"], b["offsets"], b["slot_of"],
+                                   b["src_of"], b["xe"], b["ye"], pre, hid, b["y"], b["workspace"])
+    else:
+        L.layer(1)
     dy = np.random.Generator(np.random.PCG64(31)).standard_normal((T, d)).astype(np.float32)
     W1, W2 = upload(li.W1, "bf16"), upload(li.W2, "bf16")
     f32 = lambda n: torch.full((n,), 3.0, dtype=torch.float32, device=dev)
