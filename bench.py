@@ -266,7 +266,7 @@ def main() -> int:
         # dW2[e] = act(P)^T dye: reads both operands once, writes fp32 dW2
         g1_bytes = A * l0.h * 2 + A * l0.d * 2 + l0.E * l0.d * l0.h * 4
         g1_gbps = g1_bytes / (g1_avg_ms * 1e-3) / 1e9
-    roof = {"kernel": ("wgrad_gemm_kernel (dW2 = act(P)^T dye)" if args.backward else
+    roof = {"kernel": ("weight-gradient GEMM dW2 = act(P)^T dye (wgrad_w4_kernel where 256 x 256 tiles fill the chip, else wgrad_gemm_kernel)" if args.backward else
                        moe.moe_expert_gemm_kernel(s, 0) + " <bf16 in, fp16 out, GeLU> (first expert GEMM)"
                        if bf16 else "grouped_gemm_f32_kernel (first expert GEMM)"),
             "avg_launch_us": g1_avg_ms * 1e3, "launches": int(g1_ms.size),

@@ -641,6 +641,266 @@ __global__ __launch_bounds__(256, 2) void wgrad_gemm_kernel(
     }
 }
 
+// ---------------------------------------------------------------- weight gradient, 256 x 256 tiles
+// The same product on the four-wavefront layout of gemm_w4.h, for layers whose weight
+// gradients have enough 256 x 256 tiles: four wavefronts of 128 x 128 with their accumulators in
+// AGPRs, two 64-row stages of buffer loads in flight in registers, double-buffered LDS stages
+// [64 rows][256 columns] per operand (64-byte pieces XOR-swizzled with the row, as above), the
+// MFMA fragments through the transposing LDS read, every memory instruction issued between
+// MFMAs in a fixed order.  The operands' buffer resources end with the expert's last row, so
+// rows past it -- and whole stages past the last one -- read as zeros: no clamping, no tail
+// code.  M and N are multiples of 256 (the host checks).
+template <bool AF16>
+__global__ __launch_bounds__(256, 1) void wgrad_w4_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, float *__restrict__ C,
+    const int32_t *__restrict__ offsets, int E, int M, int N, int tiles_m, int tiles_n)
+{
+    constexpr int TM = 4, TN = 4, NV = 8;
+    constexpr int kRow = 512;                     // bytes of a 256-column LDS row
+    constexpr int kOp = 64 * kRow;                // bytes of one operand's stage
+    int expert, m0, n0;
+    {
+        const int total = E * tiles_m * tiles_n;
+        const int per_xcd = (total + 7) / 8;
+        const int slot = blockIdx.x / 8;
+        const int idx = (blockIdx.x % 8) * per_xcd + slot;
+        if (slot >= per_xcd || idx >= total) return;
+        expert = idx / (tiles_m * tiles_n);
+        const int rem = idx % (tiles_m * tiles_n);
+        m0 = (rem / tiles_n) * 256;
+        n0 = (rem % tiles_n) * 256;
+    }
+    const int r0 = offsets[expert], r1 = offsets[expert + 1];
+    const int KT = (r1 - r0 + 63) / 64;
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    char *lds = reinterpret_cast<char *>(smem);   // A stages at 0 and kOp, B stages at 2 kOp and 3 kOp
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    if (KT > 0) {
+        // an operand's resource: from the tile's first column of the expert's first row to the end
+        // of the expert's last row
+        const unsigned rows = static_cast<unsigned>(r1 - r0);
+        const __amdgpu_buffer_rsrc_t rsa = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>(A + static_cast<size_t>(r0) * M + m0), 0,
+            (rows * static_cast<unsigned>(M) - static_cast<unsigned>(m0)) * 2u, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rsb = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>(B + static_cast<size_t>(r0) * N + n0), 0,
+            (rows * static_cast<unsigned>(N) - static_cast<unsigned>(n0)) * 2u, 0x00020000);
+        // staging: vector q of a stage is row tid / 32 + 8 q, 16-byte piece tid % 32 of the row
+        const int srow = tid >> 5, piece = tid & 31;
+        const int a_voff = (srow * M + piece * 8) * 2, b_voff = (srow * N + piece * 8) * 2;
+        const int a_rowstep = 8 * M * 2, b_rowstep = 8 * N * 2;       // vector q -> q + 1
+        const int a_stage = 64 * M * 2, b_stage = 64 * N * 2;         // stage kt -> kt + 1
+        const int st_off = srow * kRow + (((piece >> 2) ^ (srow & 3)) << 6) + ((piece & 3) << 4);
+        // fragments: lane = 16 g + i reads row 8 (g / 2) + i / 4 (+ 4 for the upper half) of the
+        // 16-row step, columns 16 (g % 2) + 4 (i % 4) .. + 3 of the 32-column sub-tile t, whose
+        // 64-byte piece sits at (t ^ swizzle) inside the wavefront's 256-byte half of the row
+        const int fi = lane & 15, fg = lane >> 4;
+        const int frow = 8 * (fg >> 1) + (fi >> 2), fcol = 16 * (fg & 1) + 4 * (fi & 3), fswz = fi >> 2;
+        int a_fr[TM], b_fr[TN];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            a_fr[t] = frow * kRow + wm * 256 + ((t ^ fswz) << 6) + fcol * 2;
+            b_fr[t] = 2 * kOp + frow * kRow + wn * 256 + ((t ^ fswz) << 6) + fcol * 2;
+        }
+        u32x4 ra[2][NV], rb[2][NV];
+        u32x4 bf[2][TN], af[2][TM];
+// (the whole offset goes into the per-lane operand: the range check that turns rows past the
+// expert's end into zeros does not see the scalar offset)
+#define WG4_LDA(set, q, kt_)                                                                      \
+    ra[set][q] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(                \
+                                               rsa, a_voff + ((kt_) * a_stage + (q) * a_rowstep), 0, 0))
+#define WG4_LDB(set, q, kt_)                                                                      \
+    rb[set][q] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(                \
+                                               rsb, b_voff + ((kt_) * b_stage + (q) * b_rowstep), 0, 0))
+#define WG4_STA(set, q, buf)                                                                      \
+    {                                                                                            \
+        u32x4 av_ = ra[set][q];                                                                  \
+        if constexpr (AF16)                                                                      \
+            av_ = (u32x4){f16x2_to_bf16x2(av_[0]), f16x2_to_bf16x2(av_[1]),                      \
+                          f16x2_to_bf16x2(av_[2]), f16x2_to_bf16x2(av_[3])};                     \
+        *reinterpret_cast<u32x4 *>(lds + (buf) * kOp + st_off + (q) * 8 * kRow) = av_;           \
+    }
+#define WG4_STB(set, q, buf)                                                                      \
+    *reinterpret_cast<u32x4 *>(lds + (2 + (buf)) * kOp + st_off + (q) * 8 * kRow) = rb[set][q]
+// half h (0: rows k .. k + 3, 1: rows k + 4 .. k + 7 of the lane's eight) of fragment t, step ks
+#define WG4_RDA(slot_, t, h, buf, ks)                                                             \
+    {                                                                                            \
+        const u32x2 v_ = lds_read_tr16(reinterpret_cast<const uint16_t *>(                      \
+            lds + a_fr[t] + (buf) * kOp + (ks) * 16 * kRow + (h) * 4 * kRow));                   \
+        af[slot_][t][2 * (h)] = v_[0];                                                           \
+        af[slot_][t][2 * (h) + 1] = v_[1];                                                       \
+    }
+#define WG4_RDB(slot_, t, h, buf, ks)                                                             \
+    {                                                                                            \
+        const u32x2 v_ = lds_read_tr16(reinterpret_cast<const uint16_t *>(                      \
+            lds + b_fr[t] + (buf) * kOp + (ks) * 16 * kRow + (h) * 4 * kRow));                   \
+        bf[slot_][t][2 * (h)] = v_[0];                                                           \
+        bf[slot_][t][2 * (h) + 1] = v_[1];                                                       \
+    }
+// read v (0 .. 15) of a step: B fragments first (v < 8), halves interleaved
+#define WG4_RD(slot_, v, buf, ks)                                                                 \
+    do {                                                                                         \
+        if constexpr ((v) < 8) WG4_RDB(slot_, (v) >> 1, (v) & 1, buf, ks)                        \
+        else WG4_RDA(slot_, ((v) - 8) >> 1, (v) & 1, buf, ks)                                    \
+    } while (0)
+#define WG4_WR(set, v, buf)                                                                       \
+    do {                                                                                         \
+        if constexpr ((v) < 8) WG4_STA(set, (v), buf) else WG4_STB(set, (v) - 8, buf);           \
+    } while (0)
+#define WG4_LD(set, v, kt_)                                                                       \
+    do {                                                                                         \
+        if constexpr ((v) < 8) WG4_LDA(set, (v), kt_); else WG4_LDB(set, (v) - 8, kt_);          \
+    } while (0)
+#define WG4_MM(slot_, m)                                                                          \
+    do {                                                                                         \
+        constexpr int i_ = (m) & 3, j_ = (m) >> 2;                                               \
+        mfma_32x32x16_agpr<false>(acc[i_][j_], bf[slot_][i_], af[slot_][j_]);                    \
+    } while (0)
+// MFMA m, the fragment read m of the next step, and after every second MFMA one of the eight
+// write / load instructions of the step
+#define WG4_PAIR(slot_, m, F)                                                                     \
+    WG4_MM(slot_, m);                                                                            \
+    F(std::integral_constant<int, (m)>{});                                                       \
+    if constexpr (((m) & 1) != 0) F(std::integral_constant<int, 16 + ((m) >> 1)>{});             \
+    MOE_SB();
+#define WG4_KSTEP(slot_, F)                                                                       \
+    {                                                                                            \
+        WG4_PAIR(slot_, 0, F) WG4_PAIR(slot_, 1, F) WG4_PAIR(slot_, 2, F) WG4_PAIR(slot_, 3, F)   \
+        WG4_PAIR(slot_, 4, F) WG4_PAIR(slot_, 5, F) WG4_PAIR(slot_, 6, F) WG4_PAIR(slot_, 7, F)   \
+        WG4_PAIR(slot_, 8, F) WG4_PAIR(slot_, 9, F) WG4_PAIR(slot_, 10, F) WG4_PAIR(slot_, 11, F) \
+        WG4_PAIR(slot_, 12, F) WG4_PAIR(slot_, 13, F) WG4_PAIR(slot_, 14, F) WG4_PAIR(slot_, 15, F) \
+    }
+// Stage kt from LDS buffer kt & 1; register set SET (stage kt + 1) goes to the other buffer
+// (writes 6 / 5 / 5 over steps 0 .. 2) and is refilled with stage kt + 3 (loads 2 / 3 / 3 / 8).
+#define WG4_STAGE(kt_, SET)                                                                       \
+    {                                                                                            \
+        const int kt = (kt_);                                                                    \
+        const int buf = kt & 1;                                                                  \
+        {                                                                                        \
+            auto mem0 = [&](auto mc) {                                                           \
+                constexpr int m = decltype(mc)::value;                                           \
+                if constexpr (m < 16) WG4_RD(1, m, buf, 1);                                      \
+                else if constexpr (m < 22) WG4_WR(SET, m - 16, buf ^ 1);                         \
+                else WG4_LD(SET, m - 22, kt + 3);                                                \
+            };                                                                                   \
+            WG4_KSTEP(0, mem0)                                                                   \
+        }                                                                                        \
+        {                                                                                        \
+            auto mem1 = [&](auto mc) {                                                           \
+                constexpr int m = decltype(mc)::value;                                           \
+                if constexpr (m < 16) WG4_RD(0, m, buf, 2);                                      \
+                else if constexpr (m < 21) WG4_WR(SET, m - 16 + 6, buf ^ 1);                     \
+                else WG4_LD(SET, m - 21 + 2, kt + 3);                                            \
+            };                                                                                   \
+            WG4_KSTEP(1, mem1)                                                                   \
+        }                                                                                        \
+        {                                                                                        \
+            auto mem2 = [&](auto mc) {                                                           \
+                constexpr int m = decltype(mc)::value;                                           \
+                if constexpr (m < 16) WG4_RD(1, m, buf, 3);                                      \
+                else if constexpr (m < 21) WG4_WR(SET, m - 16 + 11, buf ^ 1);                    \
+                else WG4_LD(SET, m - 21 + 5, kt + 3);                                            \
+            };                                                                                   \
+            WG4_KSTEP(0, mem2)                                                                   \
+        }                                                                                        \
+        MOE_LGKM0();                                                                             \
+        MOE_BAR();                                                                               \
+        {                                                                                        \
+            auto mem3 = [&](auto mc) {                                                           \
+                constexpr int m = decltype(mc)::value;                                           \
+                if constexpr (m < 16) WG4_RD(0, m, buf ^ 1, 0);                                  \
+                else WG4_LD(SET, m - 16 + 8, kt + 3);                                            \
+            };                                                                                   \
+            WG4_KSTEP(1, mem3)                                                                   \
+        }                                                                                        \
+    }
+        // prologue: stage 0 through set 0 into LDS buffer 0, stage 1 in set 1, stage 2 in set 0
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            WG4_LDA(0, q, 0);
+            WG4_LDB(0, q, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            WG4_LDA(1, q, 1);
+            WG4_LDB(1, q, 1);
+        }
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            WG4_STA(0, q, 0)
+            WG4_STB(0, q, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            WG4_LDA(0, q, 2);
+            WG4_LDB(0, q, 2);
+        }
+        MOE_LGKM0();
+        MOE_BAR();
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            WG4_RDB(0, t, 0, 0, 0)
+            WG4_RDB(0, t, 1, 0, 0)
+            WG4_RDA(0, t, 0, 0, 0)
+            WG4_RDA(0, t, 1, 0, 0)
+        }
+        {
+            int k2 = 0;
+            for (; k2 + 1 < KT; k2 += 2) {
+                WG4_STAGE(k2, 1)
+                WG4_STAGE(k2 + 1, 0)
+            }
+            if (k2 < KT) WG4_STAGE(k2, 1)
+        }
+#undef WG4_STAGE
+#undef WG4_KSTEP
+#undef WG4_PAIR
+#undef WG4_MM
+#undef WG4_LD
+#undef WG4_WR
+#undef WG4_RD
+#undef WG4_RDB
+#undef WG4_RDA
+#undef WG4_STB
+#undef WG4_STA
+#undef WG4_LDB
+#undef WG4_LDA
+        MOE_LGKM0();
+        MOE_BAR();
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    }
+
+    // acc[i][j][4*g + c]: column n0 + (wn*TN + i)*32 + 8*g + 4*(lane/32) + c,
+    //                     row m0 + (wm*TM + j)*32 + lane%32
+    float *Ce = C + static_cast<size_t>(expert) * M * N;
+    const int fr = lane & 31;
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int n = n0 + (wn * TN + i) * 32 + 8 * g + 4 * (lane >> 5);
+#pragma unroll
+            for (int j = 0; j < TM; ++j) {
+                const int m = m0 + (wm * TM + j) * 32 + fr;
+                *reinterpret_cast<float4 *>(Ce + static_cast<size_t>(m) * N + n) =
+                    make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
+                                acc[i][j][4 * g + 3]);
+            }
+            MOE_SB();      // a few accumulator registers at a time leave the AGPRs
+        }
+}
+
 // ---------------------------------------------------------------- gate backward
 // One wavefront per token.  Logits: lane = four consecutive columns of the model dimension,
 // EP partial sums per lane (Wgp is the forward's packed gate matrix, fp32 [EP][dP],
@@ -936,15 +1196,31 @@ void launch_gemm(const uint16_t *A, const uint16_t *W, void *C, _Float16 *P, con
 // dW[e] [M][N] = A[rows of e]^T B[rows of e] from row-major operands
 template <bool AF16>
 void launch_wgrad(const uint16_t *A, const uint16_t *B, float *C, const int32_t *offsets, int E, int M,
-                  int N, int stage, hipStream_t st)
+                  int N, int64_t max_rows, int stage, hipStream_t st)
 {
+    hipEvent_t t0, t1;
+    // 256 x 256 tiles on four wavefronts when they divide the matrix, fill the chip, and the
+    // buffer offsets (an expert's rows times the row length, in bytes) stay below 2^31
+    const uint64_t span = static_cast<uint64_t>(max_rows + 192) * static_cast<uint64_t>(std::max(M, N)) * 2;
+    if (M % 256 == 0 && N % 256 == 0 && static_cast<int64_t>(E) * (M / 256) * (N / 256) >= 768 &&
+        span < (1ull << 31)) {
+        constexpr size_t kLds4 = 4 * 64 * 512;
+        auto kern = wgrad_w4_kernel<AF16>;
+        static PerDeviceOnce once;
+        once.raise_lds(reinterpret_cast<const void *>(kern), static_cast<int>(kLds4));
+        const int tiles_m = M / 256, tiles_n = N / 256;
+        const int grid = static_cast<int>(align_up(static_cast<size_t>(E) * tiles_m * tiles_n, 8));
+        prof_kernel_events(stage, &t0, &t1);
+        hipExtLaunchKernelGGL(kern, dim3(grid), dim3(256), kLds4, st, t0, t1, 0, A, B, C, offsets, E, M,
+                              N, tiles_m, tiles_n);
+        return;
+    }
     constexpr size_t kLds = 2 * 2 * kBK * 128 * sizeof(uint16_t);
     auto kern = wgrad_gemm_kernel<AF16>;
     static PerDeviceOnce once;
     once.raise_lds(reinterpret_cast<const void *>(kern), static_cast<int>(kLds));
     const int tiles_m = (M + 127) / 128, tiles_n = (N + 127) / 128;
     const int grid = static_cast<int>(align_up(static_cast<size_t>(E) * tiles_m * tiles_n, 8));
-    hipEvent_t t0, t1;
     prof_kernel_events(stage, &t0, &t1);
     hipExtLaunchKernelGGL(kern, dim3(grid), dim3(256), kLds, st, t0, t1, 0, A, B, C, offsets, E, M, N,
                           tiles_m, tiles_n);
@@ -1041,11 +1317,11 @@ moe_status backward_t(const moe_shape &s, int n_chunks, const uint16_t *x, const
     // dW2[e] [h][d] = act(P)^T dye ; dW1[e] [d][h] = xe^T dP, operands as they are
     auto weight_grads = [&]() {
         if (pre != nullptr)      // the forward's own hidden activations, fp16
-            launch_wgrad<true>(reinterpret_cast<const uint16_t *>(hid), w.dye, dW2, offsets, E, h, d,
+            launch_wgrad<true>(reinterpret_cast<const uint16_t *>(hid), w.dye, dW2, offsets, E, h, d, R,
                                kStageBwdWgrad2, st);
         else
-            launch_wgrad<false>(w.Hb, w.dye, dW2, offsets, E, h, d, kStageBwdWgrad2, st);
-        launch_wgrad<false>(xe, w.dP, dW1, offsets, E, d, h, kStageBwdWgrad1, st);
+            launch_wgrad<false>(w.Hb, w.dye, dW2, offsets, E, h, d, R, kStageBwdWgrad2, st);
+        launch_wgrad<false>(xe, w.dP, dW1, offsets, E, d, h, R, kStageBwdWgrad1, st);
     };
     // gate: dz and dx for the tokens [t0, t1)
     auto grad_combine = [&](int t0, int t1, hipStream_t q) {
