@@ -158,7 +158,7 @@ def test_backward_other_activations(act):
         assert rel_rms_err(got[n].reshape(shape), getattr(o, n)) <= TOL, n
 
 
-@pytest.mark.parametrize("d,h,E,T,C", [(128, 256, 8, 600, 400), (512, 1024, 64, 700, 300)],
+@pytest.mark.parametrize("d,h,E,T,C", [(128, 256, 8, 600, 400), (768, 1024, 64, 700, 300)],
                          ids=["small", "weight_gradient_in_256_tiles"])
 def test_backward_with_empty_experts_and_gate_bias(d, h, E, T, C):
     """Two experts take every token, up to their capacity; the others stay empty and get zero
