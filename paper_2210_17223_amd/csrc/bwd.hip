@@ -908,26 +908,31 @@ __global__ __launch_bounds__(256, 1) void wgrad_w4_kernel(
 // differs from the forward's chain, which only the top-k decision needed.  Softmax, dz with
 // lane = expert, and finally, lane = column again,
 // dx[t, i] = sum of the token's kept dxe rows + sum_e dz[e] Wg[i, e].
-// STAGED: the gate matrix (EP x d floats, at most 64 KiB) is copied to LDS once per block of
+// MODE 1: the gate matrix (EP x d floats, at most 64 KiB) is copied to LDS once per block of
 // 16 wavefronts (16 tokens) and read from there -- a wavefront that reads the matrix twice
 // per token from the caches moves 8 EP d bytes per token through the L1, which is what
 // bounded the kernel.  (Still one token per wavefront and four wavefronts per SIMD: the
 // token's own chain of loads, butterflies and stores is covered by the other wavefronts.)
-template <int EP, bool STAGED>
-__global__ __launch_bounds__(STAGED ? 1024 : 256) void gate_bwd_kernel(
+// MODE 2: a larger matrix goes through LDS in chunks of 64 KiB of its columns, once for the
+// logits and once more for dx; every wavefront of the block walks all chunks (those without a
+// token only stage and wait).
+template <int EP, int MODE>
+__global__ __launch_bounds__(MODE != 0 ? 1024 : 256) void gate_bwd_kernel(
     const uint16_t *__restrict__ x, const float *__restrict__ Wgp, const float *__restrict__ bias,
     int bias_stride, const int32_t *__restrict__ expert_idx, const int32_t *__restrict__ slot_of,
     const float *__restrict__ dgate, const float *__restrict__ dxe, float *__restrict__ dz,
     float *__restrict__ dx, int t0, int T, int d, int dP, int E, int k, int max_rows)
-{   // tokens [t0, T)
-    constexpr int NW = STAGED ? 16 : 4;                              // wavefronts per block
+{   // tokens [t0, T).  MODE 0: the matrix from the caches; 1: staged whole in LDS; 2: staged in
+    // chunks of DC columns, once for the logits and once for dx
+    constexpr int NW = MODE != 0 ? 16 : 4;                           // wavefronts per block
+    constexpr int DC = 16384 / EP >= 256 ? 16384 / EP : 256;         // columns per 64 KiB chunk (MODE 2)
     __shared__ float dzs[NW][kWave];
-    extern __shared__ __attribute__((aligned(16))) float wlds[];     // STAGED: [EP][d]
+    extern __shared__ __attribute__((aligned(16))) float wlds[];     // MODE 1: [EP][d]; 2: [EP][DC]
     const int lane = lane_id();
     const int w = threadIdx.x / kWave;
     const float *Wsrc = Wgp;
     int wpitch = dP;
-    if constexpr (STAGED) {
+    if constexpr (MODE == 1) {
         const int rv = d / 4;                                        // 16-byte vectors per row
         for (int v = threadIdx.x; v < EP * rv; v += NW * kWave) {
             const int e = v / rv, i = (v % rv) * 4;
@@ -939,23 +944,46 @@ __global__ __launch_bounds__(STAGED ? 1024 : 256) void gate_bwd_kernel(
         wpitch = d;
     }
     const int t = t0 + blockIdx.x * NW + w;
-    if (t >= T) return;
-    const uint16_t *xrow = x + static_cast<size_t>(t) * d;
+    const bool valid = t < T;
+    if (MODE != 2 && !valid) return;
+    // columns [c0, c0 + DC) of the packed matrix (zero padded up to dP) into LDS, all wavefronts
+    auto stage_chunk = [&](int c0) {
+        __syncthreads();
+        constexpr int rv = DC / 4;
+        for (int v = threadIdx.x; v < EP * rv; v += NW * kWave) {
+            const int e = v / rv, i = (v % rv) * 4;
+            float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c0 + i < dP) q = *reinterpret_cast<const float4 *>(Wgp + static_cast<size_t>(e) * dP + c0 + i);
+            *reinterpret_cast<float4 *>(wlds + e * DC + i) = q;
+        }
+        __syncthreads();
+    };
+    const uint16_t *xrow = x + static_cast<size_t>(valid ? t : 0) * d;
     float acc[EP];
 #pragma unroll
     for (int e = 0; e < EP; ++e) acc[e] = 0.0f;
-    for (int i = lane * 4; i < d; i += kWave * 4) {
+    auto logits_part = [&](const float *wbase, int pitch, int i, int iw) {    // columns i .. i + 3 (iw: in wbase)
         const u32x2 xq = *reinterpret_cast<const u32x2 *>(xrow + i);
         const float x0 = __uint_as_float(xq[0] << 16), x1 = __uint_as_float(xq[0] & 0xFFFF0000u);
         const float x2 = __uint_as_float(xq[1] << 16), x3 = __uint_as_float(xq[1] & 0xFFFF0000u);
 #pragma unroll
         for (int e = 0; e < EP; ++e) {
-            const float4 wv = *reinterpret_cast<const float4 *>(Wsrc + static_cast<size_t>(e) * wpitch + i);
+            const float4 wv = *reinterpret_cast<const float4 *>(wbase + static_cast<size_t>(e) * pitch + iw);
             acc[e] = __builtin_fmaf(x0, wv.x, acc[e]);
             acc[e] = __builtin_fmaf(x1, wv.y, acc[e]);
             acc[e] = __builtin_fmaf(x2, wv.z, acc[e]);
             acc[e] = __builtin_fmaf(x3, wv.w, acc[e]);
         }
+    };
+    if constexpr (MODE == 2) {
+        for (int c0 = 0; c0 < d; c0 += DC) {
+            stage_chunk(c0);
+            if (valid)
+                for (int il = lane * 4; il < DC && c0 + il < d; il += kWave * 4)
+                    logits_part(wlds, DC, c0 + il, il);
+        }
+    } else {
+        for (int i = lane * 4; i < d; i += kWave * 4) logits_part(Wsrc, wpitch, i, i);
     }
     float z = 0.0f;
 #pragma unroll
@@ -967,7 +995,8 @@ __global__ __launch_bounds__(STAGED ? 1024 : 256) void gate_bwd_kernel(
     }
     const int e = lane;
     const bool live = e < E;
-    if (bias != nullptr && live) z += bias[static_cast<size_t>(t) * bias_stride + e];
+    const int tt = valid ? t : 0;
+    if (bias != nullptr && live) z += bias[static_cast<size_t>(tt) * bias_stride + e];
     float zmax = live ? z : -3.0e38f;
 #pragma unroll
     for (int m = kWave / 2; m > 0; m >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, m));
@@ -979,18 +1008,18 @@ __global__ __launch_bounds__(STAGED ? 1024 : 256) void gate_bwd_kernel(
     float dg = 0.0f;
     if (live)
         for (int j = 0; j < k; ++j)
-            if (expert_idx[static_cast<size_t>(t) * k + j] == e) dg = dgate[static_cast<size_t>(t) * k + j];
+            if (expert_idx[static_cast<size_t>(tt) * k + j] == e) dg = dgate[static_cast<size_t>(tt) * k + j];
     float s = p * dg;
 #pragma unroll
     for (int m = kWave / 2; m > 0; m >>= 1) s += __shfl_xor(s, m);
     const float dze = p * (dg - s);
-    if (live) dz[static_cast<size_t>(t) * E + e] = dze;
+    if (live && valid) dz[static_cast<size_t>(t) * E + e] = dze;
     dzs[w][lane] = live ? dze : 0.0f;
     __builtin_amdgcn_wave_barrier();
     float dzr[EP];
 #pragma unroll
     for (int ee = 0; ee < EP; ++ee) dzr[ee] = dzs[w][ee];
-    for (int i = lane * 4; i < d; i += kWave * 4) {
+    auto dx_part = [&](const float *wbase, int pitch, int i, int iw) {
         float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int j = 0; j < k; ++j) {
             const int slot = slot_of[static_cast<size_t>(t) * k + j];
@@ -1001,13 +1030,23 @@ __global__ __launch_bounds__(STAGED ? 1024 : 256) void gate_bwd_kernel(
         }
 #pragma unroll
         for (int ee = 0; ee < EP; ++ee) {
-            const float4 wv = *reinterpret_cast<const float4 *>(Wsrc + static_cast<size_t>(ee) * wpitch + i);
+            const float4 wv = *reinterpret_cast<const float4 *>(wbase + static_cast<size_t>(ee) * pitch + iw);
             o.x = __builtin_fmaf(dzr[ee], wv.x, o.x);
             o.y = __builtin_fmaf(dzr[ee], wv.y, o.y);
             o.z = __builtin_fmaf(dzr[ee], wv.z, o.z);
             o.w = __builtin_fmaf(dzr[ee], wv.w, o.w);
         }
         *reinterpret_cast<float4 *>(dx + static_cast<size_t>(t) * d + i) = o;
+    };
+    if constexpr (MODE == 2) {
+        for (int c0 = 0; c0 < d; c0 += DC) {
+            stage_chunk(c0);
+            if (valid)
+                for (int il = lane * 4; il < DC && c0 + il < d; il += kWave * 4)
+                    dx_part(wlds, DC, c0 + il, il);
+        }
+    } else {
+        for (int i = lane * 4; i < d; i += kWave * 4) dx_part(Wsrc, wpitch, i, i);
     }
 }
 
@@ -1331,14 +1370,22 @@ moe_status backward_t(const moe_shape &s, int n_chunks, const uint16_t *x, const
     if (EP == EP_) {                                                                              \
         const size_t wbytes = static_cast<size_t>(EP_) * d * sizeof(float);                       \
         if (wbytes <= 64 * 1024 && T >= 16 * 256) {                                               \
-            auto kern = gate_bwd_kernel<EP_, true>;                                               \
+            auto kern = gate_bwd_kernel<EP_, 1>;                                                  \
             static PerDeviceOnce once;                                                            \
             once.raise_lds(reinterpret_cast<const void *>(kern), 64 * 1024);                      \
             hipLaunchKernelGGL(kern, dim3(ceil_div(n, 16)), dim3(1024), wbytes, q, x, Wgp, bias,  \
                                bias_stride, expert_idx, slot_of, dgate, w.dxe, w.dz, dx, t0, t1,  \
                                d, dPad, E, k, R);                                                 \
+        } else if (wbytes > 64 * 1024 && T >= 16 * 256) {                                         \
+            /* a matrix too large for LDS: 64 KiB chunks of its columns, staged per 16 tokens */  \
+            auto kern = gate_bwd_kernel<EP_, 2>;                                                  \
+            static PerDeviceOnce once;                                                            \
+            once.raise_lds(reinterpret_cast<const void *>(kern), 64 * 1024);                      \
+            hipLaunchKernelGGL(kern, dim3(ceil_div(n, 16)), dim3(1024), 64 * 1024, q, x, Wgp,     \
+                               bias, bias_stride, expert_idx, slot_of, dgate, w.dxe, w.dz, dx,    \
+                               t0, t1, d, dPad, E, k, R);                                         \
         } else {                                                                                  \
-            hipLaunchKernelGGL((gate_bwd_kernel<EP_, false>), dim3(ceil_div(n, 4)), dim3(256), 0, \
+            hipLaunchKernelGGL((gate_bwd_kernel<EP_, 0>), dim3(ceil_div(n, 4)), dim3(256), 0,     \
                                q, x, Wgp, bias, bias_stride, expert_idx, slot_of, dgate, w.dxe,   \
                                w.dz, dx, t0, t1, d, dPad, E, k, R);                               \
         }                                                                                         \
