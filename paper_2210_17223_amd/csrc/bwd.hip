@@ -882,23 +882,37 @@ __global__ __launch_bounds__(256, 1) void wgrad_w4_kernel(
     }
 
     // acc[i][j][4*g + c]: column n0 + (wn*TN + i)*32 + 8*g + 4*(lane/32) + c,
-    //                     row m0 + (wm*TM + j)*32 + lane%32
+    //                     row m0 + (wm*TM + j)*32 + lane%32.
+    // The tile leaves through LDS, 32 columns of the wavefront's 128 x 128 at a time (a patch of
+    // 128 rows, pitch 144 bytes, per wavefront), as whole 128-byte lines, 16 bytes per lane:
+    // stores straight from the registers would put 32 bytes into each of 32 lines per instruction.
     float *Ce = C + static_cast<size_t>(expert) * M * N;
     const int fr = lane & 31;
+    constexpr int PITCH = 144;
+    char *patch = reinterpret_cast<char *>(smem) + wave * (TM * 32) * PITCH;
 #pragma unroll
-    for (int i = 0; i < TN; ++i)
+    for (int i = 0; i < TN; ++i) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const int n = n0 + (wn * TN + i) * 32 + 8 * g + 4 * (lane >> 5);
 #pragma unroll
-            for (int j = 0; j < TM; ++j) {
-                const int m = m0 + (wm * TM + j) * 32 + fr;
-                *reinterpret_cast<float4 *>(Ce + static_cast<size_t>(m) * N + n) =
+            for (int j = 0; j < TM; ++j)
+                *reinterpret_cast<float4 *>(patch + (j * 32 + fr) * PITCH + (8 * g + 4 * (lane >> 5)) * 4) =
                     make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
                                 acc[i][j][4 * g + 3]);
-            }
             MOE_SB();      // a few accumulator registers at a time leave the AGPRs
         }
+        MOE_LGKM0();
+        __builtin_amdgcn_wave_barrier();
+        const int n = n0 + (wn * TN + i) * 32 + (lane & 7) * 4;
+#pragma unroll 8
+        for (int it = 0; it < TM * 4; ++it) {
+            const int rr = it * 8 + (lane >> 3);
+            const float4 q = *reinterpret_cast<const float4 *>(patch + rr * PITCH + (lane & 7) * 16);
+            *reinterpret_cast<float4 *>(Ce + static_cast<size_t>(m0 + wm * TM * 32 + rr) * N + n) = q;
+        }
+        MOE_LGKM0();
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 // ---------------------------------------------------------------- gate backward
